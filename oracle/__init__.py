@@ -1,0 +1,127 @@
+"""CPU oracle for ``C = act(alpha * A @ B + bias)`` -- TEST INFRASTRUCTURE ONLY.
+
+A thin ctypes loader around ``gemm_epilogue_oracle.c`` (plain C, fp64
+accumulation, OpenMP over rows).  Only the tests, the smoke check and the CPU
+baseline leg of the benchmark may import this package; the GPU library never
+does, and the two share no code.
+
+The operator follows the paper's plain row-major matmul definition (appendix
+"Comparison of CuTe and CUDA Representations for Square GEMM", Fig. simp_cuda)
+with the fused bias/scale/activation writeback of the Level-2 optimisation
+prompt ("Fusion").
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gemm_epilogue_oracle.c")
+_LIB = os.path.join(_HERE, "libgemm_epilogue_oracle.so")
+
+ACT = {"none": 0, "relu": 1, "gelu_tanh": 2}
+_KIND = {np.dtype(np.float64): 0, np.dtype(np.float32): 1, np.dtype(np.uint16): 2}
+
+_lib = None
+
+
+def compile_source(src: str, out: str) -> str:
+    """gcc line for the oracle: no fast-math, no contraction, OpenMP."""
+    cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+           "-shared", "-fPIC", "-o", out, src, "-lm"]
+    subprocess.run(cmd, check=True)
+    return out
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle if it is missing or older than its source. Returns the .so path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        compile_source(_SRC, _LIB)
+    return _LIB
+
+
+def use_library(path: str | None) -> None:
+    """Point the loader at another build of the oracle (the mutation tests plant
+    mistakes in copies of the source); ``None`` returns to the real one."""
+    global _lib
+    _lib = None if path is None else _bind(ctypes.CDLL(path))
+
+
+def _bind(lib):
+    lib.oracle_gemm_epilogue.restype = ctypes.c_int
+    lib.oracle_gemm_epilogue.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p, ctypes.c_long,
+        ctypes.c_int, ctypes.c_void_p, ctypes.c_double, ctypes.c_int,
+        ctypes.c_void_p, ctypes.c_long, ctypes.c_int]
+    lib.oracle_num_threads.restype = ctypes.c_int
+    return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = _bind(ctypes.CDLL(build()))
+    return _lib
+
+
+def num_threads() -> int:
+    """OpenMP threads the oracle will use."""
+    return int(_load().oracle_num_threads())
+
+
+def gemm_epilogue(A, B, bias=None, alpha=1.0, act="none", *, M=None, N=None, K=None,
+                  lda=None, ldb=None, ldc=None, batch=1):
+    """Reference result as an fp64 array.
+
+    ``A`` and ``B`` are numpy arrays of one dtype: float64, float32, or uint16
+    holding bf16 bit patterns.  With 2-D (or 3-D batched) arrays the shapes and
+    packed leading dimensions are taken from them.  With 1-D buffers the caller
+    gives ``M, N, K, lda, ldb, ldc, batch`` and gets back a flat buffer of
+    ``batch*M*ldc`` doubles whose padding (columns ``>= N``) is NaN so that a
+    read of it cannot go unnoticed.
+
+    ``bias`` (length N or None) and ``alpha`` are widened exactly to fp64.
+    """
+    lib = _load()
+    A = np.ascontiguousarray(A)
+    B = np.ascontiguousarray(B)
+    if A.dtype != B.dtype or A.dtype not in _KIND:
+        raise TypeError("A and B must share a dtype among float64, float32, uint16(bf16 bits)")
+    flat = A.ndim == 1
+    if not flat:
+        if A.ndim == 2:
+            A3, B3 = A[None], B[None]
+        else:
+            A3, B3 = A, B
+        batch, M, K = A3.shape
+        b2, K2, N = B3.shape
+        if b2 != batch or K2 != K:
+            raise ValueError("shape mismatch")
+        lda, ldb, ldc = K, N, N
+    else:
+        if None in (M, N, K, lda, ldb, ldc):
+            raise ValueError("flat buffers need M, N, K, lda, ldb, ldc")
+        if A.size < batch * M * lda - (lda - K) or B.size < batch * K * ldb - (ldb - N):
+            raise ValueError("buffer too small")
+    if bias is not None:
+        bias64 = np.ascontiguousarray(np.asarray(bias), dtype=np.float64)
+        if bias64.shape != (N,):
+            raise ValueError("bias must have length N")
+        bias_p = bias64.ctypes.data_as(ctypes.c_void_p)
+    else:
+        bias_p = None
+    C = np.full(batch * M * ldc, np.nan, dtype=np.float64)
+    rc = lib.oracle_gemm_epilogue(
+        int(M), int(N), int(K), A.ctypes.data_as(ctypes.c_void_p), int(lda),
+        B.ctypes.data_as(ctypes.c_void_p), int(ldb), _KIND[A.dtype], bias_p,
+        float(alpha), ACT[act], C.ctypes.data_as(ctypes.c_void_p), int(ldc), int(batch))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    if flat:
+        return C
+    C = C.reshape(batch, M, N)
+    return C[0] if np.ndim(A) == 2 else C

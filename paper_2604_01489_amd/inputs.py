@@ -1,0 +1,173 @@
+"""Seeded synthetic inputs for the GEMM + epilogue workloads.
+
+This module is the only code the GPU library's tests and the CPU oracle's tests
+have in common.  It draws numbers and rounds them; it contains none of the
+operator's arithmetic.
+
+Generator (counter based, so any element can be regenerated on its own):
+    key(seed, stream) = mix64(seed * 0xD1342543DE82EF95 + stream * 0x9E3779B97F4A7C15 + 1)
+    word(i)           = mix64(key + (i + 1) * 0x9E3779B97F4A7C15)        (mod 2^64)
+    mix64             = the splitmix64 output function (Steele, Lea, Flood 2014)
+    u(i)              = (word(i) >> 11) * 2^-53                          in [0, 1)
+    uniform(a, b)     = a + (b - a) * u(i), rounded once to fp32
+    normal            = sqrt(-2 ln(1 - u(2i))) * cos(2 pi u(2i+1)), fp64, rounded once to fp32
+Streams: 0 = A, 1 = B, 2 = bias.  Elements are numbered in row-major order of
+the logical (batch, rows, cols) tensor, so a leading dimension larger than the
+row length does not change the values.
+
+The workloads below are the five synthetic stand-ins for the matmul and fused
+matmul shapes the paper evaluates on (its benchmark suite is not reproduced).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+_GOLD = np.uint64(0x9E3779B97F4A7C15)
+_SEEDMUL = np.uint64(0xD1342543DE82EF95)
+STREAM_A, STREAM_B, STREAM_BIAS = 0, 1, 2
+
+
+def _mix64(z: np.ndarray) -> np.ndarray:
+    z = z.copy()
+    z ^= z >> np.uint64(30)
+    z *= np.uint64(0xBF58476D1CE4E5B9)
+    z ^= z >> np.uint64(27)
+    z *= np.uint64(0x94D049BB133111EB)
+    z ^= z >> np.uint64(31)
+    return z
+
+
+def _key(seed: int, stream: int) -> np.uint64:
+    with np.errstate(over="ignore"):
+        k = np.array([np.uint64(seed) * _SEEDMUL + np.uint64(stream) * _GOLD + np.uint64(1)],
+                     dtype=np.uint64)
+        return _mix64(k)[0]
+
+
+def _unit(seed: int, stream: int, start: int, count: int) -> np.ndarray:
+    """u(i) for i in [start, start+count) as fp64 in [0, 1)."""
+    with np.errstate(over="ignore"):
+        i = np.arange(start + 1, start + count + 1, dtype=np.uint64)
+        w = _mix64(_key(seed, stream) + i * _GOLD)
+    return (w >> np.uint64(11)).astype(np.float64) * (2.0 ** -53)
+
+
+_CHUNK = 1 << 22
+
+
+def uniform(seed: int, stream: int, n: int, lo: float, hi: float, start: int = 0) -> np.ndarray:
+    """n fp32 samples of U(lo, hi): elements start .. start+n-1 of the stream."""
+    out = np.empty(n, dtype=np.float32)
+    for s in range(0, n, _CHUNK):
+        c = min(_CHUNK, n - s)
+        out[s:s + c] = (lo + (hi - lo) * _unit(seed, stream, start + s, c)).astype(np.float32)
+    return out
+
+
+def normal(seed: int, stream: int, n: int, scale: float = 1.0, start: int = 0) -> np.ndarray:
+    """n fp32 samples of scale * N(0, 1) (Box-Muller, cosine branch)."""
+    out = np.empty(n, dtype=np.float32)
+    for s in range(0, n, _CHUNK):
+        c = min(_CHUNK, n - s)
+        u = _unit(seed, stream, 2 * (start + s), 2 * c)
+        r = np.sqrt(-2.0 * np.log1p(-u[0::2]))
+        out[s:s + c] = (scale * r * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
+    return out
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to bf16 (nearest, ties to even); returns the 16-bit patterns.
+
+    Inputs are finite by construction; NaN handling is not needed.
+    """
+    b = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = b + (np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1)))
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    """Widen bf16 bit patterns to fp32 (exact)."""
+    return (np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+@dataclass(frozen=True)
+class Workload:
+    """One synthetic configuration: shapes, distributions and epilogue."""
+    name: str
+    dtype: str            # "bf16" or "f32": element type of A and B
+    M: int
+    N: int
+    K: int
+    batch: int
+    seed: int
+    dist: str             # "uniform" (U(-1,1)) or "normal"
+    scale: float          # multiplies normal samples (ignored for uniform)
+    alpha: float
+    bias: tuple | None    # (lo, hi) of the uniform bias, "zero", or None
+    act: str
+
+    @property
+    def flops(self) -> float:
+        return 2.0 * self.M * self.N * self.K * self.batch
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        """Read A, B and bias once, write C once."""
+        e = 2 if self.dtype == "bf16" else 4
+        nb = 0 if self.bias is None else 4 * self.N
+        return float(self.batch * (self.M * self.K + self.K * self.N) * e
+                     + self.batch * self.M * self.N * 4 + nb)
+
+
+WORKLOADS = {
+    "c1_f32_256": Workload("c1_f32_256", "f32", 256, 256, 256, 1, 0, "uniform", 1.0, 1.0, None, "none"),
+    "c2_bf16_4096": Workload("c2_bf16_4096", "bf16", 4096, 4096, 4096, 1, 1, "normal",
+                             4096 ** -0.5, 1.0, None, "none"),
+    "c3_bf16_8192_bias_gelu": Workload("c3_bf16_8192_bias_gelu", "bf16", 8192, 8192, 8192, 1, 2,
+                                       "normal", 8192 ** -0.5, 0.5, (-0.1, 0.1), "gelu_tanh"),
+    "c4_bf16_batched_512x512x64": Workload("c4_bf16_batched_512x512x64", "bf16", 512, 512, 64, 256, 3,
+                                           "normal", 1.0, 1.0, (-1.0, 1.0), "relu"),
+    "c5_bf16_splitk_1024x1024x65536": Workload("c5_bf16_splitk_1024x1024x65536", "bf16", 1024, 1024,
+                                               65536, 1, 4, "uniform", 1.0, 1.0 / 256.0, "zero", "none"),
+}
+
+
+def _draw(w: Workload, stream: int, n: int, start: int = 0) -> np.ndarray:
+    if w.dist == "uniform":
+        return uniform(w.seed, stream, n, -1.0, 1.0, start)
+    return normal(w.seed, stream, n, w.scale, start)
+
+
+def make_bias(w: Workload):
+    if w.bias is None:
+        return None
+    if w.bias == "zero":
+        return np.zeros(w.N, dtype=np.float32)
+    return uniform(w.seed, STREAM_BIAS, w.N, w.bias[0], w.bias[1])
+
+
+def make_operand(w: Workload, which: str, row_start: int = 0, rows: int | None = None,
+                 batch_index: int | None = None) -> np.ndarray:
+    """Rows [row_start, row_start+rows) of A ("A": M x K) or B ("B": K x N).
+
+    With ``batch_index`` None all batches are produced (shape (batch, rows, cols));
+    otherwise only that batch (shape (rows, cols)).  bf16 workloads return uint16
+    bit patterns (the fp32 sample rounded to nearest even), fp32 workloads float32.
+    """
+    nrows, ncols = (w.M, w.K) if which == "A" else (w.K, w.N)
+    stream = STREAM_A if which == "A" else STREAM_B
+    rows = nrows - row_start if rows is None else rows
+    batches = range(w.batch) if batch_index is None else [batch_index]
+    parts = []
+    for b in batches:
+        start = (b * nrows + row_start) * ncols
+        x = _draw(w, stream, rows * ncols, start).reshape(rows, ncols)
+        parts.append(to_bf16_bits(x) if w.dtype == "bf16" else x)
+    return parts[0] if batch_index is not None else np.stack(parts)
+
+
+def make_inputs(w: Workload):
+    """(A, B, bias) for the whole workload; A, B carry a leading batch axis."""
+    return make_operand(w, "A"), make_operand(w, "B"), make_bias(w)
