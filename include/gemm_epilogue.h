@@ -1,0 +1,147 @@
+/*
+ * gemm_epilogue -- fused dense matrix multiply for AMD MI355X (CDNA4, gfx950).
+ *
+ *     C[b][m,n] = act( alpha * sum_{k<K} A[b][m,k] * B[b][k,n] + bias[n] )
+ *
+ * The contraction is the plain row-major matmul of the paper's naive baseline
+ * (appendix "Comparison of CuTe and CUDA Representations for Square GEMM",
+ * Fig. simp_cuda): A is [M,K] row-major, B is [K,N] row-major, C is [M,N]
+ * row-major, the operand convention of the optimisation prompt's GEMM section.
+ * The writeback adds no previous C (beta = 0, as in the epilogue of the initial
+ * CuTe kernel, Fig. simple_cute) and applies scale, bias and activation in
+ * registers before the single store (Level-2 optimisation prompt, "Fusion":
+ * bias/add/scale/activation fused into the producer writeback).  Operand
+ * precision is never lowered (Experiments, "Manual Correctness Audit"): bf16
+ * operands are multiplied exactly and accumulated in fp32; fp32 operands use
+ * true fp32 matrix instructions.
+ *
+ * Layout.  All matrices are row-major with a leading dimension in ELEMENTS:
+ *     A[m,k] = A[m*lda + k],  B[k,n] = B[k*ldb + n],  C[m,n] = C[m*ldc + n].
+ * Batch b starts at A + b*M*lda, B + b*K*ldb, C + b*M*ldc (packed strides);
+ * bias (length N) is shared by every batch.
+ *
+ * Ownership.  Every pointer is a DEVICE pointer owned by the caller and must
+ * stay valid until the work enqueued on `stream` has finished.  The calls
+ * enqueue kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without synchronising.  C must not overlap A, B
+ * or bias.  bf16 values are passed as their 16-bit patterns so this header
+ * needs no HIP types.
+ *
+ * Errors.  Every call validates its arguments first and returns a status; on
+ * any status other than GE_OK nothing was enqueued and C is untouched.
+ *
+ * Determinism.  For a fixed library build, device and argument list the result
+ * is bitwise repeatable, including the split-K path (partials are summed in
+ * slice order by a second kernel; no atomics).
+ */
+#ifndef GEMM_EPILOGUE_H
+#define GEMM_EPILOGUE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GE_ACT_NONE = 0,      /* v                                                      */
+    GE_ACT_RELU = 1,      /* v > 0 ? v : 0                                          */
+    GE_ACT_GELU_TANH = 2  /* 0.5 v (1 + tanh( sqrt(2/pi) (v + 0.044715 v^3) ))      */
+} ge_act_t;
+
+typedef enum {
+    GE_OK = 0,
+    GE_ERR_NULL = 1,       /* A, B or C is NULL                                     */
+    GE_ERR_SHAPE = 2,      /* M, N, K or batch < 1, or a product overflows          */
+    GE_ERR_LD = 3,         /* lda < K, ldb < N or ldc < N                           */
+    GE_ERR_ACT = 4,        /* act is not a ge_act_t value                           */
+    GE_ERR_ALIGN = 5,      /* a pointer is not aligned to its element size          */
+    GE_ERR_WORKSPACE = 6,  /* split-K workspace missing, too small or not allocatable */
+    GE_ERR_LAUNCH = 7,     /* the HIP runtime refused a launch                      */
+    GE_ERR_CONFIG = 8      /* unknown plan / forced configuration does not fit      */
+} ge_status_t;
+
+/* How the work is decomposed (the paper's design choice "work decomposition and
+ * tiling across thread blocks and warps", Introduction; split-K and the skinny
+ * rule are items 7 and 9 of the optimisation prompt's GEMM list).            */
+typedef enum {
+    GE_PLAN_AUTO = 0,      /* choose from the shape                                 */
+    GE_PLAN_DIRECT = 1,    /* one pass, epilogue in the GEMM kernel                 */
+    GE_PLAN_SPLITK = 2     /* K sliced over blocks, partials reduced in slice order */
+} ge_plan_t;
+
+/*
+ * bf16 operands, fp32 accumulation, fp32 output.
+ *   M, N, K >= 1      problem size per batch
+ *   A, lda            device, bf16 bits, lda >= K
+ *   B, ldb            device, bf16 bits, ldb >= N
+ *   bias              device, fp32[N], or NULL for no bias
+ *   alpha             scale applied to the accumulated product
+ *   act               activation
+ *   C, ldc            device, fp32, ldc >= N; only C[m, 0..N) is written
+ *   batch >= 1        number of independent problems (packed strides)
+ *   stream            hipStream_t
+ * Fast kernels (direct-to-LDS loads) need A and B 16-byte aligned, lda, ldb, N
+ * and K multiples of 8; any other legal argument list takes a guarded generic
+ * kernel with the same result contract (Debugging guide, "gate by alignment ...
+ * correct fallback").  Large-K small-MN shapes use split-K with a workspace the
+ * library owns (grown with hipMalloc when a larger one is first needed, freed
+ * by ge_release_workspace or at process exit); calls that use it must be
+ * ordered on one stream at a time.
+ */
+ge_status_t gemm_epilogue_bf16(int M, int N, int K,
+                               const uint16_t *A, int lda,
+                               const uint16_t *B, int ldb,
+                               const float *bias, float alpha, ge_act_t act,
+                               float *C, int ldc, int batch, void *stream);
+
+/* fp32 operands, fp32 matrix instructions, fp32 output.  Same contract. */
+ge_status_t gemm_epilogue_f32(int M, int N, int K,
+                              const float *A, int lda,
+                              const float *B, int ldb,
+                              const float *bias, float alpha, ge_act_t act,
+                              float *C, int ldc, int batch, void *stream);
+
+/*
+ * Same operator with explicit control:
+ *   plan, split_k     GE_PLAN_AUTO picks both; GE_PLAN_SPLITK uses `split_k`
+ *                     slices (>= 2, or 0 to let the library choose)
+ *   workspace         device buffer for split-K partials, 256-byte aligned, of
+ *                     at least gemm_epilogue_workspace_bytes(...) bytes; NULL
+ *                     selects the library-owned buffer
+ * Never allocates when `workspace` is given.
+ */
+ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K,
+                                  const uint16_t *A, int lda,
+                                  const uint16_t *B, int ldb,
+                                  const float *bias, float alpha, ge_act_t act,
+                                  float *C, int ldc, int batch,
+                                  ge_plan_t plan, int split_k,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/* Bytes of split-K workspace the bf16 call needs for this shape with `plan` and
+ * `split_k` as above (0 when the chosen plan is direct).  Host only. */
+size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch,
+                                     ge_plan_t plan, int split_k);
+
+/* Number of K slices GE_PLAN_AUTO would use for the bf16 call (1 = direct).
+ * Host only; needs no device. */
+int gemm_epilogue_auto_split_k(int M, int N, int K, int batch);
+
+/* Frees the library-owned split-K workspace of the current device (after the
+ * caller has synchronised the streams that used it). */
+ge_status_t ge_release_workspace(void);
+
+/* Static, never NULL. */
+const char *ge_status_string(ge_status_t status);
+
+/* Name of the kernel configuration the last successful call on this thread
+ * launched ("bf16_256x256x64_w8", "f32_128x128x16", ...); for reports. */
+const char *ge_last_config(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GEMM_EPILOGUE_H */

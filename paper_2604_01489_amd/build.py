@@ -1,0 +1,42 @@
+"""Build step: compile the HIP sources into ``libgemm_epilogue.so`` for gfx950.
+
+``python -m paper_2604_01489_amd.build`` or ``build_library()``.  hipcc cross
+compiles without a GPU.  The library is kept in-tree, next to this file.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libgemm_epilogue.so")
+SOURCES = ["gemm_epilogue_api.hip"]
+# packed fp32 instructions are kept off: some of their forms have misbehaved on this hardware
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    cmd = ["hipcc", *FLAGS, *extra_flags, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        sys.stderr.write(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed")
+    return LIB
+
+
+def library_is_current() -> bool:
+    if not os.path.exists(LIB):
+        return False
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "gemm_epilogue.h"))
+    return all(os.path.getmtime(d) <= t for d in deps)
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

@@ -1,0 +1,361 @@
+// C-ABI of the gfx950 fused GEMM library: argument validation, plan selection
+// (direct / batched / split-K, tile shape) and kernel launches.  See
+// include/gemm_epilogue.h for the contract of every entry point.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/gemm_epilogue.h"
+#include "gemm_bf16_fast.h"
+#include "gemm_generic.h"
+
+namespace {
+
+using ge::GemmParams;
+
+thread_local const char *g_last_config = "none";
+
+constexpr int kNumCU = 256;          // MI355X
+constexpr int kMaxDevices = 64;
+
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+Workspace g_ws[kMaxDevices];
+std::mutex g_ws_mutex;
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// ---- shape -> plan -------------------------------------------------------
+enum TileKind { TILE_256 = 0, TILE_128 = 1, TILE_GENERIC = 2 };
+
+struct Plan {
+    TileKind tile;
+    int bm, bn, bk;
+    int tilesM, tilesN;
+    int splitK;      // >= 1
+    int kPerSlice;
+    bool edge;
+};
+
+bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
+{
+    if ((((uintptr_t)A) | ((uintptr_t)B)) & 15u) return false;
+    if ((lda | ldb | N | K) & 7) return false;
+    // per-lane byte offsets inside one tile panel must stay below 2^31
+    if ((long long)lda * 2 * 256 + 256 >= (1ll << 31)) return false;
+    if ((long long)ldb * 2 * 64 + 1024 >= (1ll << 31)) return false;
+    return true;
+}
+
+// K slices so that a launch with few output tiles still covers the chip.
+int choose_split(long long tiles, int K, int bk)
+{
+    if (tiles * 2 > kNumCU || K < 8 * bk * 2) return 1;
+    long long s = kNumCU / tiles;
+    const long long maxS = K / (8 * bk);       // at least 8 K tiles per slice
+    if (s > maxS) s = maxS;
+    if (s > 64) s = 64;
+    return s < 2 ? 1 : (int)s;
+}
+
+void slice_k(int K, int bk, int want, int *splitK, int *kPerSlice)
+{
+    int per = ceil_div(ceil_div(K, want), bk) * bk;
+    if (per < bk) per = bk;
+    *kPerSlice = per;
+    *splitK = ceil_div(K, per);
+}
+
+ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out)
+{
+    Plan pl{};
+    const char *force = std::getenv("GE_FORCE_CONFIG");
+    if (!fast || (force && std::strcmp(force, "generic") == 0)) {
+        pl.tile = TILE_GENERIC; pl.bm = 64; pl.bn = 64; pl.bk = 32;
+    } else {
+        bool big = (M >= 256 && N >= 256);
+        if (force && std::strcmp(force, "256x256") == 0) big = true;
+        if (force && std::strcmp(force, "128x128") == 0) big = false;
+        if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = 64; }
+        else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = 64; }
+    }
+    pl.tilesM = ceil_div(M, pl.bm);
+    pl.tilesN = ceil_div(N, pl.bn);
+    const long long tiles = (long long)pl.tilesM * pl.tilesN * batch;
+    if (tiles > 0x7fffffffll / 64) return GE_ERR_SHAPE;
+    int want = 1;
+    if (plan == GE_PLAN_SPLITK) {
+        want = split_k > 0 ? split_k : choose_split(tiles, K, pl.bk);
+        if (want < 2) want = 2;
+    } else if (plan == GE_PLAN_AUTO) {
+        want = choose_split(tiles, K, pl.bk);
+    } else if (plan != GE_PLAN_DIRECT) {
+        return GE_ERR_CONFIG;
+    }
+    if (split_k < 0) return GE_ERR_CONFIG;
+    slice_k(K, pl.bk, want, &pl.splitK, &pl.kPerSlice);
+    if (pl.splitK == 1) pl.kPerSlice = ceil_div(K, pl.bk) * pl.bk;
+    if (tiles * pl.splitK > 0x7fffffffll) return GE_ERR_SHAPE;
+    pl.edge = (M % pl.bm) || (N % pl.bn) || (K % pl.bk) || (pl.kPerSlice % pl.bk);
+    *out = pl;
+    return GE_OK;
+}
+
+size_t partial_bytes(int M, int N, int batch, int splitK)
+{
+    return splitK <= 1 ? 0 : (size_t)splitK * (size_t)batch * (size_t)M * (size_t)N * sizeof(float);
+}
+
+ge_status_t validate(int M, int N, int K, const void *A, int lda, const void *B, int ldb,
+                     const void *bias, int act, const void *C, int ldc, int batch, size_t elem)
+{
+    if (!A || !B || !C) return GE_ERR_NULL;
+    if (M < 1 || N < 1 || K < 1 || batch < 1) return GE_ERR_SHAPE;
+    if (lda < K || ldb < N || ldc < N) return GE_ERR_LD;
+    if (act != GE_ACT_NONE && act != GE_ACT_RELU && act != GE_ACT_GELU_TANH) return GE_ERR_ACT;
+    if (((uintptr_t)A % elem) || ((uintptr_t)B % elem) || ((uintptr_t)C % 4) || ((uintptr_t)bias % 4))
+        return GE_ERR_ALIGN;
+    // element counts of one operand must fit 63 bits comfortably
+    const long double big = 9.0e18L;
+    if ((long double)batch * M * lda > big || (long double)batch * K * ldb > big ||
+        (long double)batch * M * ldc > big)
+        return GE_ERR_SHAPE;
+    return GE_OK;
+}
+
+GemmParams base_params(int M, int N, int K, const void *A, int lda, const void *B, int ldb,
+                       const float *bias, float alpha, int act, float *C, int ldc, int batch)
+{
+    GemmParams p{};
+    p.A = A; p.B = B; p.bias = bias; p.C = C;
+    p.M = M; p.N = N; p.K = K;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.strideA = (long long)M * lda;
+    p.strideB = (long long)K * ldb;
+    p.strideC = (long long)M * ldc;
+    p.sliceStride = (long long)batch * M * N;
+    p.batch = batch;
+    p.splitK = 1;
+    p.alpha = alpha;
+    p.act = act;
+    return p;
+}
+
+// Tile rows swept together: enough that the ~32 tiles resident on one XCD form
+// a compact block (A panels and B panels both reused from that XCD's L2).
+int choose_group_m(int tilesM, int tilesN)
+{
+    int g = 8;
+    if (tilesN < 4) g = 32 / (tilesN < 1 ? 1 : tilesN);
+    if (g > tilesM) g = tilesM;
+    return g < 1 ? 1 : g;
+}
+
+ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void **out)
+{
+    if (user) {
+        if (user_bytes < need || ((uintptr_t)user & 255u)) return GE_ERR_WORKSPACE;
+        *out = user;
+        return GE_OK;
+    }
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GE_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    Workspace &ws = g_ws[dev];
+    if (ws.bytes < need) {
+        if (ws.ptr) {
+            (void)hipFree(ws.ptr);   // waits for work that may still read it
+            ws.ptr = nullptr;
+            ws.bytes = 0;
+        }
+        void *ptr = nullptr;
+        if (hipMalloc(&ptr, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return GE_ERR_WORKSPACE;
+        }
+        ws.ptr = ptr;
+        ws.bytes = need;
+    }
+    *out = ws.ptr;
+    return GE_OK;
+}
+
+template <int BM, int BN, int WM, int WN, bool EDGE>
+hipError_t launch_fast_sel(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
+{
+    constexpr int threads = WM * WN * 64;
+    if (raw) {
+        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, true, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
+    } else if (act == GE_ACT_RELU) {
+        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_RELU>), grid, dim3(threads), 0, st, p);
+    } else if (act == GE_ACT_GELU_TANH) {
+        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_GELU_TANH>), grid, dim3(threads), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce(const GemmParams &p, const float *W, float *C, int ldc, int act,
+                         const float *bias, float alpha, hipStream_t st)
+{
+    const long long total = (long long)p.batch * p.M * p.N;
+    long long blocks = (total / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
+    hipLaunchKernelGGL(ge::splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       W, p.sliceStride, p.splitK, p.M, p.N, p.batch, bias, alpha, act, C, ldc,
+                       (long long)p.M * ldc);
+    return hipGetLastError();
+}
+
+ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
+                     const float *bias, float alpha, ge_act_t act, float *C, int ldc, int batch,
+                     ge_plan_t plan, int split_k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    ge_status_t st = validate(M, N, K, A, lda, B, ldb, bias, (int)act, C, ldc, batch, 2);
+    if (st != GE_OK) return st;
+    Plan pl;
+    st = make_plan_bf16(M, N, K, batch, fast_path_ok(N, K, A, lda, B, ldb), plan, split_k, &pl);
+    if (st != GE_OK) return st;
+
+    GemmParams p = base_params(M, N, K, A, lda, B, ldb, bias, alpha, (int)act, C, ldc, batch);
+    p.tilesM = pl.tilesM;
+    p.tilesN = pl.tilesN;
+    p.groupM = choose_group_m(pl.tilesM, pl.tilesN);
+    p.splitK = pl.splitK;
+    p.kPerSlice = pl.kPerSlice;
+
+    const bool raw = pl.splitK > 1;
+    void *ws = nullptr;
+    if (raw) {
+        st = acquire_workspace(partial_bytes(M, N, batch, pl.splitK), workspace, workspace_bytes, &ws);
+        if (st != GE_OK) return st;
+        p.C = (float *)ws;
+    }
+    const dim3 grid((unsigned)((long long)pl.tilesM * pl.tilesN * batch * pl.splitK));
+    hipStream_t hs = (hipStream_t)stream;
+    hipError_t err;
+    switch (pl.tile) {
+    case TILE_256:
+        err = pl.edge ? launch_fast_sel<256, 256, 2, 4, true>(p, raw, (int)act, grid, hs)
+                      : launch_fast_sel<256, 256, 2, 4, false>(p, raw, (int)act, grid, hs);
+        g_last_config = raw ? "bf16_256x256x64_w8_splitk" : "bf16_256x256x64_w8";
+        break;
+    case TILE_128:
+        err = pl.edge ? launch_fast_sel<128, 128, 2, 2, true>(p, raw, (int)act, grid, hs)
+                      : launch_fast_sel<128, 128, 2, 2, false>(p, raw, (int)act, grid, hs);
+        g_last_config = raw ? "bf16_128x128x64_w4_splitk" : "bf16_128x128x64_w4";
+        break;
+    default:
+        if (raw) hipLaunchKernelGGL(ge::gemm_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, p);
+        else     hipLaunchKernelGGL(ge::gemm_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, p);
+        err = hipGetLastError();
+        g_last_config = raw ? "bf16_generic_64x64x32_splitk" : "bf16_generic_64x64x32";
+        break;
+    }
+    if (err != hipSuccess) return GE_ERR_LAUNCH;
+    if (raw) {
+        err = launch_reduce(p, (const float *)ws, C, ldc, (int)act, bias, alpha, hs);
+        if (err != hipSuccess) return GE_ERR_LAUNCH;
+    }
+    return GE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ge_status_t gemm_epilogue_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
+                               const float *bias, float alpha, ge_act_t act, float *C, int ldc,
+                               int batch, void *stream)
+{
+    return run_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch, GE_PLAN_AUTO, 0, nullptr, 0, stream);
+}
+
+ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
+                                  const float *bias, float alpha, ge_act_t act, float *C, int ldc,
+                                  int batch, ge_plan_t plan, int split_k, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    return run_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch, plan, split_k, workspace,
+                    workspace_bytes, stream);
+}
+
+ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, const float *B, int ldb,
+                              const float *bias, float alpha, ge_act_t act, float *C, int ldc,
+                              int batch, void *stream)
+{
+    ge_status_t st = validate(M, N, K, A, lda, B, ldb, bias, (int)act, C, ldc, batch, 4);
+    if (st != GE_OK) return st;
+    GemmParams p = base_params(M, N, K, A, lda, B, ldb, bias, alpha, (int)act, C, ldc, batch);
+    p.tilesM = ceil_div(M, 128);
+    p.tilesN = ceil_div(N, 128);
+    p.groupM = choose_group_m(p.tilesM, p.tilesN);
+    p.splitK = 1;
+    p.kPerSlice = ceil_div(K, 16) * 16;
+    const long long blocks = (long long)p.tilesM * p.tilesN * batch;
+    if (blocks > 0x7fffffffll) return GE_ERR_SHAPE;
+    hipLaunchKernelGGL(ge::gemm_f32_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, p);
+    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    g_last_config = "f32_128x128x16_w4";
+    return GE_OK;
+}
+
+size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch, ge_plan_t plan, int split_k)
+{
+    if (M < 1 || N < 1 || K < 1 || batch < 1) return 0;
+    Plan pl;
+    // the tile choice (hence the slice count) depends on whether the fast
+    // kernels apply; report the larger of the two answers
+    size_t need = 0;
+    for (int fast = 0; fast < 2; ++fast) {
+        if (make_plan_bf16(M, N, K, batch, fast != 0, plan, split_k, &pl) != GE_OK) continue;
+        const size_t b = partial_bytes(M, N, batch, pl.splitK);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+int gemm_epilogue_auto_split_k(int M, int N, int K, int batch)
+{
+    if (M < 1 || N < 1 || K < 1 || batch < 1) return 0;
+    Plan pl;
+    if (make_plan_bf16(M, N, K, batch, true, GE_PLAN_AUTO, 0, &pl) != GE_OK) return 0;
+    return pl.splitK;
+}
+
+ge_status_t ge_release_workspace(void)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GE_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_ws[dev].ptr) (void)hipFree(g_ws[dev].ptr);
+    g_ws[dev].ptr = nullptr;
+    g_ws[dev].bytes = 0;
+    return GE_OK;
+}
+
+const char *ge_status_string(ge_status_t status)
+{
+    switch (status) {
+    case GE_OK: return "ok";
+    case GE_ERR_NULL: return "A, B or C is NULL";
+    case GE_ERR_SHAPE: return "M, N, K and batch must be >= 1 and fit the index range";
+    case GE_ERR_LD: return "leading dimension smaller than the row length";
+    case GE_ERR_ACT: return "unknown activation";
+    case GE_ERR_ALIGN: return "pointer not aligned to its element size";
+    case GE_ERR_WORKSPACE: return "split-K workspace missing, too small, misaligned or not allocatable";
+    case GE_ERR_LAUNCH: return "kernel launch failed";
+    case GE_ERR_CONFIG: return "unknown plan or split count";
+    }
+    return "unknown status";
+}
+
+const char *ge_last_config(void) { return g_last_config; }
+
+}  // extern "C"

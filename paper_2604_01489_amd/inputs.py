@@ -20,6 +20,8 @@ matmul shapes the paper evaluates on (its benchmark suite is not reproduced).
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -54,27 +56,41 @@ def _unit(seed: int, stream: int, start: int, count: int) -> np.ndarray:
     return (w >> np.uint64(11)).astype(np.float64) * (2.0 ** -53)
 
 
-_CHUNK = 1 << 22
+_CHUNK = 1 << 20
+_THREADS = max(1, min(16, len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else 4))
+
+
+def _chunked(n: int, fill) -> np.ndarray:
+    """out[s:s+c] = fill(s, c) over chunks; chunks are independent (counter based),
+    so they are spread over a few threads."""
+    out = np.empty(n, dtype=np.float32)
+
+    def work(s):
+        c = min(_CHUNK, n - s)
+        out[s:s + c] = fill(s, c)
+
+    starts = range(0, n, _CHUNK)
+    if n <= _CHUNK or _THREADS == 1:
+        for s in starts:
+            work(s)
+    else:
+        with ThreadPoolExecutor(_THREADS) as pool:
+            list(pool.map(work, starts))
+    return out
 
 
 def uniform(seed: int, stream: int, n: int, lo: float, hi: float, start: int = 0) -> np.ndarray:
     """n fp32 samples of U(lo, hi): elements start .. start+n-1 of the stream."""
-    out = np.empty(n, dtype=np.float32)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
-        out[s:s + c] = (lo + (hi - lo) * _unit(seed, stream, start + s, c)).astype(np.float32)
-    return out
+    return _chunked(n, lambda s, c: (lo + (hi - lo) * _unit(seed, stream, start + s, c)).astype(np.float32))
 
 
 def normal(seed: int, stream: int, n: int, scale: float = 1.0, start: int = 0) -> np.ndarray:
     """n fp32 samples of scale * N(0, 1) (Box-Muller, cosine branch)."""
-    out = np.empty(n, dtype=np.float32)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
+    def fill(s, c):
         u = _unit(seed, stream, 2 * (start + s), 2 * c)
         r = np.sqrt(-2.0 * np.log1p(-u[0::2]))
-        out[s:s + c] = (scale * r * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
-    return out
+        return (scale * r * np.cos(2.0 * np.pi * u[1::2])).astype(np.float32)
+    return _chunked(n, fill)
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:

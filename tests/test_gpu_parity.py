@@ -1,0 +1,132 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on the
+same seeded inputs, through the C-ABI.  Sizes span several tiles and ragged
+tails; every kernel family (fast 256x256, fast 128x128, guarded bf16, fp32,
+split-K + reduce, batched) is exercised."""
+import numpy as np
+import pytest
+
+from gpu_util import run_case
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ bf16, fast kernels
+@pytest.mark.parametrize("M,N,K", [
+    (256, 256, 64),      # one 256 tile, one K tile
+    (256, 256, 128),     # two K tiles (both stages)
+    (256, 256, 192),     # three K tiles (stage reuse)
+    (512, 768, 256),     # 2x3 tiles
+    (520, 776, 328),     # ragged M, N and K (K % 64 = 8)
+    (1024, 256, 72),     # ragged K only
+    (257, 264, 64),      # one row / one chunk over the tile
+])
+def test_bf16_fast_256(oracle, M, N, K):
+    _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K)
+    assert cfg == "bf16_256x256x64_w8"
+
+
+@pytest.mark.parametrize("M,N,K", [
+    (128, 128, 64), (128, 128, 192), (128, 384, 128), (200, 136, 72), (8, 8, 8), (1, 8, 8), (131, 248, 200),
+])
+def test_bf16_fast_128(oracle, M, N, K):
+    _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=1.25, act="relu", seed=M * 3 + N + K)
+    assert cfg == "bf16_128x128x64_w4"
+
+
+@pytest.mark.parametrize("act", ["none", "relu", "gelu_tanh"])
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_bf16_epilogue_variants(oracle, act, with_bias):
+    run_case(oracle, "bf16", 384, 512, 256, alpha=0.75, act=act, with_bias=with_bias, seed=5, dist="normal")
+
+
+def test_bf16_padded_leading_dimensions(oracle):
+    run_case(oracle, "bf16", 300, 264, 136, lda=144, ldb=272, ldc=301, alpha=1.0, act="none", seed=6)
+    run_case(oracle, "bf16", 512, 512, 128, lda=136, ldb=520, ldc=515, alpha=1.0, act="relu", seed=7)
+
+
+# ------------------------------------------------------------------ bf16, guarded kernel
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (67, 45, 33), (64, 66, 32), (130, 70, 100), (33, 257, 7)])
+def test_bf16_generic_odd_sizes(oracle, M, N, K):
+    _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + 7 * N + K)
+    assert cfg == "bf16_generic_64x64x32"
+
+
+def test_bf16_generic_misaligned_and_odd_ld(oracle):
+    _, _, _, cfg = run_case(oracle, "bf16", 128, 128, 64, misalign=1, act="relu", seed=8)
+    assert cfg == "bf16_generic_64x64x32"
+    _, _, _, cfg = run_case(oracle, "bf16", 128, 128, 64, lda=65, ldb=131, ldc=129, act="none", seed=9)
+    assert cfg == "bf16_generic_64x64x32"
+
+
+# ------------------------------------------------------------------ fp32
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (128, 128, 16), (1, 1, 1), (130, 257, 75), (300, 96, 40)])
+def test_f32(oracle, M, N, K):
+    run_case(oracle, "f32", M, N, K, alpha=1.0, act="none", with_bias=False, seed=M + N + K)
+    run_case(oracle, "f32", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K + 1)
+
+
+def test_f32_layouts(oracle):
+    run_case(oracle, "f32", 200, 136, 72, lda=76, ldb=140, ldc=137, act="relu", seed=3)
+    run_case(oracle, "f32", 200, 136, 72, lda=75, ldb=139, ldc=137, act="relu", seed=4)
+    run_case(oracle, "f32", 129, 130, 31, misalign=1, act="none", seed=5)
+    run_case(oracle, "f32", 100, 60, 50, batch=3, act="gelu_tanh", seed=6)
+
+
+# ------------------------------------------------------------------ batched
+def test_bf16_batched(oracle):
+    _, _, _, cfg = run_case(oracle, "bf16", 512, 512, 64, batch=4, act="relu", seed=10, dist="normal")
+    assert cfg.startswith("bf16_")
+    run_case(oracle, "bf16", 128, 136, 72, batch=5, act="relu", seed=11)
+    run_case(oracle, "bf16", 65, 33, 17, batch=3, act="none", seed=12)          # guarded kernel
+    run_case(oracle, "bf16", 256, 256, 128, batch=2, lda=136, ldb=264, ldc=260, act="gelu_tanh", seed=13)
+
+
+# ------------------------------------------------------------------ split-K
+def test_splitk_auto_and_forced(oracle):
+    from paper_2604_01489_amd import binding
+    assert binding.auto_split_k(128, 128, 8192, 1) > 1
+    got_auto, ref, _, cfg = run_case(oracle, "bf16", 128, 128, 8192, alpha=1 / 64, act="none", seed=14)
+    assert cfg.endswith("_splitk")
+    got_direct, _, _, cfg2 = run_case(oracle, "bf16", 128, 128, 8192, alpha=1 / 64, act="none", seed=14,
+                                      plan="direct")
+    assert not cfg2.endswith("_splitk")
+    assert np.max(np.abs(got_auto - got_direct)) <= 1e-2
+    for s in (2, 3, 7):
+        run_case(oracle, "bf16", 264, 256, 1096, alpha=0.125, act="gelu_tanh", seed=15, plan="splitk",
+                 split_k=s, workspace="caller")
+    run_case(oracle, "bf16", 70, 50, 1000, alpha=0.125, act="relu", seed=16, plan="splitk", split_k=4)
+    run_case(oracle, "bf16", 128, 128, 1024, batch=2, alpha=0.125, act="relu", seed=17, plan="splitk",
+             split_k=4, ldc=130)
+
+
+def test_splitk_bitwise_repeatable(oracle):
+    outs = [run_case(oracle, "bf16", 256, 256, 4096, alpha=1 / 64, act="none", seed=18)[0].tobytes()
+            for _ in range(3)]
+    assert outs[0] == outs[1] == outs[2]
+
+
+def test_direct_bitwise_repeatable(oracle):
+    outs = [run_case(oracle, "bf16", 512, 512, 512, alpha=0.5, act="gelu_tanh", seed=19)[0].tobytes()
+            for _ in range(2)]
+    assert outs[0] == outs[1]
+
+
+def test_integer_inputs_are_exact(oracle):
+    """Small integers: every product and partial sum is exact in fp32, so the
+    GPU must equal the oracle bit for bit whatever the summation order."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    from gpu_util import to_device
+    rng = np.random.default_rng(0)
+    for (M, N, K) in [(256, 256, 128), (128, 136, 72), (67, 45, 33)]:
+        Ai = rng.integers(-4, 5, (M, K)).astype(np.float32)
+        Bi = rng.integers(-4, 5, (K, N)).astype(np.float32)
+        C = torch.empty(M, N, dtype=torch.float32, device="cuda:0")
+        binding.gemm_epilogue_bf16(M, N, K, to_device(gen.to_bf16_bits(Ai)), K, to_device(gen.to_bf16_bits(Bi)),
+                                   N, None, 1.0, "none", C, N)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy().astype(np.float64), oracle.gemm_epilogue(Ai, Bi))
+        C32 = torch.empty(M, N, dtype=torch.float32, device="cuda:0")
+        binding.gemm_epilogue_f32(M, N, K, to_device(Ai), K, to_device(Bi), N, None, 1.0, "none", C32, N)
+        torch.cuda.synchronize()
+        assert np.array_equal(C32.cpu().numpy().astype(np.float64), oracle.gemm_epilogue(Ai, Bi))

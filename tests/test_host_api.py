@@ -1,0 +1,86 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the
+header declares, validates arguments before touching a device and plans split-K
+as documented."""
+import os
+import re
+
+import pytest
+
+from paper_2604_01489_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not build.library_is_current():
+        build.build_library()
+    return binding.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "gemm_epilogue.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*)\s*\(", header))
+    assert declared == set(binding.SYMBOLS), declared ^ set(binding.SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = {binding.status_string(i) for i in range(9)}
+    assert len(seen) == 9 and "ok" in seen
+    assert binding.status_string(99) == "unknown status"
+
+
+P = 0x10000  # a plausible, suitably aligned fake device address: never dereferenced on error paths
+
+
+@pytest.mark.parametrize("name", ["gemm_epilogue_bf16", "gemm_epilogue_f32"])
+def test_argument_errors_return_codes(lib, name):
+    call = lambda *a: binding.raw_call(name, *a)
+    ok = (64, 64, 64, P, 64, P, 64, None, 1.0, 0, P, 64, 1)
+
+    def with_(**kw):
+        names = ["M", "N", "K", "A", "lda", "B", "ldb", "bias", "alpha", "act", "C", "ldc", "batch"]
+        vals = list(ok)
+        for k, v in kw.items():
+            vals[names.index(k)] = v
+        return call(*vals)
+
+    assert with_(A=None) == 1 and with_(B=None) == 1 and with_(C=None) == 1
+    assert with_(M=0) == 2 and with_(N=-1) == 2 and with_(K=0) == 2 and with_(batch=0) == 2
+    assert with_(lda=63) == 3 and with_(ldb=63) == 3 and with_(ldc=63) == 3
+    assert with_(act=3) == 4 and with_(act=-1) == 4
+    assert with_(A=P + 1) == 5 and with_(C=P + 2) == 5 and with_(bias=P + 1) == 5
+    if name.endswith("f32"):
+        assert with_(B=P + 2) == 5
+
+
+def test_ex_plan_errors(lib):
+    base = (64, 64, 64, P, 64, P, 64, None, 1.0, 0, P, 64, 1)
+    assert binding.raw_call("gemm_epilogue_bf16_ex", *base, extra=(7, 0, None, 0)) == 8
+    assert binding.raw_call("gemm_epilogue_bf16_ex", *base, extra=(2, -1, None, 0)) == 8
+    # caller workspace too small / misaligned for a forced split
+    big = (256, 256, 4096, P, 4096, P, 256, None, 1.0, 0, P, 256, 1)
+    need = binding.workspace_bytes(256, 256, 4096, 1, "splitk", 4)
+    assert need == 4 * 256 * 256 * 4
+    assert binding.raw_call("gemm_epilogue_bf16_ex", *big, extra=(2, 4, P, need - 1)) == 6
+    assert binding.raw_call("gemm_epilogue_bf16_ex", *big, extra=(2, 4, P + 16, need)) == 6
+
+
+def test_split_k_planning(lib):
+    # many output tiles: never split
+    assert binding.auto_split_k(8192, 8192, 8192) == 1
+    assert binding.auto_split_k(4096, 4096, 4096) == 1
+    assert binding.auto_split_k(512, 512, 64, 256) == 1
+    # 16 tiles of 256x256, K = 65536: one slice per CU
+    assert binding.auto_split_k(1024, 1024, 65536) == 16
+    assert binding.workspace_bytes(1024, 1024, 65536) == 16 * 1024 * 1024 * 4
+    # short K is not worth slicing
+    assert binding.auto_split_k(128, 128, 512) == 1
+    assert binding.workspace_bytes(8192, 8192, 8192) == 0
+    # forced split rounds slices to whole K tiles and drops empty ones: 5 wanted, K = 128
+    # gives 2 slices of 64 with the fast kernels and 4 of 32 with the guarded one; the
+    # query does not know the pointers' alignment and reports the larger need
+    assert binding.workspace_bytes(256, 256, 128, 1, "splitk", 5) == 4 * 256 * 256 * 4
