@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Throughput of the fused GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole path (tile dispatch, global->LDS staging, MFMA
+main loop, fused epilogue, and the split-K reduction when the plan has one) over
+one synthetic batch already resident in HBM.  The default workload is the
+8192^3 bf16 GEMM + bias + tanh-GELU the headline metric is quoted on.  Prints one
+JSON line with the whole-job rate, the roofline fraction of the dominant kernel
+(algorithmic FLOP or bytes per launch over the launch time measured with HIP
+events on the launch stream) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 matrix peak (datasheet)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E bandwidth (datasheet)
+DEFAULT_WORKLOAD = "c3_bf16_8192_bias_gelu"
+# which roofline bounds the dominant kernel of each workload
+BOUND = {
+    "c2_bf16_4096": "mfma",
+    "c3_bf16_8192_bias_gelu": "mfma",
+    "c4_bf16_batched_512x512x64": "hbm",
+    "c5_bf16_splitk_1024x1024x65536": "mfma",
+}
+
+
+def sample_rows(M: int, count: int) -> np.ndarray:
+    """`count` rows in blocks of 32 spread evenly over M, always including the
+    first and the last block (so first/last tiles and wave sub-tiles are hit)."""
+    count = min(count, M)
+    blocks = max(1, count // 32)
+    if blocks * 32 >= M:
+        return np.arange(M)
+    starts = np.unique(np.round(np.linspace(0, M - 32, blocks)).astype(np.int64))
+    starts = starts + (np.arange(starts.size) % 7)      # not always tile aligned
+    starts = np.clip(starts, 0, M - 32)
+    return np.unique((starts[:, None] + np.arange(32)[None, :]).ravel())
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--oracle-rows", type=int, default=8192,
+                    help="rows of C the CPU oracle computes (bounded sample); 0 skips the oracle")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this library has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    binding.load()
+    w = gen.WORKLOADS[args.workload]
+    if w.dtype != "bf16":
+        print("bench.py times the bf16 workloads", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    M, N, K, batch = w.M, w.N, w.K, w.batch
+
+    # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
+    A = gen.make_operand(w, "A")
+    B = gen.make_operand(w, "B")
+    bias = gen.make_bias(w)
+    dA = torch.from_numpy(A.view(np.int16)).to(dev)
+    dB = torch.from_numpy(B.view(np.int16)).to(dev)
+    dbias = None if bias is None else torch.from_numpy(bias).to(dev)
+    dC = torch.empty(batch, M, N, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        binding.gemm_epilogue_bf16(M, N, K, dA, K, dB, N, dbias, w.alpha, w.act, dC, N, batch, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_wall = (t1 - t0) * 1e3 / args.steps
+    ms_dev = ev0.elapsed_time(ev1) / args.steps     # HIP events on the launch stream
+    config_name = binding.last_config()
+
+    tflops = w.flops / (ms_wall * 1e-3) / 1e12
+    bound = BOUND[args.workload]
+    if bound == "mfma":
+        achieved = w.flops / (ms_dev * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    else:
+        achieved = w.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline["kernel"] = config_name
+    roofline["ms_per_launch"] = round(ms_dev, 4)
+
+    # ---- CPU oracle on a bounded sample of the same workload, and parity on that sample
+    cpu_baseline = None
+    parity = None
+    if args.oracle_rows > 0:
+        import oracle
+        rows = sample_rows(M, args.oracle_rows)
+        nb = 1 if batch == 1 else min(batch, max(1, args.oracle_rows // len(rows)))
+        bsel = np.unique(np.round(np.linspace(0, batch - 1, nb)).astype(np.int64))
+        got = dC[torch.from_numpy(bsel).to(dev)][:, torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+        A_s = np.ascontiguousarray(A[bsel][:, rows])
+        B_s = np.ascontiguousarray(B[bsel])
+        c0 = time.perf_counter()
+        ref = oracle.gemm_epilogue(A_s, B_s, bias, w.alpha, w.act)
+        c1 = time.perf_counter()
+        sample_flops = 2.0 * len(bsel) * len(rows) * N * K
+        cpu_baseline = {"value": round(sample_flops / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"{len(rows)} of {M} rows of C in {len(bsel)} of {batch} batch(es), "
+                                  f"full N={N}, K={K}; {c1 - c0:.1f} s"}
+        err = np.abs(got - ref)
+        rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+        ok = bool(rel <= 1e-3 and np.all(err <= 1e-2 * np.maximum(1.0, np.abs(ref))))
+        parity = {"rows_checked": int(len(rows) * len(bsel)), "rel_frobenius": rel,
+                  "max_abs_err": float(err.max()), "ok": ok}
+
+    out = {
+        "metric": "TFLOP/s and % of MI355X bf16 MFMA peak, GEMM+bias+GELU at 8192^3",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_wall, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "batch": batch,
+                   "alpha": w.alpha, "act": w.act, "bias": w.bias is not None, "out_dtype": "f32",
+                   "kernel": config_name},
+        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "parity": parity,
+    }
+    print(json.dumps(out))
+    if parity is not None and not parity["ok"]:
+        print("parity check against the oracle FAILED", file=sys.stderr)
+        return 1
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
