@@ -1,91 +1,123 @@
 // bf16 x bf16 -> fp32 GEMM main kernel for gfx950 (MI355X).
 //
-// Structure, after the optimisation list for GEMM-like kernels in the paper's
-// optimisation prompt (block tiling, wave tiling, matrix instructions, bank
-// conflict free staging, multi-stage asynchronous loads) and the square-GEMM
-// case study (two staging buffers per operand, next K tile prefetched while the
-// current one is consumed), redone for CDNA4:
-//   * one workgroup owns a BM x BN tile of C and walks K in steps of 64;
-//   * WM x WN wavefronts of 64 lanes, each owning a (BM/WM) x (BN/WN) sub-tile
-//     as a grid of 32x32 v_mfma_f32_32x32x16_bf16 accumulators (fp32);
+// The optimisation list for GEMM-like kernels in the paper's optimisation prompt
+// (block tiling, wave tiling, matrix instructions, bank-conflict-free staging,
+// multi-stage asynchronous loads) and its square-GEMM case study (staging
+// buffers per operand, the next K tile prefetched while the current one is
+// consumed) are kept as ideas; the realisation is CDNA4's own:
+//   * one workgroup owns a BM x BN tile of C and walks K in steps of 32;
+//   * WM x WN wavefronts of 64 lanes, each owning a (BM/WM) x (BN/WN) sub-tile as
+//     a grid of 16x16 v_mfma_f32_16x16x32_bf16 accumulators (fp32).  Of the bf16
+//     shapes this one draws the least power per FLOP, and on this part the clock
+//     under load, not the issue rate, is what bounds a dense GEMM;
 //   * A and B tiles go global -> LDS with buffer_load_dwordx4 ... lds (16 bytes
-//     per lane, no register round trip), two stages, one barrier per K tile;
-//   * A fragments are ds_read_b128, B fragments ds_read_b64_tr_b16 (B is
-//     [K,N] row-major while the matrix unit wants 8 consecutive k per lane);
-//   * both LDS layouts are XOR-swizzled so fragment reads spread over all banks;
-//     because a direct-to-LDS load lands at base + 16*lane, the swizzle is
-//     applied by choosing which global chunk each lane fetches;
-//   * scale, bias and activation are applied to the accumulators in registers
-//     and C is written once.
+//     per lane, no register round trip) into a ring of four stages, three tiles
+//     in flight; completion is tracked with explicit s_waitcnt vmcnt(N);
+//   * A fragments are ds_read_b128, B fragments ds_read_b64_tr_b16 (B is [K,N]
+//     row-major while the matrix unit wants 8 consecutive k per lane);
+//   * both LDS layouts are XOR-swizzled so fragment reads spread over all banks
+//     (measured: SQ_LDS_BANK_CONFLICT = 0).  A direct-to-LDS load lands at
+//     base + 16*lane, so the swizzle is applied by choosing which global chunk
+//     each lane fetches;
+//   * with 8 waves the two waves of every SIMD run half a step apart: one issues
+//     its loads and LDS reads while the other issues back-to-back MFMAs, swapping
+//     at each barrier, so the matrix pipe never waits on LDS latency;
+//   * the product is formed transposed (B fragment as first operand) so a lane
+//     ends with 4 consecutive columns of one row: scale, bias and activation are
+//     applied in registers and C is written once with 16-byte stores.
 #pragma once
 #include "ge_device.h"
 
 namespace ge {
 
-constexpr int BF16_BK = 64;
-constexpr unsigned OOB_OFFSET = 0x80000000u;   // beyond num_records: the load returns 0
+constexpr int BF16_BK = 32;
+constexpr int BF16_STAGES = 4;
+constexpr unsigned OOB_OFFSET = 0x80000000u;   // >= num_records: the load returns 0, touches no memory
 constexpr unsigned RSRC_RECORDS = 0x80000000u;
 constexpr unsigned RSRC_FLAGS = 0x00020000u;   // raw buffer, 32-bit data format
-// s_waitcnt immediate (gfx9 encoding): vmcnt = 0, expcnt and lgkmcnt left at their maxima
-constexpr int WAIT_VMCNT0 = 0x0F70;
 
-// LDS byte offset of 16-byte chunk `c` (8 bf16 along k) of row `row` in an A
-// stage.  Rows r and r+8 share a 256-byte line (one in each half) and the chunk
-// index is XORed with row%8, so 8 or 16 consecutive rows reading the same k
-// chunk touch distinct banks.
-__device__ __host__ constexpr int lds_a_offset(int row, int c)
+// LDS byte offset of 16-byte chunk `c` (8 bf16 along k, c < 4) of row `r` in an A
+// stage (64 bytes per row).  Address bits 4-5: chunk ^ r[2:1]; bit 6: r[0]; bit 7:
+// r[3]; 256-byte line: (r/16)*4 + r[2:1].  Any 8 or 16 consecutive rows reading
+// the same chunk fall in distinct banks, and a 1 KB direct-to-LDS load covers
+// 16 rows with 4 consecutive lanes on the 64 contiguous bytes of one row.
+__device__ __host__ constexpr int lds_a_offset(int r, int c)
 {
-    return (((row >> 4) * 8 + (row & 7)) * 256) + (((row >> 3) & 1) * 128) + ((c ^ (row & 7)) * 16);
+    return (((r >> 4) * 4 + ((r >> 1) & 3)) * 256) + (((r >> 3) & 1) * 128) + ((r & 1) * 64) +
+           ((c ^ ((r >> 1) & 3)) * 16);
 }
 
-// 3-bit hash of a k row used to rotate the 64-byte column segments of a B stage:
-// the 8 k rows one transposing read touches (k%16 in {0..3, 8..11} or
-// {4..7, 12..15}) get 8 distinct values.
+// 3-bit hash of a k row that rotates the 64-byte column segments of a B stage: the
+// k rows one transposing read touches are spread over all segments.
 __device__ __host__ constexpr int lds_b_hash(int k)
 {
     return (k & 3) | ((k >> 1) & 4);
 }
 
-// LDS byte offset of 16-byte chunk `c` (8 bf16 along n) of k row `k` in a B
-// stage of width BN.
-template <int BN>
-__device__ __host__ constexpr int lds_b_offset(int k, int c)
+typedef __attribute__((ext_vector_type(4))) int rsrc_words_t;
+
+// 16 bytes per lane from a raw buffer straight into LDS at ldsAddr + 16*lane.
+// Written as inline assembly so the compiler does not track it: its own
+// bookkeeping of LDS DMA forces vmcnt(0) at loop headers, which would serialise
+// the pipeline.  The caller awaits completion with s_waitcnt vmcnt(N).
+__device__ inline void lds_dma16(rsrc_words_t rs, unsigned ldsAddr, unsigned voff)
 {
-    constexpr int SEGS = BN / 32;
-    return k * (BN * 2) + ((((c >> 2) ^ lds_b_hash(k)) & (SEGS - 1)) * 64) + ((c & 3) * 16);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(ldsAddr), "v"(voff), "s"(rs) : "memory");
+}
+
+__device__ inline rsrc_words_t make_rsrc(const void *base, unsigned records)
+{
+    const unsigned long long a = (unsigned long long)base;
+    rsrc_words_t r;
+    r[0] = (int)(unsigned)a;
+    r[1] = (int)((unsigned)(a >> 32) & 0xFFFFu);
+    r[2] = (int)records;
+    r[3] = (int)RSRC_FLAGS;
+    return r;
 }
 
 template <int BM, int BN, int WM, int WN>
 struct Bf16Tile {
-    static constexpr int BK = BF16_BK;
+    static constexpr int BK = BF16_BK, NS = BF16_STAGES;
     static constexpr int NW = WM * WN;
     static constexpr int THREADS = NW * 64;
     static constexpr int WTM = BM / WM, WTN = BN / WN;
-    static constexpr int TM = WTM / 32, TN = WTN / 32;
+    static constexpr int TM = WTM / 16, TN = WTN / 16;
     static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BK * BN * 2;
-    static constexpr int A_LOADS = A_BYTES / 1024 / NW;  // wave-wide 1 KB loads per wave
+    static constexpr int A_LOADS = A_BYTES / 1024 / NW;  // wave-wide 1 KB loads per wave and tile
     static constexpr int B_LOADS = B_BYTES / 1024 / NW;
-    static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be 32x32 blocks");
+    static constexpr int LOADS = A_LOADS + B_LOADS;
+    static constexpr int LDS_BYTES = NS * (A_BYTES + B_BYTES);
+    static constexpr bool PINGPONG = (NW == 8);
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(WTM % 16 == 0 && WTN % 32 == 0, "wave tile shape");
     static_assert((A_BYTES / 1024) % NW == 0 && (B_BYTES / 1024) % NW == 0, "loads must divide over waves");
-    static_assert(BM % 16 == 0 && BN % 32 == 0 && (BN & (BN - 1)) == 0, "tile shape");
-    static_assert((TN & (TN - 1)) == 0, "TN must be a power of two");
+    static_assert(BM % 16 == 0 && BN % 32 == 0 && (BN & (BN - 1)) == 0, "block tile shape");
+    static_assert(((WTN / 32) & (WTN / 32 - 1)) == 0, "WTN/32 must be a power of two");
+    static_assert(2 * LOADS <= 63, "vmcnt range");
 };
 
-// EDGE: the tile may hang over M, N or the K range (loads are zero filled
-// through the buffer bounds check, stores are masked).  RAW: write alpha-less,
-// bias-less fp32 partial sums for the split-K reduction instead of C.
+// EDGE: the tile may hang over M, N or the K range (loads are zero filled through
+// the buffer bounds check, stores are masked).  RAW: write fp32 partial sums for
+// the split-K reduction (no scale, bias or activation) instead of C.
 template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmParams p)
 {
     using T = Bf16Tile<BM, BN, WM, WN>;
-    constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN;
+    constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
+    constexpr bool PINGPONG = T::PINGPONG;
 
+    // one array per stage and operand (kept apart for the compiler's alias analysis)
     __shared__ __attribute__((aligned(1024))) char sA0[T::A_BYTES];
     __shared__ __attribute__((aligned(1024))) char sA1[T::A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA2[T::A_BYTES];
+    __shared__ __attribute__((aligned(1024))) char sA3[T::A_BYTES];
     __shared__ __attribute__((aligned(1024))) char sB0[T::B_BYTES];
     __shared__ __attribute__((aligned(1024))) char sB1[T::B_BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB2[T::B_BYTES];
+    __shared__ __attribute__((aligned(1024))) char sB3[T::B_BYTES];
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -100,17 +132,15 @@ gemm_bf16_kernel(const GemmParams p)
     const char *gA = (const char *)p.A + 2 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda + kBegin);
     const char *gB = (const char *)p.B + 2 * ((long long)tc.b * p.strideB + (long long)kBegin * p.ldb + n0);
 
-    // ---- per-lane global offsets of the 16-byte chunks this lane fetches -----
+    // ---- per-lane global offsets of the 16-byte chunks this lane fetches (inverse of
+    // the LDS layout: slot -> (row, chunk)) -------------------------------------------
     unsigned voffA[T::A_LOADS], voffB[T::B_LOADS];
-    int rowA[T::A_LOADS], chA[T::A_LOADS], rowB[T::B_LOADS];
-    bool okB[T::B_LOADS];
+    int chA[T::A_LOADS], rowB[T::B_LOADS];
 #pragma unroll
     for (int j = 0; j < T::A_LOADS; ++j) {
-        const int q = (j * NW + w) * 64 + lane;      // 16-byte slot in the stage
-        const int line = q >> 4, half = (q >> 3) & 1, pc = q & 7;
-        const int row = (line >> 3) * 16 + half * 8 + (line & 7);
-        const int c = pc ^ (row & 7);
-        rowA[j] = row;
+        const int wl = j * NW + w;                   // 1 KB slab = 16 rows
+        const int row = wl * 16 + ((lane >> 3) & 1) * 8 + ((lane >> 4) & 3) * 2 + ((lane >> 2) & 1);
+        const int c = (lane & 3) ^ ((lane >> 4) & 3);
         chA[j] = c;
         voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
         if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
@@ -124,100 +154,130 @@ gemm_bf16_kernel(const GemmParams p)
         const int c = seg * 4 + (pc & 3);
         rowB[j] = k;
         voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
-        okB[j] = !EDGE || (n0 + c * 8 < p.N);
-        if (!okB[j]) voffB[j] = OOB_OFFSET;
+        if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
     }
 
+    // Tiles past the end of the K range are fetched through a zero-length resource:
+    // every lane is out of range, nothing is read and zeros land in a stage nobody
+    // consumes, so the number of loads in flight is the same in every step.
     auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
-        const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(gA + (long long)kt * (BK * 2)), 0, RSRC_RECORDS, RSRC_FLAGS);
-        const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(gB + (long long)kt * BK * p.ldb * 2), 0, RSRC_RECORDS, RSRC_FLAGS);
+        const unsigned rec = kt < nk ? RSRC_RECORDS : 0u;
+        const rsrc_words_t rA = make_rsrc(gA + (long long)kt * (BK * 2), rec);
+        const rsrc_words_t rB = make_rsrc(gB + (long long)kt * BK * p.ldb * 2, rec);
         const int kLeft = kLen - kt * BK;            // valid k in this tile (EDGE only)
 #pragma unroll
         for (int j = 0; j < T::A_LOADS; ++j) {
             unsigned v = voffA[j];
             if (EDGE && chA[j] * 8 >= kLeft) v = OOB_OFFSET;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (GE_LDS void *)(dA + (j * NW + w) * 1024), 16, v, 0, 0, 0);
+            lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
         }
 #pragma unroll
         for (int j = 0; j < T::B_LOADS; ++j) {
             unsigned v = voffB[j];
             if (EDGE && rowB[j] >= kLeft) v = OOB_OFFSET;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (GE_LDS void *)(dB + (j * NW + w) * 1024), 16, v, 0, 0, 0);
+            lds_dma16(rB, (unsigned)(size_t)(dB + (j * NW + w) * 1024), v);
         }
     };
 
-    // ---- per-lane LDS read addresses ---------------------------------------
-    // A fragment (tm, ks): row = wm*WTM + tm*32 + lane%32, chunk = 2*ks + lane/32.
-    // The chunk bits sit alone in address bits 4..6, so stepping ks is an XOR.
-    const int rowInWave = lane & 31;
-    const unsigned aBase = (unsigned)lds_a_offset(wm * T::WTM + rowInWave, lane >> 5);
-    // B fragment (tn, ks), read r in {0,1}: the 16-lane group g = lane/16 covers
-    // n = tn*32 + (g%2)*16 .. +15 and k = ks*16 + (lane/32)*8 + r*4 .. +3; lane i
-    // of the group addresses k row i/4, 4 columns starting at (i%4)*4, and
-    // receives column i of the 4x16 block.
+    // ---- per-lane LDS read addresses ---------------------------------------------
+    // A fragment i: rows wm*WTM + 16 i + lane%16, k chunk lane/16 (k = 8*(lane/16) + e).
+    const unsigned aBase = (unsigned)lds_a_offset(wm * T::WTM + (lane & 15), lane >> 4);
+    // B fragment j, read r in {0,1}: the 16-lane group g = lane/16 covers k = 8g + 4r .. +3
+    // of columns wn*WTN + 16 j .. +15; lane i of the group addresses k row i/4, the 4
+    // columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
     const int i16 = lane & 15;
-    const int kLane = (lane >> 5) * 8 + (i16 >> 2);
-    const int cLane = ((lane >> 4) & 1) * 2 + ((i16 & 3) >> 1);
-    const unsigned bBase = (unsigned)lds_b_offset<BN>(kLane, wn * TN * 4 + cLane) + (unsigned)(i16 & 1) * 8u;
+    const int kLane = 8 * (lane >> 4) + (i16 >> 2);
+    const unsigned bBase = (unsigned)kLane * (BN * 2) +
+                           (unsigned)(((wn * (T::WTN / 32)) ^ lds_b_hash(kLane)) & (BN / 32 - 1)) * 64u +
+                           (unsigned)((i16 & 3) >> 1) * 16u + (unsigned)(i16 & 1) * 8u;
 
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.0f;
 
-    auto compute = [&](const GE_LDS char *cA, const GE_LDS char *cB) {
+    bf16x8_t fa[TM], fb[TN];
+
+    auto read_frags = [&](const GE_LDS char *cA, const GE_LDS char *cB) {
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t a[TM], b[TN];
+        for (int i = 0; i < TM; ++i)
+            fa[i] = *(const GE_LDS bf16x8_t *)(cA + (aBase + (unsigned)(i * 1024)));
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const GE_LDS char *ptr = cA + ((aBase ^ (unsigned)(ks * 32)) + (unsigned)(i * 32 * 128));
-                a[i] = *(const GE_LDS bf16x8_t *)ptr;
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const GE_LDS char *ptr = cB + ((bBase ^ (unsigned)(j * 64)) + (unsigned)(ks * 16 * BN * 2));
-                short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
-                short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * BN * 2));
-                short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                b[j] = __builtin_bit_cast(bf16x8_t, both);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) {
+            const GE_LDS char *ptr = cB + ((bBase ^ (unsigned)((j >> 1) * 64)) + (unsigned)((j & 1) * 32));
+            short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
+            short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * BN * 2));
+            short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            fb[j] = __builtin_bit_cast(bf16x8_t, both);
         }
     };
+    // Transposed product: the B fragment is the matrix unit's first operand, so
+    // accumulator register r of lane l is C[m = 16 i + l%16][n = 16 j + 4*(l/16) + r].
+    auto mma = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    };
 
-    GE_LDS char *lA0 = (GE_LDS char *)sA0, *lA1 = (GE_LDS char *)sA1;
-    GE_LDS char *lB0 = (GE_LDS char *)sB0, *lB1 = (GE_LDS char *)sB1;
+    GE_LDS char *lA[4] = {(GE_LDS char *)sA0, (GE_LDS char *)sA1, (GE_LDS char *)sA2, (GE_LDS char *)sA3};
+    GE_LDS char *lB[4] = {(GE_LDS char *)sB0, (GE_LDS char *)sB1, (GE_LDS char *)sB2, (GE_LDS char *)sB3};
+    // waves w and w+4 share a SIMD: they form the two phase groups
+    const int group = w >> 2;
 
-    // ---- main loop: one barrier per K tile ---------------------------------
-    // At the barrier every wave has (a) seen its own loads of tile kt land
-    // (vmcnt 0) and (b) finished reading the other stage, so that stage can be
-    // refilled with tile kt+1 while tile kt is consumed.
-    issue(0, lA0, lB0);
-    for (int kt = 0; kt < nk; kt += 2) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        __syncthreads();
-        if (kt + 1 < nk) issue(kt + 1, lA1, lB1);
-        compute(lA0, lB0);
-        if (kt + 1 < nk) {
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-            __syncthreads();
-            if (kt + 2 < nk) issue(kt + 2, lA0, lB0);
-            compute(lA1, lB1);
-        }
+    // One K tile t held in stage S (compile time).  Loads of tile t+3 refill the stage of
+    // tile t-1, which every wave has finished reading (barrier of the previous step).
+    //  8 waves: [loads t+3, LDS reads t, wait own part of t+1] barrier [MFMAs t] barrier,
+    //           the two groups half a step apart (one extra barrier for group 1 up front);
+    //  4 waves: [wait own part of t] barrier [loads t+3, LDS reads t, MFMAs t].
+#define GE_BF16_STEP(S, t)                                                                          \
+    if (PINGPONG) {                                                                                 \
+        issue((t) + 3, lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
+        read_frags(lA[S], lB[S]);                                                                   \
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");    \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        __builtin_amdgcn_s_setprio(1);                                                              \
+        mma();                                                                                      \
+        __builtin_amdgcn_s_setprio(0);                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        asm volatile("s_barrier" ::: "memory");                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+    } else {                                                                                        \
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");    \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        issue((t) + 3, lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
+        read_frags(lA[S], lB[S]);                                                                   \
+        mma();                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
-    // ---- epilogue: acc register r of lane l is row 8*(r/4) + 4*(l/32) + r%4,
-    // column l%32 of its 32x32 block ------------------------------------------
+    issue(0, lA[0], lB[0]);
+    issue(1, lA[1], lB[1]);
+    issue(2, lA[2], lB[2]);
+    if (PINGPONG) {
+        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
+        if (group == 1) asm volatile("s_barrier" ::: "memory");
+    }
+    for (int kt = 0;; kt += 4) {
+        GE_BF16_STEP(0, kt);
+        if (kt + 1 >= nk) break;
+        GE_BF16_STEP(1, kt + 1);
+        if (kt + 2 >= nk) break;
+        GE_BF16_STEP(2, kt + 2);
+        if (kt + 3 >= nk) break;
+        GE_BF16_STEP(3, kt + 3);
+        if (kt + 4 >= nk) break;
+    }
+#undef GE_BF16_STEP
+    if (PINGPONG && group == 0) asm volatile("s_barrier" ::: "memory");
+    // the zero-length loads of the padding tiles must have retired before the LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+    // ---- epilogue in registers, 16-byte stores --------------------------------------
     float *cBase;
     long long ldc;
     if (RAW) {
@@ -227,22 +287,36 @@ gemm_bf16_kernel(const GemmParams p)
         ldc = p.ldc;
         cBase = p.C + (long long)tc.b * p.strideC;
     }
-    const int rowLane = m0 + wm * T::WTM + 4 * (lane >> 5);
-    const int colLane = n0 + wn * T::WTN + (lane & 31);
+    const int rowLane = m0 + wm * T::WTM + (lane & 15);
+    const int colLane = n0 + wn * T::WTN + 4 * (lane >> 4);
+    const bool vecStore = ((ldc & 3) == 0) && ((((unsigned long long)cBase) & 15) == 0);
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int n = colLane + j * 32;
-        const bool nOk = !EDGE || n < p.N;
-        float bv = 0.0f;
-        if (!RAW && p.bias != nullptr && nOk) bv = p.bias[n];
+        const int n = colLane + j * 16;
+        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (!RAW && p.bias != nullptr) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (!EDGE || n + r < p.N) bv[r] = p.bias[n + r];
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
+            const int m = rowLane + i * 16;
+            float v[4];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = rowLane + i * 32 + 8 * (r >> 2) + (r & 3);
-                float v = acc[i][j][r];
-                if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv);
-                if (!EDGE || (nOk && m < p.M)) cBase[(long long)m * ldc + n] = v;
+            for (int r = 0; r < 4; ++r) {
+                v[r] = acc[i][j][r];
+                if (!RAW) v[r] = epilogue_value<ACT>(v[r], p.alpha, bv[r]);
+            }
+            float *dst = cBase + (long long)m * ldc + n;
+            if (!EDGE || m < p.M) {
+                if (vecStore && (!EDGE || n + 4 <= p.N)) {
+                    *(float4 *)dst = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (!EDGE || n + r < p.N) dst[r] = v[r];
+                }
             }
         }
     }

@@ -52,11 +52,12 @@ bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
 }
 
 // K slices so that a launch with few output tiles still covers the chip.
-int choose_split(long long tiles, int K, int bk)
+int choose_split(long long tiles, int K)
 {
-    if (tiles * 2 > kNumCU || K < 8 * bk * 2) return 1;
+    constexpr int kMinSlice = 512;             // K extent below which a slice is not worth its partial tile
+    if (tiles * 2 > kNumCU || K < 2 * kMinSlice) return 1;
     long long s = kNumCU / tiles;
-    const long long maxS = K / (8 * bk);       // at least 8 K tiles per slice
+    const long long maxS = K / kMinSlice;
     if (s > maxS) s = maxS;
     if (s > 64) s = 64;
     return s < 2 ? 1 : (int)s;
@@ -80,8 +81,8 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
         bool big = (M >= 256 && N >= 256);
         if (force && std::strcmp(force, "256x256") == 0) big = true;
         if (force && std::strcmp(force, "128x128") == 0) big = false;
-        if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = 64; }
-        else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = 64; }
+        if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = ge::BF16_BK; }
+        else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = ge::BF16_BK; }
     }
     pl.tilesM = ceil_div(M, pl.bm);
     pl.tilesN = ceil_div(N, pl.bn);
@@ -89,10 +90,10 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
     if (tiles > 0x7fffffffll / 64) return GE_ERR_SHAPE;
     int want = 1;
     if (plan == GE_PLAN_SPLITK) {
-        want = split_k > 0 ? split_k : choose_split(tiles, K, pl.bk);
+        want = split_k > 0 ? split_k : choose_split(tiles, K);
         if (want < 2) want = 2;
     } else if (plan == GE_PLAN_AUTO) {
-        want = choose_split(tiles, K, pl.bk);
+        want = choose_split(tiles, K);
     } else if (plan != GE_PLAN_DIRECT) {
         return GE_ERR_CONFIG;
     }
@@ -244,12 +245,12 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     case TILE_256:
         err = pl.edge ? launch_fast_sel<256, 256, 2, 4, true>(p, raw, (int)act, grid, hs)
                       : launch_fast_sel<256, 256, 2, 4, false>(p, raw, (int)act, grid, hs);
-        g_last_config = raw ? "bf16_256x256x64_w8_splitk" : "bf16_256x256x64_w8";
+        g_last_config = raw ? "bf16_256x256x32_w8_splitk" : "bf16_256x256x32_w8";
         break;
     case TILE_128:
         err = pl.edge ? launch_fast_sel<128, 128, 2, 2, true>(p, raw, (int)act, grid, hs)
                       : launch_fast_sel<128, 128, 2, 2, false>(p, raw, (int)act, grid, hs);
-        g_last_config = raw ? "bf16_128x128x64_w4_splitk" : "bf16_128x128x64_w4";
+        g_last_config = raw ? "bf16_128x128x32_w4_splitk" : "bf16_128x128x32_w4";
         break;
     default:
         if (raw) hipLaunchKernelGGL(ge::gemm_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, p);

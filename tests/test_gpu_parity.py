@@ -22,7 +22,7 @@ pytestmark = pytest.mark.gpu
 ])
 def test_bf16_fast_256(oracle, M, N, K):
     _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K)
-    assert cfg == "bf16_256x256x64_w8"
+    assert cfg == "bf16_256x256x32_w8"
 
 
 @pytest.mark.parametrize("M,N,K", [
@@ -30,7 +30,7 @@ def test_bf16_fast_256(oracle, M, N, K):
 ])
 def test_bf16_fast_128(oracle, M, N, K):
     _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=1.25, act="relu", seed=M * 3 + N + K)
-    assert cfg == "bf16_128x128x64_w4"
+    assert cfg == "bf16_128x128x32_w4"
 
 
 @pytest.mark.parametrize("act", ["none", "relu", "gelu_tanh"])
