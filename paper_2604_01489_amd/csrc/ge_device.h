@@ -76,7 +76,8 @@ __device__ inline float gelu_tanh_f32(float v)
 {
     const float c2 = 2.0f * 0.7978845608028654f;
     float u2 = c2 * (v + 0.044715f * v * v * v);
-    return v / (1.0f + __expf(-u2));
+    // hardware reciprocal (1 ulp) instead of an IEEE division: 1 + exp(-2u) >= 1, or +inf -> 0
+    return v * __builtin_amdgcn_rcpf(1.0f + __expf(-u2));
 }
 
 // scale -> bias -> activation, fp32, in registers.
