@@ -1,0 +1,73 @@
+"""The five synthetic workloads at full size, in the launch configuration bench.py
+times (plain gemm_epilogue_* calls, library-chosen plan), checked against the oracle
+on sampled rows of C (whole first and last tiles' rows included) -- the oracle computes
+each sampled row exactly as it would in a full run.  The small fp32 workload is compared
+in full."""
+import numpy as np
+import pytest
+
+from gpu_util import compare, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(M, count):
+    """Blocks of 32 rows spread over M, first and last block included, not tile aligned."""
+    if count >= M:
+        return np.arange(M)
+    blocks = max(2, count // 32)
+    starts = np.unique(np.round(np.linspace(0, M - 32, blocks)).astype(np.int64))
+    starts = np.clip(starts + (np.arange(starts.size) % 5) * 3, 0, M - 32)
+    starts[0], starts[-1] = 0, M - 32
+    return np.unique((starts[:, None] + np.arange(32)[None, :]).ravel())
+
+
+def _run_workload(oracle, name, rows_wanted, batches_wanted=4):
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    w = gen.WORKLOADS[name]
+    A, B, bias = gen.make_inputs(w)
+    dA, dB, dbias = to_device(A), to_device(B), to_device(bias)
+    C = torch.empty(w.batch, w.M, w.N, dtype=torch.float32, device="cuda:0")
+    print(f"workload {name}", flush=True)
+    call = binding.gemm_epilogue_bf16 if w.dtype == "bf16" else binding.gemm_epilogue_f32
+    call(w.M, w.N, w.K, dA, w.K, dB, w.N, dbias, w.alpha, w.act, C, w.N, w.batch)
+    torch.cuda.synchronize()
+    cfg = binding.last_config()
+    rows = _sample_rows(w.M, rows_wanted)
+    bsel = np.unique(np.round(np.linspace(0, w.batch - 1, min(w.batch, batches_wanted))).astype(np.int64))
+    got = C[torch.from_numpy(bsel).cuda()][:, torch.from_numpy(rows).cuda()].cpu().numpy()
+    ref = oracle.gemm_epilogue(np.ascontiguousarray(A[bsel][:, rows]), np.ascontiguousarray(B[bsel]),
+                               bias, w.alpha, w.act)
+    rel = compare(got, ref, f"{name} [{cfg}]")
+    return C, cfg, rel
+
+
+def test_c1_f32_256_full(oracle):
+    _, cfg, _ = _run_workload(oracle, "c1_f32_256", 256)
+    assert cfg.startswith("f32_")
+
+
+def test_c2_bf16_4096(oracle):
+    _, cfg, _ = _run_workload(oracle, "c2_bf16_4096", 320)
+    assert cfg == "bf16_256x256x32_w8"
+
+
+def test_c3_bf16_8192_bias_gelu(oracle):
+    _, cfg, _ = _run_workload(oracle, "c3_bf16_8192_bias_gelu", 320)
+    assert cfg == "bf16_256x256x32_w8"
+
+
+def test_c4_bf16_batched(oracle):
+    C, cfg, _ = _run_workload(oracle, "c4_bf16_batched_512x512x64", 512, batches_wanted=6)
+    assert cfg.startswith("bf16_")
+    # relu output: no negative value anywhere in the full result
+    assert float(C.min()) >= 0.0
+
+
+def test_c5_bf16_splitk(oracle):
+    import torch
+    C1, cfg, _ = _run_workload(oracle, "c5_bf16_splitk_1024x1024x65536", 160)
+    assert cfg.endswith("_splitk")
+    C2, _, _ = _run_workload(oracle, "c5_bf16_splitk_1024x1024x65536", 32)
+    assert torch.equal(C1, C2), "split-K result must be bitwise repeatable"
