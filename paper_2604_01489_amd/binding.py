@@ -36,10 +36,11 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    path = os.environ.get("GE_LIBRARY", LIB_PATH)     # another build of the same library, for A/B timing
+    if not os.path.exists(path):
         raise FileNotFoundError(
-            f"{LIB_PATH} is missing: run `python -m paper_2604_01489_amd.build` first")
-    lib = ctypes.CDLL(LIB_PATH)
+            f"{path} is missing: run `python -m paper_2604_01489_amd.build` first")
+    lib = ctypes.CDLL(path)
     c_int, c_void, c_float, c_size = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
     common = [c_int, c_int, c_int, c_void, c_int, c_void, c_int, c_void, c_float, c_int,
               c_void, c_int, c_int]

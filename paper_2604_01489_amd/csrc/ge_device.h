@@ -35,6 +35,7 @@ struct GemmParams {
     int groupM;      // tile rows swept together (L2 reuse of the B panels)
     float alpha;
     int act;
+    long long bytesA, bytesB;  // extent of the A and B allocations as the arguments describe them
 };
 
 struct TileCoord {
@@ -46,9 +47,9 @@ struct TileCoord {
 // in groups of `groupM` tile rows so that the tiles resident on one XCD at a
 // time share A and B panels in that XCD's L2.  Logical order, innermost first:
 // tile within problem, batch, K slice.
-__device__ inline TileCoord map_block(const GemmParams &p)
+__device__ inline TileCoord map_block(const GemmParams &p, unsigned bid)
 {
-    const unsigned total = gridDim.x, bid = blockIdx.x;
+    const unsigned total = gridDim.x;
     const unsigned q = total / 8u, rem = total % 8u, xcd = bid % 8u;
     unsigned L = xcd * q + (xcd < rem ? xcd : rem) + bid / 8u;
     const unsigned tiles = (unsigned)(p.tilesM * p.tilesN);
@@ -67,6 +68,8 @@ __device__ inline TileCoord map_block(const GemmParams &p)
     c.tn = (int)(in / rows);
     return c;
 }
+
+__device__ inline TileCoord map_block(const GemmParams &p) { return map_block(p, blockIdx.x); }
 
 // gelu_tanh(v) = 0.5 v (1 + tanh u) with u = sqrt(2/pi) (v + 0.044715 v^3).
 // Since 0.5 (1 + tanh u) = 1 / (1 + exp(-2u)) this is v / (1 + exp(-2u)): one

@@ -29,6 +29,7 @@
 //     few instructions (measured faster than 16-byte-per-lane stores whose
 //     neighbouring lanes sit in different rows).
 #pragma once
+#include "bf16_layout.h"
 #include "ge_device.h"
 
 namespace ge {
@@ -36,26 +37,8 @@ namespace ge {
 constexpr int BF16_BK = 32;
 constexpr int BF16_STAGES = 4;
 constexpr unsigned OOB_OFFSET = 0x80000000u;   // >= num_records: the load returns 0, touches no memory
-constexpr unsigned RSRC_RECORDS = 0x80000000u;
+constexpr unsigned RSRC_RECORDS = 0x80000000u;  // upper bound of num_records (keeps OOB_OFFSET out of range)
 constexpr unsigned RSRC_FLAGS = 0x00020000u;   // raw buffer, 32-bit data format
-
-// LDS byte offset of 16-byte chunk `c` (8 bf16 along k, c < 4) of row `r` in an A
-// stage (64 bytes per row).  Address bits 4-5: chunk ^ r[2:1]; bit 6: r[0]; bit 7:
-// r[3]; 256-byte line: (r/16)*4 + r[2:1].  Any 8 or 16 consecutive rows reading
-// the same chunk fall in distinct banks, and a 1 KB direct-to-LDS load covers
-// 16 rows with 4 consecutive lanes on the 64 contiguous bytes of one row.
-__device__ __host__ constexpr int lds_a_offset(int r, int c)
-{
-    return (((r >> 4) * 4 + ((r >> 1) & 3)) * 256) + (((r >> 3) & 1) * 128) + ((r & 1) * 64) +
-           ((c ^ ((r >> 1) & 3)) * 16);
-}
-
-// 3-bit hash of a k row that rotates the 64-byte column segments of a B stage: the
-// k rows one transposing read touches are spread over all segments.
-__device__ __host__ constexpr int lds_b_hash(int k)
-{
-    return (k & 3) | ((k >> 1) & 4);
-}
 
 typedef __attribute__((ext_vector_type(4))) int rsrc_words_t;
 
@@ -67,6 +50,21 @@ __device__ inline void lds_dma16(rsrc_words_t rs, unsigned ldsAddr, unsigned vof
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(ldsAddr), "v"(voff), "s"(rs) : "memory");
+}
+
+// num_records for a resource that starts `consumed` bytes into an allocation of `total` bytes:
+// what is left of the allocation, capped at RSRC_RECORDS.  With it an offset that is wrong for
+// whatever reason reads zeros instead of faulting.
+// Written on 32-bit halves so that it stays on the scalar unit (there is no 64-bit scalar
+// compare, and vector instructions in the load phase would take issue slots from the MFMAs of
+// the other wave group).  `consumed` never exceeds `total` for the tiles a block loads.
+__device__ inline unsigned records_left(long long total, long long consumed)
+{
+    const unsigned long long left = (unsigned long long)(total - consumed);
+    unsigned hi = (unsigned)(left >> 32), lo = (unsigned)left;
+    asm volatile("" : "+s"(hi), "+s"(lo));     // keep the halves apart: no 64-bit (vector) compare
+    const unsigned capped = lo < RSRC_RECORDS ? lo : RSRC_RECORDS;
+    return hi != 0u ? RSRC_RECORDS : capped;
 }
 
 __device__ inline rsrc_words_t make_rsrc(const void *base, unsigned records)
@@ -112,15 +110,10 @@ gemm_bf16_kernel(const GemmParams p)
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
 
-    // one array per stage and operand (kept apart for the compiler's alias analysis)
-    __shared__ __attribute__((aligned(1024))) char sA0[T::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sA1[T::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sA2[T::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sA3[T::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sB0[T::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sB1[T::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sB2[T::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) char sB3[T::B_BYTES];
+    // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages
+    // and, from a second lane base, the B stages each lie within the 64 KB immediate range), so
+    // the main loop carries no address arithmetic on the vector unit.
+    __shared__ __attribute__((aligned(1024))) char smem[T::LDS_BYTES];
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -132,8 +125,10 @@ gemm_bf16_kernel(const GemmParams p)
     const int kLen = min(p.K - kBegin, p.kPerSlice);
     const int nk = (kLen + BK - 1) / BK;
 
-    const char *gA = (const char *)p.A + 2 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda + kBegin);
-    const char *gB = (const char *)p.B + 2 * ((long long)tc.b * p.strideB + (long long)kBegin * p.ldb + n0);
+    const long long offA = 2 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda + kBegin);
+    const long long offB = 2 * ((long long)tc.b * p.strideB + (long long)kBegin * p.ldb + n0);
+    const char *gA = (const char *)p.A + offA;
+    const char *gB = (const char *)p.B + offB;
 
     // ---- per-lane global offsets of the 16-byte chunks this lane fetches (inverse of
     // the LDS layout: slot -> (row, chunk)) -------------------------------------------
@@ -141,20 +136,14 @@ gemm_bf16_kernel(const GemmParams p)
     int chA[T::A_LOADS], rowB[T::B_LOADS];
 #pragma unroll
     for (int j = 0; j < T::A_LOADS; ++j) {
-        const int wl = j * NW + w;                   // 1 KB slab = 16 rows
-        const int row = wl * 16 + ((lane >> 3) & 1) * 8 + ((lane >> 4) & 3) * 2 + ((lane >> 2) & 1);
-        const int c = (lane & 3) ^ ((lane >> 4) & 3);
+        const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);   // 1 KB slab = 16 rows
         chA[j] = c;
         voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
         if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
     }
 #pragma unroll
     for (int j = 0; j < T::B_LOADS; ++j) {
-        constexpr int CPR = BN / 8;                  // chunks per k row
-        const int q = (j * NW + w) * 64 + lane;
-        const int k = q / CPR, pc = q % CPR;
-        const int seg = ((pc >> 2) ^ lds_b_hash(k)) & (BN / 32 - 1);
-        const int c = seg * 4 + (pc & 3);
+        const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
         rowB[j] = k;
         voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
         if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
@@ -164,9 +153,18 @@ gemm_bf16_kernel(const GemmParams p)
     // every lane is out of range, nothing is read and zeros land in a stage nobody
     // consumes, so the number of loads in flight is the same in every step.
     auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
-        const unsigned rec = kt < nk ? RSRC_RECORDS : 0u;
-        const rsrc_words_t rA = make_rsrc(gA + (long long)kt * (BK * 2), rec);
-        const rsrc_words_t rB = make_rsrc(gB + (long long)kt * BK * p.ldb * 2, rec);
+        const long long stepA = (long long)kt * (BK * 2), stepB = (long long)kt * BK * p.ldb * 2;
+        // Full tiles: every offset lies inside the operand by construction, and the exact extent
+        // (ten scalar instructions per step, measured at 1-3 % of the 8192^3 run) is skipped.
+        // Edge tiles: the resource ends where the operand ends, so a lane that is not masked for
+        // whatever reason reads zeros instead of memory beyond the allocation.  Computed
+        // unconditionally, then selected: a conditional around it would be a scalar branch.
+        const unsigned leftA = EDGE ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
+        const unsigned leftB = EDGE ? records_left(p.bytesB, offB + stepB) : RSRC_RECORDS;
+        const unsigned recA = kt < nk ? leftA : 0u;
+        const unsigned recB = kt < nk ? leftB : 0u;
+        const rsrc_words_t rA = make_rsrc(gA + stepA, recA);
+        const rsrc_words_t rB = make_rsrc(gB + stepB, recB);
         const int kLeft = kLen - kt * BK;            // valid k in this tile (EDGE only)
 #pragma unroll
         for (int j = 0; j < T::A_LOADS; ++j) {
@@ -184,15 +182,13 @@ gemm_bf16_kernel(const GemmParams p)
 
     // ---- per-lane LDS read addresses ---------------------------------------------
     // A fragment i: rows wm*WTM + 16 i + lane%16, k chunk lane/16 (k = 8*(lane/16) + e).
-    const unsigned aBase = (unsigned)lds_a_offset(wm * T::WTM + (lane & 15), lane >> 4);
+    const unsigned aBase = (unsigned)a_frag_offset(wm * T::WTM, lane);
     // B fragment j, read r in {0,1}: the 16-lane group g = lane/16 covers k = 8g + 4r .. +3
     // of columns wn*WTN + 16 j .. +15; lane i of the group addresses k row i/4, the 4
     // columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
-    const int i16 = lane & 15;
-    const int kLane = 8 * (lane >> 4) + (i16 >> 2);
-    const unsigned bBase = (unsigned)kLane * (BN * 2) +
-                           (unsigned)(((wn * (T::WTN / 32)) ^ lds_b_hash(kLane)) & (BN / 32 - 1)) * 64u +
-                           (unsigned)((i16 & 3) >> 1) * 16u + (unsigned)(i16 & 1) * 8u;
+    // Stepping j moves 16 columns: bit 5 of the address for odd j, an XOR on the segment bits
+    // (6..8, hashed) for j/2; stepping r adds 4 k rows.
+    const unsigned bBase = (unsigned)b_frag_offset<BN>(wn * T::WTN, lane, 0);
 
     f32x4_t acc[TM][TN];
 #pragma unroll
@@ -204,13 +200,24 @@ gemm_bf16_kernel(const GemmParams p)
 
     bf16x8_t fa[TM], fb[TN];
 
-    auto read_frags = [&](const GE_LDS char *cA, const GE_LDS char *cB) {
+    // Lane bases held in registers the compiler cannot see through, so that each read below is
+    // "base + immediate": aAddr covers the A stages (offsets < 64 KB), bAddr[jj] the B stages
+    // for column pair jj.
+    unsigned aAddr = (unsigned)(size_t)(GE_LDS char *)smem + aBase;
+    asm volatile("" : "+v"(aAddr));
+    unsigned bAddr[TN / 2];
+#pragma unroll
+    for (int jj = 0; jj < TN / 2; ++jj) {
+        bAddr[jj] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(jj * 64));
+        asm volatile("" : "+v"(bAddr[jj]));
+    }
+    auto read_frags = [&](int stage) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fa[i] = *(const GE_LDS bf16x8_t *)(cA + (aBase + (unsigned)(i * 1024)));
+            fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr + (unsigned)(stage * T::A_BYTES + i * 1024));
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const GE_LDS char *ptr = cB + ((bBase ^ (unsigned)((j >> 1) * 64)) + (unsigned)((j & 1) * 32));
+            const GE_LDS char *ptr = (const GE_LDS char *)(size_t)(bAddr[j >> 1] + (unsigned)(stage * T::B_BYTES + (j & 1) * 32));
             short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
             short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * BN * 2));
             short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -226,20 +233,27 @@ gemm_bf16_kernel(const GemmParams p)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
 
-    GE_LDS char *lA[4] = {(GE_LDS char *)sA0, (GE_LDS char *)sA1, (GE_LDS char *)sA2, (GE_LDS char *)sA3};
-    GE_LDS char *lB[4] = {(GE_LDS char *)sB0, (GE_LDS char *)sB1, (GE_LDS char *)sB2, (GE_LDS char *)sB3};
+    GE_LDS char *const ldsBase = (GE_LDS char *)smem;
+    GE_LDS char *lA[4], *lB[4];
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+        lA[st] = ldsBase + st * T::A_BYTES;
+        lB[st] = ldsBase + 4 * T::A_BYTES + st * T::B_BYTES;
+    }
     // waves w and w+4 share a SIMD: they form the two phase groups
     const int group = w >> 2;
 
     // One K tile t held in stage S (compile time).  Loads of tile t+3 refill the stage of
     // tile t-1, which every wave has finished reading (barrier of the previous step).
-    //  8 waves: [loads t+3, LDS reads t, wait own part of t+1] barrier [MFMAs t] barrier,
+    //  8 waves: [LDS reads t, loads t+3, wait own part of t+1] barrier [MFMAs t] barrier (the LDS
+    //           reads go first: their latency, not the load issue, is what the phase waits for),
     //           the two groups half a step apart (one extra barrier for group 1 up front);
     //  4 waves: [wait own part of t] barrier [loads t+3, LDS reads t, MFMAs t].
 #define GE_BF16_STEP(S, t)                                                                          \
     if (PINGPONG) {                                                                                 \
+        read_frags(S);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
         issue((t) + 3, lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
-        read_frags(lA[S], lB[S]);                                                                   \
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");    \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         __builtin_amdgcn_s_setprio(1);                                                              \
@@ -252,30 +266,44 @@ gemm_bf16_kernel(const GemmParams p)
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");    \
         __builtin_amdgcn_sched_barrier(0);                                                          \
         issue((t) + 3, lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
-        read_frags(lA[S], lB[S]);                                                                   \
+        read_frags(S);                                                                              \
         mma();                                                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
-    issue(0, lA[0], lB[0]);
-    issue(1, lA[1], lB[1]);
-    issue(2, lA[2], lB[2]);
-    if (PINGPONG) {
-        asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
-        if (group == 1) asm volatile("s_barrier" ::: "memory");
+    if (nk <= 4) {
+        // The whole K range fits the four stages (K <= 128, always bound by the C stores): one
+        // load phase, one barrier, then the multiply; no ring, no phase groups.
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (t < nk) issue(t, lA[t], lB[t]);
+        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (t < nk) {
+                read_frags(t);
+                mma();
+            }
+    } else {
+        issue(0, lA[0], lB[0]);
+        issue(1, lA[1], lB[1]);
+        issue(2, lA[2], lB[2]);
+        if (PINGPONG) {
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");
+            if (group == 1) asm volatile("s_barrier" ::: "memory");
+        }
+        for (int kt = 0;; kt += 4) {
+            GE_BF16_STEP(0, kt);
+            if (kt + 1 >= nk) break;
+            GE_BF16_STEP(1, kt + 1);
+            if (kt + 2 >= nk) break;
+            GE_BF16_STEP(2, kt + 2);
+            if (kt + 3 >= nk) break;
+            GE_BF16_STEP(3, kt + 3);
+            if (kt + 4 >= nk) break;
+        }
+        if (PINGPONG && group == 0) asm volatile("s_barrier" ::: "memory");
     }
-    for (int kt = 0;; kt += 4) {
-        GE_BF16_STEP(0, kt);
-        if (kt + 1 >= nk) break;
-        GE_BF16_STEP(1, kt + 1);
-        if (kt + 2 >= nk) break;
-        GE_BF16_STEP(2, kt + 2);
-        if (kt + 3 >= nk) break;
-        GE_BF16_STEP(3, kt + 3);
-        if (kt + 4 >= nk) break;
-    }
-#undef GE_BF16_STEP
-    if (PINGPONG && group == 0) asm volatile("s_barrier" ::: "memory");
     // the zero-length loads of the padding tiles must have retired before the LDS is released
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -311,5 +339,7 @@ gemm_bf16_kernel(const GemmParams p)
             }
         }
 }
+
+#undef GE_BF16_STEP
 
 }  // namespace ge

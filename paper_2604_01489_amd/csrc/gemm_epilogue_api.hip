@@ -143,6 +143,8 @@ GemmParams base_params(int M, int N, int K, const void *A, int lda, const void *
     p.splitK = 1;
     p.alpha = alpha;
     p.act = act;
+    p.bytesA = 0;
+    p.bytesB = 0;
     return p;
 }
 
@@ -230,6 +232,10 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     p.groupM = choose_group_m(pl.tilesM, pl.tilesN);
     p.splitK = pl.splitK;
     p.kPerSlice = pl.kPerSlice;
+
+    // extent of the operands as the arguments describe them (last row ends at its last element)
+    p.bytesA = 2 * (((long long)batch * M - 1) * lda + K);
+    p.bytesB = 2 * (((long long)batch * K - 1) * ldb + N);
 
     const bool raw = pl.splitK > 1;
     void *ws = nullptr;

@@ -81,6 +81,15 @@ def test_bf16_batched(oracle):
     run_case(oracle, "bf16", 256, 256, 128, batch=2, lda=136, ldb=264, ldc=260, act="gelu_tanh", seed=13)
 
 
+def test_bf16_batched_small_k_many_rounds(oracle):
+    """More blocks than CUs at small K: the first round of blocks also touches the inputs of
+    later rounds (up-front reads); full and ragged tiles."""
+    _, _, _, cfg = run_case(oracle, "bf16", 512, 512, 64, batch=80, act="relu", seed=20, dist="normal")
+    assert cfg == "bf16_256x256x32_w8"
+    run_case(oracle, "bf16", 520, 264, 72, batch=70, act="gelu_tanh", alpha=0.25, seed=21, lda=80, ldb=272, ldc=268)
+    run_case(oracle, "bf16", 256, 256, 128, batch=300, act="none", with_bias=False, seed=22)
+
+
 # ------------------------------------------------------------------ split-K
 def test_splitk_auto_and_forced(oracle):
     from paper_2604_01489_amd import binding
