@@ -58,6 +58,9 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--oracle-rows", type=int, default=8192,
                     help="rows of C the CPU oracle computes (bounded sample); 0 skips the oracle")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB five times "
+                         "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this library has no multi-GPU path (--gpus must be 1)",
@@ -70,6 +73,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if args.copy_probe > 0:
+        n = args.copy_probe * (1 << 20)
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": n, "launches": 5}))
+        return 0
     binding.load()
     w = gen.WORKLOADS[args.workload]
     if w.dtype != "bf16":

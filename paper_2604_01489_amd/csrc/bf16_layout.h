@@ -31,15 +31,19 @@ GE_HD constexpr int a_slot_row(int wl, int lane)
 }
 GE_HD constexpr int a_slot_chunk(int lane) { return (lane & 3) ^ ((lane >> 4) & 3); }
 
-// 3-bit hash of a k row that rotates the 64-byte column segments of a B stage: the k rows one
-// transposing read touches are spread over all segments.
+// B stage swizzle.  One transposing read serves, per half wave, the k rows {k0..k0+3, k0+8..k0+11}
+// with 32 bytes each: the 64-byte column segments are rotated by a 3-bit hash of the row
+// (k[1:0] | k[3] << 2) and the two 32-byte halves of a segment are swapped for rows with k[3] set,
+// so those 8 x 32 bytes fall in 8 different 32-byte bank groups (measured: the version without
+// the half swap spent a quarter of its LDS cycles on bank conflicts).
 GE_HD constexpr int lds_b_hash(int k) { return (k & 3) | ((k >> 1) & 4); }
+GE_HD constexpr int lds_b_half(int k) { return ((k >> 3) & 1) << 1; }
 
 // LDS byte offset of 16-byte chunk c (8 bf16 along n) of k row k in a B stage of width BN
 template <int BN>
 GE_HD constexpr int lds_b_offset(int k, int c)
 {
-    return k * (BN * 2) + ((((c >> 2) ^ lds_b_hash(k)) & (BN / 32 - 1)) * 64) + ((c & 3) * 16);
+    return k * (BN * 2) + ((((c >> 2) ^ lds_b_hash(k)) & (BN / 32 - 1)) * 64) + (((c & 3) ^ lds_b_half(k)) * 16);
 }
 
 // k row and column chunk fetched by lane `lane` of the load that fills slab `wl` of a B stage
@@ -49,7 +53,7 @@ template <int BN>
 GE_HD constexpr int b_slot_chunk(int wl, int lane)
 {
     const int q = wl * 64 + lane, k = q / (BN / 8), pc = q % (BN / 8);
-    return ((((pc >> 2) ^ lds_b_hash(k)) & (BN / 32 - 1)) * 4) + (pc & 3);
+    return ((((pc >> 2) ^ lds_b_hash(k)) & (BN / 32 - 1)) * 4) + ((pc & 3) ^ lds_b_half(k));
 }
 
 // A fragment of the 16x16x32 MFMA: lane l reads the 16 bytes of row rowBase + l%16, chunk l/16

@@ -186,8 +186,8 @@ gemm_bf16_kernel(const GemmParams p)
     // B fragment j, read r in {0,1}: the 16-lane group g = lane/16 covers k = 8g + 4r .. +3
     // of columns wn*WTN + 16 j .. +15; lane i of the group addresses k row i/4, the 4
     // columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
-    // Stepping j moves 16 columns: bit 5 of the address for odd j, an XOR on the segment bits
-    // (6..8, hashed) for j/2; stepping r adds 4 k rows.
+    // Stepping j moves 16 columns: an XOR with 32 j on the hashed half (bit 5) and segment
+    // (bits 6..8) fields; stepping r adds 4 k rows.
     const unsigned bBase = (unsigned)b_frag_offset<BN>(wn * T::WTN, lane, 0);
 
     f32x4_t acc[TM][TN];
@@ -201,15 +201,15 @@ gemm_bf16_kernel(const GemmParams p)
     bf16x8_t fa[TM], fb[TN];
 
     // Lane bases held in registers the compiler cannot see through, so that each read below is
-    // "base + immediate": aAddr covers the A stages (offsets < 64 KB), bAddr[jj] the B stages
-    // for column pair jj.
+    // "base + immediate": aAddr covers the A stages (offsets < 64 KB), bAddr[j] the B stages
+    // for column block j.
     unsigned aAddr = (unsigned)(size_t)(GE_LDS char *)smem + aBase;
     asm volatile("" : "+v"(aAddr));
-    unsigned bAddr[TN / 2];
+    unsigned bAddr[TN];
 #pragma unroll
-    for (int jj = 0; jj < TN / 2; ++jj) {
-        bAddr[jj] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(jj * 64));
-        asm volatile("" : "+v"(bAddr[jj]));
+    for (int j = 0; j < TN; ++j) {
+        bAddr[j] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(j * 32));
+        asm volatile("" : "+v"(bAddr[j]));
     }
     auto read_frags = [&](int stage) {
 #pragma unroll
@@ -217,7 +217,7 @@ gemm_bf16_kernel(const GemmParams p)
             fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr + (unsigned)(stage * T::A_BYTES + i * 1024));
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const GE_LDS char *ptr = (const GE_LDS char *)(size_t)(bAddr[j >> 1] + (unsigned)(stage * T::B_BYTES + (j & 1) * 32));
+            const GE_LDS char *ptr = (const GE_LDS char *)(size_t)(bAddr[j] + (unsigned)(stage * T::B_BYTES));
             short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
             short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * BN * 2));
             short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
