@@ -37,6 +37,37 @@ BOUND = {
 }
 
 
+# HBM-side traffic per launch of the dominant kernel, from rocprofv3 --pmc runs of this file
+# (profiles/): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
+# reads for a plain 1 GiB device-to-device copy (FETCH_SIZE reads 0.5 KiB per KiB copied there,
+# WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
+# dropped (reported as null) as soon as the hash of csrc/ changes.
+TRAFFIC = {
+    "source_hash": "e1a532b0f5619e32",
+    "bytes_per_launch": {
+        "c3_bf16_8192_bias_gelu": (834360 * 2.0 + 263320 * 1.0) * 1024,
+        "c4_bf16_batched_512x512x64": (16480 * 2.0 + 262160 * 1.0) * 1024,
+    },
+}
+
+
+def kernel_source_hash() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2604_01489_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    if kernel_source_hash() != TRAFFIC["source_hash"]:
+        return None
+    v = TRAFFIC["bytes_per_launch"].get(workload)
+    return None if v is None else float(v)
+
+
 def sample_rows(M: int, count: int) -> np.ndarray:
     """`count` rows in blocks of 32 spread evenly over M, always including the
     first and the last block (so first/last tiles and wave sub-tiles are hit)."""
@@ -129,6 +160,7 @@ def main() -> int:
         achieved = w.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline["traffic"] = measured_traffic(args.workload)     # HBM-side bytes per launch, or null
     roofline["kernel"] = config_name
     roofline["ms_per_launch"] = round(ms_dev, 4)
 
