@@ -9,6 +9,7 @@
 
 #include "../../include/gemm_epilogue.h"
 #include "gemm_bf16_fast.h"
+#include "gemm_f32_fast.h"
 #include "gemm_generic.h"
 
 namespace {
@@ -300,16 +301,48 @@ ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, cons
     ge_status_t st = validate(M, N, K, A, lda, B, ldb, bias, (int)act, C, ldc, batch, 4);
     if (st != GE_OK) return st;
     GemmParams p = base_params(M, N, K, A, lda, B, ldb, bias, alpha, (int)act, C, ldc, batch);
+    p.bytesA = 4 * (((long long)batch * M - 1) * lda + K);
+    p.bytesB = 4 * (((long long)batch * K - 1) * ldb + N);
+    p.splitK = 1;
+    p.kPerSlice = ceil_div(K, 16) * 16;
+    hipStream_t hs = (hipStream_t)stream;
+    const char *force = std::getenv("GE_FORCE_CONFIG");
+    // direct-to-LDS kernel: 16-byte chunks of 4 floats must not straddle rows or the K / N edge
+    const bool fast = !((((uintptr_t)A) | ((uintptr_t)B)) & 15u) && !((lda | ldb | N | K) & 3) &&
+                      (long long)lda * 4 * 128 + 256 < (1ll << 31) && (long long)ldb * 4 * 16 + 1024 < (1ll << 31) &&
+                      !(force && std::strcmp(force, "generic") == 0);
+    if (fast) {
+        // 128x128 tiles once they give every other CU a block, else 64x64 (more blocks, less padding)
+        const long long t128 = (long long)ceil_div(M, 128) * ceil_div(N, 128) * batch;
+        const bool big = t128 * 2 >= kNumCU && M >= 128 && N >= 128;
+        const int bm = big ? 128 : 64;
+        p.tilesM = ceil_div(M, bm);
+        p.tilesN = ceil_div(N, bm);
+        p.groupM = choose_group_m(p.tilesM, p.tilesN);
+        const long long blocks = (long long)p.tilesM * p.tilesN * batch;
+        if (blocks > 0x7fffffffll) return GE_ERR_SHAPE;
+        const bool edge = (M % bm) || (N % bm) || (K % 16);
+        const dim3 grid((unsigned)blocks), block(256);
+        if (big) {
+            if (edge) hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<128, 128, true>), grid, block, 0, hs, p);
+            else      hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<128, 128, false>), grid, block, 0, hs, p);
+            g_last_config = "f32_128x128x16_w4";
+        } else {
+            if (edge) hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<64, 64, true>), grid, block, 0, hs, p);
+            else      hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<64, 64, false>), grid, block, 0, hs, p);
+            g_last_config = "f32_64x64x16_w4";
+        }
+        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+        return GE_OK;
+    }
     p.tilesM = ceil_div(M, 128);
     p.tilesN = ceil_div(N, 128);
     p.groupM = choose_group_m(p.tilesM, p.tilesN);
-    p.splitK = 1;
-    p.kPerSlice = ceil_div(K, 16) * 16;
     const long long blocks = (long long)p.tilesM * p.tilesN * batch;
     if (blocks > 0x7fffffffll) return GE_ERR_SHAPE;
-    hipLaunchKernelGGL(ge::gemm_f32_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL(ge::gemm_f32_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, hs, p);
     if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
-    g_last_config = "f32_128x128x16_w4";
+    g_last_config = "f32_generic_128x128x16";
     return GE_OK;
 }
 

@@ -105,8 +105,49 @@ template <int BN> void check_steps()
     }
 }
 
+// fp32 kernel: same byte geometry, a 16-byte chunk holds 4 floats; BNB = 2 * BN
+template <int BM, int BN> void check_f32()
+{
+    constexpr int BNB = 2 * BN;
+    std::vector<int> ldsA(BM * 16, -1), ldsB(16 * BN, -1);      // one int per float
+    for (int wl = 0; wl < BM * 64 / 1024; ++wl)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int row = a_slot_row(wl, lane), c = a_slot_chunk(lane), slot = wl * 1024 + lane * 16;
+            CHECK(row < BM && slot == lds_a_offset(row, c), "f32 A slot");
+            for (int e = 0; e < 4; ++e) ldsA[slot / 4 + e] = (row << 8) | (4 * c + e);
+        }
+    for (int wl = 0; wl < 16 * BN * 4 / 1024; ++wl)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int k = b_slot_k<BNB>(wl, lane), c = b_slot_chunk<BNB>(wl, lane), slot = wl * 1024 + lane * 16;
+            CHECK(k < 16 && c < BN / 4 && slot == lds_b_offset<BNB>(k, c), "f32 B slot");
+            for (int e = 0; e < 4; ++e) ldsB[slot / 4 + e] = (k << 12) | (4 * c + e);
+        }
+    for (int v : ldsA) CHECK(v != -1, "f32 A stage not covered");
+    for (int v : ldsB) CHECK(v != -1, "f32 B stage not covered");
+    for (int lane = 0; lane < 64; ++lane) {
+        const int g = lane >> 5, l32 = lane & 31;
+        for (int rowBase = 0; rowBase < BM; rowBase += 32)
+            for (int rho = 0; rho < 2; ++rho) {
+                const int off = lds_a_offset(rowBase % 64 == 0 ? rowBase + l32 : rowBase + l32, 2 * rho + g);
+                CHECK(off == lds_a_offset((rowBase / 64) * 64 + l32, 2 * rho + g) + ((rowBase % 64) / 32) * 2048, "f32 A step");
+                for (int e = 0; e < 4; ++e)
+                    CHECK(ldsA[off / 4 + e] == (((rowBase + l32) << 8) | (8 * rho + 4 * g + e)), "f32 A fragment");
+            }
+        for (int colBase = 0; colBase < BN; colBase += 32)
+            for (int rho = 0; rho < 2; ++rho)
+                for (int e = 0; e < 4; ++e) {
+                    const int k = 8 * rho + 4 * g + e, n = colBase + l32;
+                    const int off = lds_b_offset<BNB>(k, n >> 2) + (n & 3) * 4;
+                    CHECK(off % 4 == 0 && off + 4 <= 16 * BN * 4, "f32 B address");
+                    CHECK(ldsB[off / 4] == ((k << 12) | n), "f32 B fragment");
+                }
+    }
+}
+
 int main()
 {
+    check_f32<128, 128>();
+    check_f32<64, 64>();
     check_steps<256>();
     check_steps<128>();
     check_a<256>();

@@ -65,6 +65,22 @@ def test_f32(oracle, M, N, K):
     run_case(oracle, "f32", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K + 1)
 
 
+def test_f32_fast_kernels(oracle):
+    """direct-to-LDS fp32 kernels: 64x64 and 128x128 tiles, full and ragged, several K tiles"""
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 256, act="none", with_bias=False, seed=30)
+    assert cfg == "f32_64x64x16_w4"
+    _, _, _, cfg = run_case(oracle, "f32", 1024, 2048, 64, alpha=0.5, act="gelu_tanh", seed=31)
+    assert cfg == "f32_128x128x16_w4"
+    _, _, _, cfg = run_case(oracle, "f32", 1100, 1900, 68, alpha=0.5, act="relu", seed=32, lda=72, ldb=1904, ldc=1901)
+    assert cfg == "f32_128x128x16_w4"
+    _, _, _, cfg = run_case(oracle, "f32", 300, 96, 40, alpha=1.0, act="none", seed=33)
+    assert cfg == "f32_64x64x16_w4"
+    _, _, _, cfg = run_case(oracle, "f32", 72, 200, 20, batch=5, act="relu", seed=34)
+    assert cfg == "f32_64x64x16_w4"
+    _, _, _, cfg = run_case(oracle, "f32", 129, 130, 31, act="none", seed=35)
+    assert cfg == "f32_generic_128x128x16"
+
+
 def test_f32_layouts(oracle):
     run_case(oracle, "f32", 200, 136, 72, lda=76, ldb=140, ldc=137, act="relu", seed=3)
     run_case(oracle, "f32", 200, 136, 72, lda=75, ldb=139, ldc=137, act="relu", seed=4)
