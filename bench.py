@@ -43,7 +43,7 @@ BOUND = {
 # WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
 # dropped (reported as null) as soon as the hash of csrc/ changes.
 TRAFFIC = {
-    "source_hash": "7a4189a0e7f400b1",
+    "source_hash": "37dc9d1e20e834d5",
     "bytes_per_launch": {
         "c3_bf16_8192_bias_gelu": (814763 * 2.0 + 263117 * 1.0) * 1024,
         "c4_bf16_batched_512x512x64": (16484 * 2.0 + 262152 * 1.0) * 1024,
@@ -51,14 +51,47 @@ TRAFFIC = {
 }
 
 
+# the sources the GEMM kernels and their dispatch are built from (the probes are not among them)
+KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h",
+                  "gemm_epilogue_api.hip")
+
+
 def kernel_source_hash() -> str:
-    import glob
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2604_01489_amd", "csrc", "*"))):
-        with open(f, "rb") as fh:
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_01489_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
+
+
+def measured_ceilings(torch, binding, dA, stream):
+    """What the device itself sustains, measured in this run with HIP events: a register-resident
+    bf16 MFMA loop fed with the workload's own operand values (the clock is power-managed and
+    depends on them), and a streaming fp32 store of 256 MiB."""
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    blocks, iters = 512, 40000
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device=dA.device)
+    operands = dA.reshape(-1)[:32768]
+    t = timed(lambda: binding.probe_mfma_bf16(operands, sink, blocks, iters, stream=stream), 3)
+    mfma = blocks * 8 * iters * 16 * (2.0 * 16 * 16 * 32) / t / 1e12
+    buf = torch.empty(64 << 20, dtype=torch.float32, device=dA.device)
+    t = timed(lambda: binding.probe_store_f32(buf, 1.0, stream=stream), 20)
+    store = buf.numel() * 4 / t / 1e9
+    return {"mfma_bf16_tflops": round(mfma, 1), "store_gbs": round(store, 1),
+            "how": "v_mfma_f32_16x16x32_bf16 loop, 512 blocks x 8 waves, operands = first 64 KiB of A; "
+                   "fp32 store of 256 MiB, 16 B per lane"}
 
 
 def measured_traffic(workload: str):
@@ -89,6 +122,10 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--oracle-rows", type=int, default=8192,
                     help="rows of C the CPU oracle computes (bounded sample); 0 skips the oracle")
+    ap.add_argument("--rotate", type=int, default=1, metavar="R",
+                    help="cycle through R copies of A, B and C (R x the footprint) so that no launch finds "
+                         "its inputs in the 256 MB memory-side cache")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling probes")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times "
                          "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -130,12 +167,19 @@ def main() -> int:
     dbias = None if bias is None else torch.from_numpy(bias).to(dev)
     dC = torch.empty(batch, M, N, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
+    sets = [(dA, dB, dC)]
+    for _ in range(1, max(1, args.rotate)):
+        sets.append((dA.clone(), dB.clone(), torch.empty_like(dC)))
+    calls = [0]
 
     def step():
-        binding.gemm_epilogue_bf16(M, N, K, dA, K, dB, N, dbias, w.alpha, w.act, dC, N, batch, stream=stream)
+        a, b, c = sets[calls[0] % len(sets)]
+        calls[0] += 1
+        binding.gemm_epilogue_bf16(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
 
     for _ in range(args.warmup):
         step()
+    calls[0] = 0
     torch.cuda.synchronize()
     ev0 = torch.cuda.Event(enable_timing=True)
     ev1 = torch.cuda.Event(enable_timing=True)
@@ -163,6 +207,11 @@ def main() -> int:
     roofline["traffic"] = measured_traffic(args.workload)     # HBM-side bytes per launch, or null
     roofline["kernel"] = config_name
     roofline["ms_per_launch"] = round(ms_dev, 4)
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measured_ceilings(torch, binding, dA, stream)
+        top = ceilings["mfma_bf16_tflops"] if bound == "mfma" else ceilings["store_gbs"]
+        roofline["frac_of_measured"] = round(achieved / top, 4)
 
     # ---- CPU oracle on a bounded sample of the same workload, and parity on that sample
     cpu_baseline = None
@@ -207,6 +256,7 @@ def main() -> int:
                    "kernel": config_name},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": roofline,
+        "ceilings": ceilings,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }

@@ -20,7 +20,8 @@ GE_OK = 0
 
 SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
-           "ge_release_workspace", "ge_status_string", "ge_last_config")
+           "ge_release_workspace", "ge_status_string", "ge_last_config",
+           "ge_probe_mfma_bf16", "ge_probe_store_f32")
 
 _lib = None
 
@@ -60,6 +61,10 @@ def load():
     lib.ge_status_string.argtypes = [c_int]
     lib.ge_last_config.restype = ctypes.c_char_p
     lib.ge_last_config.argtypes = []
+    lib.ge_probe_mfma_bf16.restype = c_int
+    lib.ge_probe_mfma_bf16.argtypes = [c_void, c_void, c_int, c_int, c_void]
+    lib.ge_probe_store_f32.restype = c_int
+    lib.ge_probe_store_f32.argtypes = [c_void, c_size, c_float, c_void]
     _lib = lib
     return lib
 
@@ -131,6 +136,18 @@ def auto_split_k(M, N, K, batch=1) -> int:
 
 def release_workspace():
     _check(load().ge_release_workspace())
+
+
+def probe_mfma_bf16(operands, sink, blocks, iters, stream=None):
+    """Measured ceiling: register-resident bf16 MFMA loop (include/ge_probes.h)."""
+    _require_device(operands, sink)
+    _check(load().ge_probe_mfma_bf16(_ptr(operands), _ptr(sink), blocks, iters, _stream_handle(stream)))
+
+
+def probe_store_f32(dst, value=1.0, stream=None):
+    """Measured ceiling: streaming fp32 store over all of ``dst`` (include/ge_probes.h)."""
+    _require_device(dst)
+    _check(load().ge_probe_store_f32(_ptr(dst), dst.numel(), value, _stream_handle(stream)))
 
 
 def _require_device(*tensors):

@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_epilogue.so")
-SOURCES = ["gemm_epilogue_api.hip"]
+SOURCES = ["gemm_epilogue_api.hip", "ge_probes.hip"]
 # packed fp32 instructions are kept off: some of their forms have misbehaved on this hardware
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -34,7 +34,8 @@ def library_is_current() -> bool:
         return False
     t = os.path.getmtime(LIB)
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
-    deps.append(os.path.join(os.path.dirname(HERE), "include", "gemm_epilogue.h"))
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    deps += [os.path.join(inc, f) for f in os.listdir(inc)]
     return all(os.path.getmtime(d) <= t for d in deps)
 
 

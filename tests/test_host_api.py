@@ -19,7 +19,8 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "gemm_epilogue.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*)\s*\(", header))
     assert declared == set(binding.SYMBOLS), declared ^ set(binding.SYMBOLS)
