@@ -25,7 +25,12 @@ _LIB = os.path.join(_HERE, "libgemm_epilogue_oracle.so")
 ACT = {"none": 0, "relu": 1, "gelu_tanh": 2}
 _KIND = {np.dtype(np.float64): 0, np.dtype(np.float32): 1, np.dtype(np.uint16): 2}
 
+_FUSED_SRC = os.path.join(_HERE, "gemm_fused_oracle.c")
+_FUSED_LIB = os.path.join(_HERE, "libgemm_fused_oracle.so")
+OUT = {"f64": 0, "f32": 1, "bf16": 2}
+
 _lib = None
+_fused = None
 
 
 def compile_source(src: str, out: str) -> str:
@@ -37,9 +42,11 @@ def compile_source(src: str, out: str) -> str:
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle if it is missing or older than its source. Returns the .so path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        compile_source(_SRC, _LIB)
+    """Compile the oracles that are missing or older than their source. Returns the path of the
+    plain operator's library."""
+    for src, lib in ((_SRC, _LIB), (_FUSED_SRC, _FUSED_LIB)):
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+            compile_source(src, lib)
     return _LIB
 
 
@@ -125,3 +132,96 @@ def gemm_epilogue(A, B, bias=None, alpha=1.0, act="none", *, M=None, N=None, K=N
         return C
     C = C.reshape(batch, M, N)
     return C[0] if np.ndim(A) == 2 else C
+
+
+# ---------------------------------------------------------------------------------------------
+# the widened operator: stored-transposed operands, row scale, residual, clamp, rounded output
+# ---------------------------------------------------------------------------------------------
+def _bind_fused(lib):
+    c = ctypes
+    lib.oracle_gemm_fused.restype = c.c_int
+    lib.oracle_gemm_fused.argtypes = [
+        c.c_int, c.c_int, c.c_int, c.c_int,
+        c.c_void_p, c.c_long, c.c_int, c.c_void_p, c.c_long, c.c_int, c.c_int,
+        c.c_double, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_long, c.c_int, c.c_double,
+        c.c_int, c.c_double, c.c_double, c.c_int,
+        c.c_void_p, c.c_long]
+    lib.oracle_round_f32_to_bf16.restype = c.c_float
+    lib.oracle_round_f32_to_bf16.argtypes = [c.c_float]
+    return lib
+
+
+def use_fused_library(path: str | None) -> None:
+    """As ``use_library`` for the widened operator's oracle."""
+    global _fused
+    _fused = None if path is None else _bind_fused(ctypes.CDLL(path))
+
+
+def _load_fused():
+    global _fused
+    if _fused is None:
+        build()
+        _fused = _bind_fused(ctypes.CDLL(_FUSED_LIB))
+    return _fused
+
+
+def round_f32_to_bf16(x: float) -> float:
+    """The oracle's fp32 -> bf16 rounding (nearest, ties to even), as a float."""
+    return float(_load_fused().oracle_round_f32_to_bf16(float(x)))
+
+
+def gemm_fused(M, N, K, A, B, *, batch=1, transA=False, transB=False, lda=None, ldb=None,
+               alpha=1.0, row_scale=None, bias=None, residual=None, ldr=None, beta=1.0,
+               act="none", clamp=None, out="f64"):
+    """Reference for ``round_out(clamp(act(alpha*row_scale[m]*(opA(A) @ opB(B)) + bias[n] + beta*R)))``.
+
+    ``M, N, K`` are the logical sizes.  ``A`` holds ``batch`` matrices stored M x lda
+    (``transA=False``) or K x lda (``transA=True``), ``B`` K x ldb or N x ldb, ``residual`` M x ldr;
+    any array shape is accepted, the C-order content is the storage.  Leading dimensions default
+    to packed.  A and B share a dtype among float64, float32, uint16 (bf16 bits); the residual may
+    be any of the three.  ``clamp`` is ``(lo, hi)`` or None.  Returns fp64 values of shape
+    [batch, M, N] (already rounded to fp32 / bf16 when ``out`` says so).
+    """
+    lib = _load_fused()
+    A = np.ascontiguousarray(A).ravel()
+    B = np.ascontiguousarray(B).ravel()
+    if A.dtype != B.dtype or A.dtype not in _KIND:
+        raise TypeError("A and B must share a dtype among float64, float32, uint16(bf16 bits)")
+    lda = (M if transA else K) if lda is None else lda
+    ldb = (K if transB else N) if ldb is None else ldb
+    if A.size < batch * (K if transA else M) * lda or B.size < batch * (N if transB else K) * ldb:
+        raise ValueError("operand buffer too small")
+
+    def vec(x, n, name):
+        if x is None:
+            return None, None
+        v = np.ascontiguousarray(np.asarray(x), dtype=np.float64)
+        if v.shape != (n,):
+            raise ValueError(f"{name} must have length {n}")
+        return v, v.ctypes.data_as(ctypes.c_void_p)
+
+    rs_keep, rs_p = vec(row_scale, M, "row_scale")
+    bias_keep, bias_p = vec(bias, N, "bias")
+    if residual is not None:
+        R = np.ascontiguousarray(residual).ravel()
+        if R.dtype not in _KIND:
+            raise TypeError("residual dtype")
+        ldr = N if ldr is None else ldr
+        if R.size < batch * M * ldr:
+            raise ValueError("residual buffer too small")
+        r_p, r_kind = R.ctypes.data_as(ctypes.c_void_p), _KIND[R.dtype]
+    else:
+        r_p, r_kind, ldr = None, 0, 0
+    lo, hi = (-np.inf, np.inf) if clamp is None else clamp
+    C = np.full(batch * M * N, np.nan, dtype=np.float64)
+    rc = lib.oracle_gemm_fused(
+        int(M), int(N), int(K), int(batch),
+        A.ctypes.data_as(ctypes.c_void_p), int(lda), int(bool(transA)),
+        B.ctypes.data_as(ctypes.c_void_p), int(ldb), int(bool(transB)), _KIND[A.dtype],
+        float(alpha), rs_p, bias_p, r_p, int(ldr), r_kind, float(beta),
+        ACT[act], float(lo), float(hi), OUT[out],
+        C.ctypes.data_as(ctypes.c_void_p), int(N))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return C.reshape(batch, M, N)
