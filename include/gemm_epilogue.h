@@ -59,7 +59,8 @@ typedef enum {
     GE_ERR_ALIGN = 5,      /* a pointer is not aligned to its element size          */
     GE_ERR_WORKSPACE = 6,  /* split-K workspace missing, too small or not allocatable */
     GE_ERR_LAUNCH = 7,     /* the HIP runtime refused a launch                      */
-    GE_ERR_CONFIG = 8      /* unknown plan / forced configuration does not fit      */
+    GE_ERR_CONFIG = 8,     /* unknown plan / forced configuration does not fit      */
+    GE_ERR_EPILOGUE = 9    /* clamp_lo > clamp_hi (or NaN), or an unknown element type */
 } ge_status_t;
 
 /* How the work is decomposed (the paper's design choice "work decomposition and
@@ -120,6 +121,70 @@ ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K,
                                   ge_plan_t plan, int split_k,
                                   void *workspace, size_t workspace_bytes,
                                   void *stream);
+
+/*
+ * The widened operator (bf16 operands, fp32 accumulation):
+ *
+ *     P[b][m,n] = sum_{k<K} opA(A[b])[m,k] * opB(B[b])[k,n]
+ *     v         = alpha * row_scale[m] * P[b][m,n] + bias[n] + beta * R[b][m,n]
+ *     C[b][m,n] = round( min(max(act(v), clamp_lo), clamp_hi) )
+ *
+ * The consumer chain after the product is what the Level-2 optimisation prompt
+ * asks to fold into the producer's writeback ("Fusion": bias / add / scale /
+ * activation; "clamp" in its list of consumer operations): computed on the
+ * accumulator in registers, C written once.  opA / opB choose how an operand is
+ * STORED, not what is computed (the strided, transposed operand views of the
+ * initial CuTe kernel, Fig. simple_cute): the matrix instruction sees the same
+ * fragments either way.  With A = I and row_scale = d the operator is
+ * diag(d) * B, the paper's diagonal-matrix multiply.  The order of the chain,
+ * the broadcast axes and beta are this library's reading; the paper names the
+ * operations only.
+ *
+ *   M, N, K, batch >= 1
+ *   A, lda, transA    device, bf16 bits.  transA = 0: A[m,k] = A[m*lda + k], lda >= K;
+ *                     transA != 0: A[m,k] = A[k*lda + m], lda >= M
+ *   B, ldb, transB    device, bf16 bits.  transB = 0: B[k,n] = B[k*ldb + n], ldb >= N;
+ *                     transB != 0: B[k,n] = B[n*ldb + k], ldb >= K
+ *   alpha             scale of the product
+ *   row_scale         device, fp32[M], or NULL (= 1); multiplies the scaled product of
+ *                     row m, not the bias; shared by every batch
+ *   bias              device, fp32[N], or NULL; shared by every batch
+ *   R, ldr, r_type    device residual [M, ldr >= N] per batch of r_type elements, or NULL;
+ *   beta              scale of the residual (ignored when R is NULL)
+ *   act               activation, applied after the residual
+ *   clamp_lo/hi       clamp_lo <= clamp_hi, applied after the activation;
+ *                     -INFINITY / +INFINITY switch a side off
+ *   C, ldc, c_type    device result [M, ldc >= N] per batch; GE_DTYPE_BF16 rounds the fp32
+ *                     value to nearest-even.  Only C[m, 0..N) is written
+ *   plan, split_k, workspace, workspace_bytes   as for gemm_epilogue_bf16_ex
+ * Batches are packed: A advances by (transA ? K : M)*lda elements, B by
+ * (transB ? N : K)*ldb, R by M*ldr, C by M*ldc.  C must not overlap any input.
+ *
+ * `args` is a HOST pointer, read before the call returns.  The direct-to-LDS
+ * kernels need A and B 16-byte aligned, lda and ldb multiples of 8 and the row
+ * payloads (K or M for A, N or K for B) multiples of 8, plus for bf16 output an
+ * even N and ldc and a 4-byte aligned C; any other legal argument list takes a
+ * guarded kernel with the same result contract.
+ * Errors: as gemm_epilogue_bf16, plus GE_ERR_EPILOGUE.
+ */
+typedef enum { GE_DTYPE_F32 = 0, GE_DTYPE_BF16 = 1 } ge_dtype_t;
+
+typedef struct ge_fused_args {
+    int M, N, K, batch;
+    const uint16_t *A; int lda; int transA;
+    const uint16_t *B; int ldb; int transB;
+    float alpha;
+    const float *row_scale;
+    const float *bias;
+    const void *R; int ldr; ge_dtype_t r_type; float beta;
+    ge_act_t act;
+    float clamp_lo, clamp_hi;
+    void *C; int ldc; ge_dtype_t c_type;
+    ge_plan_t plan; int split_k;
+    void *workspace; size_t workspace_bytes;
+} ge_fused_args_t;
+
+ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
 
 /* Bytes of split-K workspace the bf16 call needs for this shape with `plan` and
  * `split_k` as above (0 when the chosen plan is direct).  Host only. */

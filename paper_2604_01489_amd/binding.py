@@ -21,7 +21,28 @@ GE_OK = 0
 SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
            "ge_release_workspace", "ge_status_string", "ge_last_config",
-           "ge_probe_mfma_bf16", "ge_probe_store_f32")
+           "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused")
+
+DTYPE = {"f32": 0, "bf16": 1}
+
+
+class FusedArgs(ctypes.Structure):
+    """Mirror of ``ge_fused_args_t`` (include/gemm_epilogue.h)."""
+    _fields_ = [
+        ("M", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int), ("batch", ctypes.c_int),
+        ("A", ctypes.c_void_p), ("lda", ctypes.c_int), ("transA", ctypes.c_int),
+        ("B", ctypes.c_void_p), ("ldb", ctypes.c_int), ("transB", ctypes.c_int),
+        ("alpha", ctypes.c_float),
+        ("row_scale", ctypes.c_void_p),
+        ("bias", ctypes.c_void_p),
+        ("R", ctypes.c_void_p), ("ldr", ctypes.c_int), ("r_type", ctypes.c_int), ("beta", ctypes.c_float),
+        ("act", ctypes.c_int),
+        ("clamp_lo", ctypes.c_float), ("clamp_hi", ctypes.c_float),
+        ("C", ctypes.c_void_p), ("ldc", ctypes.c_int), ("c_type", ctypes.c_int),
+        ("plan", ctypes.c_int), ("split_k", ctypes.c_int),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
 
 _lib = None
 
@@ -61,6 +82,8 @@ def load():
     lib.ge_status_string.argtypes = [c_int]
     lib.ge_last_config.restype = ctypes.c_char_p
     lib.ge_last_config.argtypes = []
+    lib.gemm_epilogue_bf16_fused.restype = c_int
+    lib.gemm_epilogue_bf16_fused.argtypes = [ctypes.POINTER(FusedArgs), c_void]
     lib.ge_probe_mfma_bf16.restype = c_int
     lib.ge_probe_mfma_bf16.argtypes = [c_void, c_void, c_int, c_int, c_void]
     lib.ge_probe_store_f32.restype = c_int
@@ -84,6 +107,10 @@ def _check(status: int):
 
 def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _addr(t):
+    return None if t is None else int(t.data_ptr())
 
 
 def _stream_handle(stream):
@@ -136,6 +163,46 @@ def auto_split_k(M, N, K, batch=1) -> int:
 
 def release_workspace():
     _check(load().ge_release_workspace())
+
+
+def fused_args(M, N, K, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, *, batch=1, transA=False, transB=False,
+               alpha=1.0, row_scale_ptr=None, bias_ptr=None, R_ptr=None, ldr=0, r_type="f32", beta=1.0,
+               act="none", clamp=None, c_type="f32", plan="auto", split_k=0, workspace_ptr=None,
+               workspace_bytes=0) -> FusedArgs:
+    """Fill a ``ge_fused_args_t`` from raw addresses (no checks: that is the library's job)."""
+    lo, hi = (-float("inf"), float("inf")) if clamp is None else clamp
+    return FusedArgs(M, N, K, batch, A_ptr, lda, int(bool(transA)), B_ptr, ldb, int(bool(transB)),
+                     alpha, row_scale_ptr, bias_ptr, R_ptr, ldr, DTYPE[r_type], beta,
+                     ACT[act] if isinstance(act, str) else int(act), lo, hi,
+                     C_ptr, ldc, DTYPE[c_type] if isinstance(c_type, str) else int(c_type),
+                     PLAN[plan] if isinstance(plan, str) else int(plan), split_k,
+                     workspace_ptr, workspace_bytes)
+
+
+def raw_fused(args: FusedArgs, stream_handle=None) -> int:
+    """The status code of ``gemm_epilogue_bf16_fused`` (for argument-error tests)."""
+    return int(load().gemm_epilogue_bf16_fused(ctypes.byref(args), stream_handle))
+
+
+def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA=False, transB=False,
+                             alpha=1.0, row_scale=None, bias=None, residual=None, ldr=0, beta=1.0,
+                             act="none", clamp=None, plan="auto", split_k=0, workspace=None, stream=None):
+    """``C = round(clamp(act(alpha*row_scale[m]*(opA(A) @ opB(B)) + bias[n] + beta*R)))`` on device
+    tensors.  A and B hold bf16 bits (int16/uint16/bfloat16 tensors); the output type follows
+    ``C.dtype`` (float32 or bfloat16/int16), the residual's its tensor's."""
+    import torch
+    _require_device(A, B, C, row_scale, bias, residual, workspace)
+
+    def kind(t):
+        return "f32" if t.dtype == torch.float32 else "bf16"
+
+    args = fused_args(M, N, K, _addr(A), lda, _addr(B), ldb, _addr(C), ldc, batch=batch, transA=transA,
+                      transB=transB, alpha=alpha, row_scale_ptr=_addr(row_scale), bias_ptr=_addr(bias),
+                      R_ptr=_addr(residual), ldr=ldr, r_type=kind(residual) if residual is not None else "f32",
+                      beta=beta, act=act, clamp=clamp, c_type=kind(C), plan=plan, split_k=split_k,
+                      workspace_ptr=_addr(workspace),
+                      workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+    _check(load().gemm_epilogue_bf16_fused(ctypes.byref(args), _stream_handle(stream)))
 
 
 def probe_mfma_bf16(operands, sink, blocks, iters, stream=None):

@@ -1,0 +1,38 @@
+// Host-side pieces shared by the translation units of the library: plan selection, the
+// library-owned split-K workspace and the last-configuration string.  Defined in
+// gemm_epilogue_api.hip.
+#pragma once
+#include <stddef.h>
+
+#include "../../include/gemm_epilogue.h"
+#include "ge_device.h"
+
+namespace ge_host {
+
+using ge::GemmParams;
+
+constexpr int kNumCU = 256;          // MI355X
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// ---- shape -> plan -------------------------------------------------------
+enum TileKind { TILE_256 = 0, TILE_128 = 1, TILE_GENERIC = 2 };
+
+struct Plan {
+    TileKind tile;
+    int bm, bn, bk;
+    int tilesM, tilesN;
+    int splitK;      // >= 1
+    int kPerSlice;
+    bool edge;
+};
+
+extern thread_local const char *g_last_config;
+
+int choose_split(long long tiles, int K);
+ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out);
+size_t partial_bytes(int M, int N, int batch, int splitK);
+int choose_group_m(int tilesM, int tilesN);
+ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void **out);
+
+}  // namespace ge_host

@@ -102,13 +102,23 @@ struct Bf16Tile {
 // EDGE: the tile may hang over M, N or the K range (loads are zero filled through
 // the buffer bounds check, stores are masked).  RAW: write fp32 partial sums for
 // the split-K reduction (no scale, bias or activation) instead of C.
-template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT>
+//
+// TA / TB: the operand is stored transposed (A as K x M, B as N x K).  Only the staging differs:
+// an operand whose rows run along k uses the "k-contiguous" stage (rows of 64 bytes, fragments
+// by ds_read_b128), one whose rows run along m or n the "k-strided" stage (k rows of the tile
+// width, fragments by transposing reads); the matrix instruction sees the same fragments.
+// FUSED: the run-time epilogue of the widened operator (row scale, residual, clamp, fp32 or bf16
+// output) instead of the compile-time scale/bias/activation.
+template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT, bool TA = false, bool TB = false,
+          bool FUSED = false>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmParams p)
 {
     using T = Bf16Tile<BM, BN, WM, WN>;
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
+    static_assert(!(RAW && FUSED), "partial tiles carry no epilogue");
+    static_assert((BM & (BM - 1)) == 0 && ((T::WTM / 32) & (T::WTM / 32 - 1)) == 0, "k-strided A stage");
 
     // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages
     // and, from a second lane base, the B stages each lie within the 64 KB immediate range), so
@@ -125,35 +135,53 @@ gemm_bf16_kernel(const GemmParams p)
     const int kLen = min(p.K - kBegin, p.kPerSlice);
     const int nk = (kLen + BK - 1) / BK;
 
-    const long long offA = 2 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda + kBegin);
-    const long long offB = 2 * ((long long)tc.b * p.strideB + (long long)kBegin * p.ldb + n0);
+    const long long offA = 2 * ((long long)tc.b * p.strideA +
+                                (TA ? (long long)kBegin * p.lda + m0 : (long long)m0 * p.lda + kBegin));
+    const long long offB = 2 * ((long long)tc.b * p.strideB +
+                                (TB ? (long long)n0 * p.ldb + kBegin : (long long)kBegin * p.ldb + n0));
     const char *gA = (const char *)p.A + offA;
     const char *gB = (const char *)p.B + offB;
 
     // ---- per-lane global offsets of the 16-byte chunks this lane fetches (inverse of
-    // the LDS layout: slot -> (row, chunk)) -------------------------------------------
+    // the LDS layout: slot -> (row, chunk)); kA / kB hold what the K-edge mask compares:
+    // the chunk along k (k-contiguous stage) or the k row (k-strided stage) ---------------
     unsigned voffA[T::A_LOADS], voffB[T::B_LOADS];
-    int chA[T::A_LOADS], rowB[T::B_LOADS];
+    int kA[T::A_LOADS], kB[T::B_LOADS];
 #pragma unroll
     for (int j = 0; j < T::A_LOADS; ++j) {
-        const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);   // 1 KB slab = 16 rows
-        chA[j] = c;
-        voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
-        if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
+        if (!TA) {
+            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);   // 1 KB slab = 16 rows
+            kA[j] = c * 8;
+            voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
+            if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
+        } else {
+            const int k = b_slot_k<BM>(j * NW + w, lane), c = b_slot_chunk<BM>(j * NW + w, lane);
+            kA[j] = k;
+            voffA[j] = (unsigned)k * (unsigned)p.lda * 2u + (unsigned)c * 16u;
+            if (EDGE && m0 + c * 8 >= p.M) voffA[j] = OOB_OFFSET;
+        }
     }
 #pragma unroll
     for (int j = 0; j < T::B_LOADS; ++j) {
-        const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
-        rowB[j] = k;
-        voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
-        if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
+        if (!TB) {
+            const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
+            kB[j] = k;
+            voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
+            if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
+        } else {
+            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);
+            kB[j] = c * 8;
+            voffB[j] = (unsigned)row * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
+            if (EDGE && n0 + row >= p.N) voffB[j] = OOB_OFFSET;
+        }
     }
 
     // Tiles past the end of the K range are fetched through a zero-length resource:
     // every lane is out of range, nothing is read and zeros land in a stage nobody
     // consumes, so the number of loads in flight is the same in every step.
     auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
-        const long long stepA = (long long)kt * (BK * 2), stepB = (long long)kt * BK * p.ldb * 2;
+        const long long stepA = TA ? (long long)kt * BK * p.lda * 2 : (long long)kt * (BK * 2);
+        const long long stepB = TB ? (long long)kt * (BK * 2) : (long long)kt * BK * p.ldb * 2;
         // Full tiles: every offset lies inside the operand by construction, and the exact extent
         // (ten scalar instructions per step, measured at 1-3 % of the 8192^3 run) is skipped.
         // Edge tiles: the resource ends where the operand ends, so a lane that is not masked for
@@ -169,26 +197,29 @@ gemm_bf16_kernel(const GemmParams p)
 #pragma unroll
         for (int j = 0; j < T::A_LOADS; ++j) {
             unsigned v = voffA[j];
-            if (EDGE && chA[j] * 8 >= kLeft) v = OOB_OFFSET;
+            if (EDGE && kA[j] >= kLeft) v = OOB_OFFSET;
             lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
         }
 #pragma unroll
         for (int j = 0; j < T::B_LOADS; ++j) {
             unsigned v = voffB[j];
-            if (EDGE && rowB[j] >= kLeft) v = OOB_OFFSET;
+            if (EDGE && kB[j] >= kLeft) v = OOB_OFFSET;
             lds_dma16(rB, (unsigned)(size_t)(dB + (j * NW + w) * 1024), v);
         }
     };
 
     // ---- per-lane LDS read addresses ---------------------------------------------
-    // A fragment i: rows wm*WTM + 16 i + lane%16, k chunk lane/16 (k = 8*(lane/16) + e).
-    const unsigned aBase = (unsigned)a_frag_offset(wm * T::WTM, lane);
-    // B fragment j, read r in {0,1}: the 16-lane group g = lane/16 covers k = 8g + 4r .. +3
-    // of columns wn*WTN + 16 j .. +15; lane i of the group addresses k row i/4, the 4
-    // columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
+    // k-contiguous stage, fragment i: rows base + 16 i + lane%16, k chunk lane/16
+    // (k = 8*(lane/16) + e): one ds_read_b128, stepping i adds 1 KB.
+    // k-strided stage, fragment j, read r in {0,1}: the 16-lane group g = lane/16 covers
+    // k = 8g + 4r .. +3 of columns base + 16 j .. +15; lane i of the group addresses k row i/4,
+    // the 4 columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
     // Stepping j moves 16 columns: an XOR with 32 j on the hashed half (bit 5) and segment
     // (bits 6..8) fields; stepping r adds 4 k rows.
-    const unsigned bBase = (unsigned)b_frag_offset<BN>(wn * T::WTN, lane, 0);
+    const unsigned aBase = TA ? (unsigned)b_frag_offset<BM>(wm * T::WTM, lane, 0)
+                              : (unsigned)a_frag_offset(wm * T::WTM, lane);
+    const unsigned bBase = TB ? (unsigned)a_frag_offset(wn * T::WTN, lane)
+                              : (unsigned)b_frag_offset<BN>(wn * T::WTN, lane, 0);
 
     f32x4_t acc[TM][TN];
 #pragma unroll
@@ -201,27 +232,37 @@ gemm_bf16_kernel(const GemmParams p)
     bf16x8_t fa[TM], fb[TN];
 
     // Lane bases held in registers the compiler cannot see through, so that each read below is
-    // "base + immediate": aAddr covers the A stages (offsets < 64 KB), bAddr[j] the B stages
-    // for column block j.
-    unsigned aAddr = (unsigned)(size_t)(GE_LDS char *)smem + aBase;
-    asm volatile("" : "+v"(aAddr));
-    unsigned bAddr[TN];
+    // "base + immediate": one base covers every fragment of a k-contiguous operand, a
+    // k-strided operand needs one per 16-column block (its stepping is an XOR, not an add).
+    constexpr int NA = TA ? TM : 1, NB = TB ? 1 : TN;
+    unsigned aAddr[NA], bAddr[NB];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int i = 0; i < NA; ++i) {
+        aAddr[i] = (unsigned)(size_t)(GE_LDS char *)smem + (aBase ^ (unsigned)(i * 32));
+        asm volatile("" : "+v"(aAddr[i]));
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
         bAddr[j] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(j * 32));
         asm volatile("" : "+v"(bAddr[j]));
     }
+    auto read_strided = [&](unsigned addr, int rowBytes) {
+        const GE_LDS char *ptr = (const GE_LDS char *)(size_t)addr;
+        short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
+        short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * rowBytes));
+        short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8_t, both);
+    };
     auto read_frags = [&](int stage) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr + (unsigned)(stage * T::A_BYTES + i * 1024));
+        for (int i = 0; i < TM; ++i) {
+            if (TA) fa[i] = read_strided(aAddr[TA ? i : 0] + (unsigned)(stage * T::A_BYTES), BM * 2);
+            else fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr[0] + (unsigned)(stage * T::A_BYTES + i * 1024));
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const GE_LDS char *ptr = (const GE_LDS char *)(size_t)(bAddr[j] + (unsigned)(stage * T::B_BYTES));
-            short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)ptr);
-            short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)(ptr + 4 * BN * 2));
-            short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            fb[j] = __builtin_bit_cast(bf16x8_t, both);
+            if (TB) fb[j] = *(const GE_LDS bf16x8_t *)(size_t)(bAddr[0] + (unsigned)(stage * T::B_BYTES + j * 1024));
+            else fb[j] = read_strided(bAddr[TB ? 0 : j] + (unsigned)(stage * T::B_BYTES), BN * 2);
         }
     };
     // accumulator register r of lane l is C[m = 16 i + 4*(l/16) + r][n = 16 j + l%16]
@@ -308,36 +349,40 @@ gemm_bf16_kernel(const GemmParams p)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue in registers ----------------------------------------------------
-    float *cBase;
-    long long ldc;
-    if (RAW) {
-        ldc = p.N;
-        cBase = p.C + (long long)tc.s * p.sliceStride + (long long)tc.b * p.M * p.N;
-    } else {
-        ldc = p.ldc;
-        cBase = p.C + (long long)tc.b * p.strideC;
-    }
     const int rowLane = m0 + wm * T::WTM + 4 * (lane >> 4);
     const int colLane = n0 + wn * T::WTN + (lane & 15);
-    float bv[TN];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = colLane + j * 16;
-        bv[j] = (!RAW && p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
-    }
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int m = rowLane + i * 16 + r;
-            float *rowPtr = cBase + (long long)m * ldc + colLane;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                float v = acc[i][j][r];
-                if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
-                if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
-            }
+    if constexpr (FUSED) {
+        fused_epilogue_16x16<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane, lane);
+    } else {
+        float *cBase;
+        long long ldc;
+        if (RAW) {
+            ldc = p.N;
+            cBase = p.C + (long long)tc.s * p.sliceStride + (long long)tc.b * p.M * p.N;
+        } else {
+            ldc = p.ldc;
+            cBase = p.C + (long long)tc.b * p.strideC;
         }
+        float bv[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = colLane + j * 16;
+            bv[j] = (!RAW && p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = rowLane + i * 16 + r;
+                float *rowPtr = cBase + (long long)m * ldc + colLane;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float v = acc[i][j][r];
+                    if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
+                    if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
+                }
+            }
+    }
 }
 
 #undef GE_BF16_STEP

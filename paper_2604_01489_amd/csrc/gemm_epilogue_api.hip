@@ -11,14 +11,12 @@
 #include "gemm_bf16_fast.h"
 #include "gemm_f32_fast.h"
 #include "gemm_generic.h"
+#include "ge_host.h"
 
-namespace {
-
-using ge::GemmParams;
+namespace ge_host {
 
 thread_local const char *g_last_config = "none";
 
-constexpr int kNumCU = 256;          // MI355X
 constexpr int kMaxDevices = 64;
 
 struct Workspace {
@@ -27,20 +25,6 @@ struct Workspace {
 };
 Workspace g_ws[kMaxDevices];
 std::mutex g_ws_mutex;
-
-inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
-
-// ---- shape -> plan -------------------------------------------------------
-enum TileKind { TILE_256 = 0, TILE_128 = 1, TILE_GENERIC = 2 };
-
-struct Plan {
-    TileKind tile;
-    int bm, bn, bk;
-    int tilesM, tilesN;
-    int splitK;      // >= 1
-    int kPerSlice;
-    bool edge;
-};
 
 bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
 {
@@ -274,7 +258,9 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     return GE_OK;
 }
 
-}  // namespace
+}  // namespace ge_host
+
+using namespace ge_host;
 
 extern "C" {
 
@@ -392,6 +378,7 @@ const char *ge_status_string(ge_status_t status)
     case GE_ERR_WORKSPACE: return "split-K workspace missing, too small, misaligned or not allocatable";
     case GE_ERR_LAUNCH: return "kernel launch failed";
     case GE_ERR_CONFIG: return "unknown plan or split count";
+    case GE_ERR_EPILOGUE: return "clamp bounds out of order or unknown element type";
     }
     return "unknown status";
 }

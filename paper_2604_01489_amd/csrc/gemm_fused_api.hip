@@ -1,0 +1,173 @@
+// C-ABI of the widened operator (operands stored either way round, row scale, residual, clamp,
+// fp32 or bf16 output): validation, plan selection and kernel launches.  See
+// include/gemm_epilogue.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/gemm_epilogue.h"
+#include "gemm_bf16_fast.h"
+#include "gemm_fused.h"
+#include "ge_host.h"
+
+namespace {
+
+using ge::GemmParams;
+using namespace ge_host;
+
+const char *kLayoutName[4] = {"nn", "nt", "tn", "tt"};
+thread_local char g_config_buf[96];
+
+void set_config(const char *kernel, int transA, int transB, bool splitk)
+{
+    std::snprintf(g_config_buf, sizeof g_config_buf, "bf16_fused_%s_%s%s", kernel,
+                  kLayoutName[(transA ? 2 : 0) + (transB ? 1 : 0)], splitk ? "_splitk" : "");
+    g_last_config = g_config_buf;
+}
+
+ge_status_t validate(const ge_fused_args_t &a)
+{
+    if (!a.A || !a.B || !a.C) return GE_ERR_NULL;
+    if (a.M < 1 || a.N < 1 || a.K < 1 || a.batch < 1) return GE_ERR_SHAPE;
+    if (a.lda < (a.transA ? a.M : a.K) || a.ldb < (a.transB ? a.K : a.N) || a.ldc < a.N) return GE_ERR_LD;
+    if (a.R && a.ldr < a.N) return GE_ERR_LD;
+    if (a.act != GE_ACT_NONE && a.act != GE_ACT_RELU && a.act != GE_ACT_GELU_TANH) return GE_ERR_ACT;
+    if (a.c_type != GE_DTYPE_F32 && a.c_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
+    if (a.R && a.r_type != GE_DTYPE_F32 && a.r_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
+    if (!(a.clamp_lo <= a.clamp_hi)) return GE_ERR_EPILOGUE;
+    const uintptr_t cMask = a.c_type == GE_DTYPE_F32 ? 3u : 1u, rMask = a.r_type == GE_DTYPE_F32 ? 3u : 1u;
+    if ((((uintptr_t)a.A) & 1u) || (((uintptr_t)a.B) & 1u) || (((uintptr_t)a.C) & cMask)) return GE_ERR_ALIGN;
+    if (a.R && (((uintptr_t)a.R) & rMask)) return GE_ERR_ALIGN;
+    if ((a.bias && (((uintptr_t)a.bias) & 3u)) || (a.row_scale && (((uintptr_t)a.row_scale) & 3u))) return GE_ERR_ALIGN;
+    // element counts of one operand / result must fit 63 bits with room to spare
+    const long long big = 1ll << 40;
+    if ((long long)a.batch * a.M > big / a.ldc || (long long)a.batch * (a.transA ? a.K : a.M) > big / a.lda ||
+        (long long)a.batch * (a.transB ? a.N : a.K) > big / a.ldb)
+        return GE_ERR_SHAPE;
+    return GE_OK;
+}
+
+// The direct-to-LDS kernel moves 16-byte chunks along an operand's rows: they must be aligned
+// and must not straddle the end of a row's payload.
+bool fast_ok(const ge_fused_args_t &a)
+{
+    if ((((uintptr_t)a.A) | ((uintptr_t)a.B)) & 15u) return false;
+    if ((a.lda | a.ldb) & 7) return false;
+    if ((a.transA ? a.M : a.K) & 7) return false;
+    if ((a.transB ? a.K : a.N) & 7) return false;
+    // per-lane byte offsets inside one tile panel must stay below 2^31
+    const long long rowsA = a.transA ? 32 : 256, rowsB = a.transB ? 256 : 32;
+    if ((long long)a.lda * 2 * rowsA + 1024 >= (1ll << 31)) return false;
+    if ((long long)a.ldb * 2 * rowsB + 1024 >= (1ll << 31)) return false;
+    if (a.c_type == GE_DTYPE_BF16 && ((a.N | a.ldc) & 1 || (((uintptr_t)a.C) & 3u))) return false;   // packed pairs
+    return true;
+}
+
+template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW>
+void launch_layout(const GemmParams &p, dim3 grid, hipStream_t st)
+{
+    constexpr int threads = WM * WN * 64;
+    constexpr bool F = !RAW;
+    if (p.transA) {
+        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, true, true, F>), grid, dim3(threads), 0, st, p);
+        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, true, false, F>), grid, dim3(threads), 0, st, p);
+    } else {
+        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, false, true, F>), grid, dim3(threads), 0, st, p);
+        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, false, false, F>), grid, dim3(threads), 0, st, p);
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
+{
+    if (edge) {
+        if (raw) launch_layout<BM, BN, WM, WN, true, true>(p, grid, st);
+        else     launch_layout<BM, BN, WM, WN, true, false>(p, grid, st);
+    } else {
+        if (raw) launch_layout<BM, BN, WM, WN, false, true>(p, grid, st);
+        else     launch_layout<BM, BN, WM, WN, false, false>(p, grid, st);
+    }
+}
+
+}  // namespace
+
+extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream)
+{
+    if (!args) return GE_ERR_NULL;
+    const ge_fused_args_t &a = *args;
+    ge_status_t st = validate(a);
+    if (st != GE_OK) return st;
+    Plan pl;
+    st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a), a.plan, a.split_k, &pl);
+    if (st != GE_OK) return st;
+
+    GemmParams p{};
+    p.A = a.A; p.B = a.B; p.bias = a.bias; p.C = (float *)a.C;
+    p.M = a.M; p.N = a.N; p.K = a.K;
+    p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
+    const long long rowsA = a.transA ? a.K : a.M, colsA = a.transA ? a.M : a.K;
+    const long long rowsB = a.transB ? a.N : a.K, colsB = a.transB ? a.K : a.N;
+    p.strideA = rowsA * a.lda;
+    p.strideB = rowsB * a.ldb;
+    p.strideC = (long long)a.M * a.ldc;
+    p.sliceStride = (long long)a.batch * a.M * a.N;
+    p.batch = a.batch;
+    p.splitK = pl.splitK;
+    p.kPerSlice = pl.kPerSlice;
+    p.tilesM = pl.tilesM;
+    p.tilesN = pl.tilesN;
+    p.groupM = choose_group_m(pl.tilesM, pl.tilesN);
+    p.alpha = a.alpha;
+    p.act = (int)a.act;
+    // extent of the operands as the arguments describe them (last row ends at its last element)
+    p.bytesA = 2 * (((long long)a.batch * rowsA - 1) * a.lda + colsA);
+    p.bytesB = 2 * (((long long)a.batch * rowsB - 1) * a.ldb + colsB);
+    p.rowScale = a.row_scale;
+    p.R = a.R;
+    p.strideR = (long long)a.M * a.ldr;
+    p.ldr = a.ldr;
+    p.rType = (int)a.r_type;
+    p.beta = a.R ? a.beta : 0.0f;
+    p.clampLo = a.clamp_lo;
+    p.clampHi = a.clamp_hi;
+    p.cType = (int)a.c_type;
+    p.transA = a.transA ? 1 : 0;
+    p.transB = a.transB ? 1 : 0;
+
+    const bool raw = pl.splitK > 1;
+    void *ws = nullptr;
+    GemmParams pg = p;                      // the GEMM pass: partial tiles go to the workspace
+    if (raw) {
+        st = acquire_workspace(partial_bytes(a.M, a.N, a.batch, pl.splitK), a.workspace, a.workspace_bytes, &ws);
+        if (st != GE_OK) return st;
+        pg.C = (float *)ws;
+    }
+    const dim3 grid((unsigned)((long long)pl.tilesM * pl.tilesN * a.batch * pl.splitK));
+    hipStream_t hs = (hipStream_t)stream;
+    switch (pl.tile) {
+    case TILE_256:
+        launch_tile<256, 256, 2, 4>(pg, pl.edge, raw, grid, hs);
+        set_config("256x256x32_w8", a.transA, a.transB, raw);
+        break;
+    case TILE_128:
+        launch_tile<128, 128, 2, 2>(pg, pl.edge, raw, grid, hs);
+        set_config("128x128x32_w4", a.transA, a.transB, raw);
+        break;
+    default:
+        if (raw) hipLaunchKernelGGL(ge::gemm_bf16_fused_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
+        else     hipLaunchKernelGGL(ge::gemm_bf16_fused_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
+        set_config("generic_64x64x32", a.transA, a.transB, raw);
+        break;
+    }
+    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    if (raw) {
+        const long long total = (long long)a.batch * a.M * a.N;
+        long long blocks = (total + 255) / 256;
+        if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
+        hipLaunchKernelGGL(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
+        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    }
+    return GE_OK;
+}

@@ -127,3 +127,82 @@ def run_case(oracle, dtype, M, N, K, *, batch=1, alpha=1.0, act="none", with_bia
     rel = compare(got, ref, f"{cfg} {dtype} {M}x{N}x{K}x{batch}")
     del keepA, keepB
     return got, ref, rel, cfg
+
+
+def run_fused_case(oracle, M, N, K, *, batch=1, transA=False, transB=False, alpha=1.0, with_row_scale=False,
+                   with_bias=True, residual=None, beta=1.0, act="none", clamp=None, out="f32",
+                   pad=(0, 0, 0, 0), seed=0, misalign=0, plan="auto", split_k=0, dist="uniform"):
+    """The widened operator through the C-ABI against its oracle on the same seeded inputs.
+
+    ``pad`` = extra elements on (lda, ldb, ldr, ldc).  ``residual`` is None, "f32" or "bf16".
+    ``misalign`` shifts the A, B and C pointers by that many elements (guarded kernel).  Padding
+    of the inputs holds large finite garbage, padding of C a canary that must survive.
+    Returns (got, ref, relative Frobenius error, configuration name).
+    """
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+
+    rowsA, colsA = (K, M) if transA else (M, K)
+    rowsB, colsB = (N, K) if transB else (K, N)
+    lda, ldb, ldr, ldc = colsA + pad[0], colsB + pad[1], N + pad[2], N + pad[3]
+
+    def draw(stream, n):
+        if dist == "uniform":
+            return gen.uniform(seed, stream, n, -1.0, 1.0)
+        return gen.normal(seed, stream, n, 1.0)
+
+    A = gen.to_bf16_bits(draw(gen.STREAM_A, batch * M * K).reshape(batch, M, K))
+    B = gen.to_bf16_bits(draw(gen.STREAM_B, batch * K * N).reshape(batch, K, N))
+    bias = gen.uniform(seed, gen.STREAM_BIAS, N, -1.0, 1.0) if with_bias else None
+    rs = gen.uniform(seed, 7, M, 0.25, 2.0) if with_row_scale else None
+    junk = np.uint16(0x7F00)
+    As = np.full((batch, rowsA, lda), junk, dtype=np.uint16)
+    As[:, :, :colsA] = A.transpose(0, 2, 1) if transA else A
+    Bs = np.full((batch, rowsB, ldb), junk, dtype=np.uint16)
+    Bs[:, :, :colsB] = B.transpose(0, 2, 1) if transB else B
+    Rs = None
+    if residual is not None:
+        R32 = gen.uniform(seed, 8, batch * M * N, -1.0, 1.0).reshape(batch, M, N)
+        if residual == "bf16":
+            Rs = np.full((batch, M, ldr), junk, dtype=np.uint16)
+            Rs[:, :, :N] = gen.to_bf16_bits(R32)
+        else:
+            Rs = np.full((batch, M, ldr), np.float32(3.0e37), dtype=np.float32)
+            Rs[:, :, :N] = R32
+
+    def shifted(flat, junk_value):
+        buf = np.full(flat.size + misalign, junk_value, dtype=flat.dtype)
+        buf[misalign:] = flat
+        t = to_device(buf)
+        return t, t[misalign:]
+
+    keepA, dA = shifted(As.ravel(), junk)
+    keepB, dB = shifted(Bs.ravel(), junk)
+    dbias, drs, dR = to_device(bias), to_device(rs), to_device(None if Rs is None else Rs.ravel())
+    cdtype = torch.float32 if out == "f32" else torch.bfloat16
+    canary = CANARY if out == "f32" else -7.0e30
+    Cbuf = torch.full((batch * M * ldc + misalign,), canary, dtype=cdtype, device=torch_device())
+    dC = Cbuf[misalign:]
+    if dR is not None and residual == "bf16":
+        dR = dR.view(torch.bfloat16)
+    torch.cuda.synchronize()
+    print(f"fused case M={M} N={N} K={K} batch={batch} tA={transA} tB={transB} pad={pad} act={act} out={out} "
+          f"res={residual} rs={with_row_scale} bias={with_bias} clamp={clamp} misalign={misalign} plan={plan} "
+          f"split_k={split_k}", flush=True)
+    binding.gemm_epilogue_bf16_fused(M, N, K, dA, lda, dB, ldb, dC, ldc, batch=batch, transA=transA, transB=transB,
+                                     alpha=alpha, row_scale=drs, bias=dbias, residual=dR, ldr=ldr, beta=beta,
+                                     act=act, clamp=clamp, plan=plan, split_k=split_k)
+    torch.cuda.synchronize()
+    cfg = binding.last_config()
+    outv = Cbuf.to(torch.float32).cpu().numpy()
+    canary32 = np.float32(torch.tensor(canary, dtype=cdtype).to(torch.float32).item())
+    assert np.all(outv[:misalign] == canary32), "wrote before C"
+    Cp = outv[misalign:].reshape(batch, M, ldc)
+    assert np.all(Cp[:, :, N:] == canary32), f"{cfg}: wrote into the padding of C"
+    got = Cp[:, :, :N]
+    ref = oracle.gemm_fused(M, N, K, As, Bs, batch=batch, transA=transA, transB=transB, lda=lda, ldb=ldb,
+                            alpha=alpha, row_scale=rs, bias=bias, residual=Rs, ldr=ldr, beta=beta, act=act,
+                            clamp=clamp, out=out)
+    rel = compare(got, ref, f"{cfg} fused {M}x{N}x{K}x{batch}")
+    del keepA, keepB
+    return got, ref, rel, cfg

@@ -1,0 +1,107 @@
+"""GPU parity of the widened operator (gemm_epilogue_bf16_fused) against its CPU oracle:
+operands stored either way round, row scale, residual, clamp, fp32 and bf16 output, on the
+direct-to-LDS kernels (256 and 128 tiles), the guarded kernel and the split-K path."""
+import itertools
+
+import numpy as np
+import pytest
+
+from gpu_util import run_case, run_fused_case
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = list(itertools.product([False, True], repeat=2))
+NAME = {(False, False): "nn", (False, True): "nt", (True, False): "tn", (True, True): "tt"}
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_layouts_tile_256(oracle, transA, transB):
+    """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded."""
+    for M, N, K, pad in [(256, 256, 64, (0, 0, 0, 0)), (512, 768, 256, (8, 16, 0, 4)), (520, 776, 328, (24, 8, 0, 0))]:
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, act="gelu_tanh",
+                                      pad=pad, seed=M + K + 2 * transA + transB)
+        assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}"
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_layouts_tile_128(oracle, transA, transB):
+    for M, N, K in [(128, 128, 192), (136, 248, 200), (8, 8, 8), (64, 384, 40)]:
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", seed=3 * M + K)
+        assert cfg == f"bf16_fused_128x128x32_w4_{NAME[transA, transB]}"
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_layouts_guarded_kernel(oracle, transA, transB):
+    for M, N, K, mis in [(67, 45, 33, 0), (130, 70, 100, 0), (1, 1, 1, 0), (128, 128, 64, 1)]:
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="gelu_tanh", alpha=1.5,
+                                      with_row_scale=True, residual="f32", beta=0.5, clamp=(-0.1, 2.0),
+                                      pad=(1, 3, 2, 5), misalign=mis, seed=M + N)
+        assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}"
+
+
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("residual", [None, "f32", "bf16"])
+def test_epilogue_chain(oracle, out, residual):
+    """Row scale, bias, residual with beta, activation and a clamp that bites on both sides."""
+    for (M, N, K), (tA, tB) in [((520, 264, 136), (False, True)), ((128, 136, 72), (True, False))]:
+        got, _, _, cfg = run_fused_case(oracle, M, N, K, transA=tA, transB=tB, alpha=0.75, with_row_scale=True,
+                                        residual=residual, beta=-0.5, act="gelu_tanh", clamp=(-0.05, 1.25), out=out,
+                                        pad=(0, 0, 8, 8), seed=11 + M)
+        assert "generic" not in cfg
+        assert (got == np.float32(-0.05)).any() or out == "bf16"
+        assert got.max() <= 1.25 + 1e-6
+
+
+def test_bf16_output_all_paths(oracle):
+    run_fused_case(oracle, 512, 512, 128, out="bf16", act="relu", seed=21)                       # 256 tile, full
+    run_fused_case(oracle, 264, 520, 72, out="bf16", act="none", pad=(0, 0, 0, 6), seed=22)      # 256 tile, ragged, ldc even
+    run_fused_case(oracle, 72, 136, 40, out="bf16", act="gelu_tanh", seed=23)                    # 128 tile
+    _, _, _, cfg = run_fused_case(oracle, 72, 136, 40, out="bf16", pad=(0, 0, 0, 3), seed=24)    # odd ldc -> guarded
+    assert "generic" in cfg
+    _, _, _, cfg = run_fused_case(oracle, 45, 67, 33, out="bf16", act="relu", seed=25)
+    assert "generic" in cfg
+
+
+def test_batched(oracle):
+    run_fused_case(oracle, 256, 256, 64, batch=5, transB=True, act="relu", residual="bf16", out="bf16", seed=31)
+    run_fused_case(oracle, 136, 72, 48, batch=4, transA=True, with_row_scale=True, pad=(8, 8, 0, 4), seed=32)
+    run_fused_case(oracle, 33, 65, 17, batch=3, transA=True, transB=True, residual="f32", seed=33)
+
+
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_split_k(oracle, transA, transB):
+    _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
+                                  with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
+                                  plan="splitk", split_k=0, seed=41)
+    assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}_splitk"
+    _, _, _, cfg = run_fused_case(oracle, 130, 70, 1500, transA=transA, transB=transB, alpha=1.0 / 32,
+                                  plan="splitk", split_k=3, seed=42)
+    assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}_splitk"
+
+
+def test_plain_operator_is_the_special_case(oracle):
+    """Extras off, fp32 output, both operands as stored by the plain entry point: same bits."""
+    for M, N, K in [(512, 512, 256), (200, 136, 72), (67, 45, 33)]:
+        got_f, _, _, _ = run_fused_case(oracle, M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
+        got_p, _, _, _ = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
+        assert np.array_equal(got_f, got_p)
+
+
+def test_diagonal_times_dense(oracle):
+    """A = identity with a row scale: the row scaling diag(d) @ B as a special case of the operator."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    M, N = 256, 512
+    dev = torch.device("cuda:0")
+    B32 = gen.uniform(9, 1, M * N, -1.0, 1.0).reshape(M, N)
+    Bb = gen.to_bf16_bits(B32)
+    d = gen.uniform(9, 7, M, -2.0, 2.0)
+    eye = gen.to_bf16_bits(np.eye(M, dtype=np.float32))
+    dA = torch.from_numpy(eye.view(np.int16)).to(dev)
+    dB = torch.from_numpy(Bb.view(np.int16)).to(dev)
+    dd = torch.from_numpy(d).to(dev)
+    C = torch.empty(M, N, dtype=torch.float32, device=dev)
+    binding.gemm_epilogue_bf16_fused(M, N, M, dA, M, dB, N, C, N, row_scale=dd)
+    torch.cuda.synchronize()
+    want = d.astype(np.float64)[:, None] * gen.bf16_bits_to_f32(Bb).astype(np.float64)
+    assert np.allclose(C.cpu().numpy(), want, rtol=1e-6, atol=1e-7)

@@ -29,8 +29,8 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_status_strings(lib):
-    seen = {binding.status_string(i) for i in range(9)}
-    assert len(seen) == 9 and "ok" in seen
+    seen = {binding.status_string(i) for i in range(10)}
+    assert len(seen) == 10 and "ok" in seen
     assert binding.status_string(99) == "unknown status"
 
 
@@ -56,6 +56,32 @@ def test_argument_errors_return_codes(lib, name):
     assert with_(A=P + 1) == 5 and with_(C=P + 2) == 5 and with_(bias=P + 1) == 5
     if name.endswith("f32"):
         assert with_(B=P + 2) == 5
+
+
+def test_fused_argument_errors_return_codes(lib):
+    """gemm_epilogue_bf16_fused validates before it touches a device (the addresses are fake)."""
+    def call(**kw):
+        a = dict(M=64, N=48, K=32, A_ptr=P, lda=32, B_ptr=P, ldb=48, C_ptr=P, ldc=48)
+        a.update(kw)
+        pos = [a.pop(k) for k in ("M", "N", "K", "A_ptr", "lda", "B_ptr", "ldb", "C_ptr", "ldc")]
+        return binding.raw_fused(binding.fused_args(*pos, **a))
+
+    assert call(A_ptr=None) == 1 and call(B_ptr=None) == 1 and call(C_ptr=None) == 1
+    assert call(M=0) == 2 and call(batch=0) == 2
+    # leading dimensions follow the storage: lda >= K, or >= M when A is stored transposed
+    assert call(lda=31) == 3 and call(transA=True, lda=63) == 3
+    assert call(ldb=47) == 3 and call(transB=True, ldb=31) == 3
+    assert call(ldc=47) == 3 and call(R_ptr=P, ldr=47) == 3
+    assert call(act=3) == 4
+    assert call(A_ptr=P + 1) == 5 and call(C_ptr=P + 2) == 5 and call(bias_ptr=P + 2) == 5
+    assert call(R_ptr=P + 2, ldr=48, r_type="f32") == 5
+    assert call(row_scale_ptr=P + 1) == 5
+    assert call(clamp=(1.0, 0.5)) == 9 and call(clamp=(float("nan"), 1.0)) == 9
+    assert call(c_type=2) == 9
+    assert call(plan=7) == 8
+    # bf16 output only needs 2-byte alignment of C
+    assert call(C_ptr=P + 2, c_type="bf16", plan=7) == 8
+    assert binding.load().gemm_epilogue_bf16_fused(None, None) == 1
 
 
 def test_ex_plan_errors(lib):
