@@ -34,6 +34,9 @@ BOUND = {
     "c3_bf16_8192_bias_gelu": "mfma",
     "c4_bf16_batched_512x512x64": "hbm",
     "c5_bf16_splitk_1024x1024x65536": "mfma",
+    "c6_fused_nt_8192_bias_gelu_bf16out": "mfma",
+    "c7_fused_tn_8192_chain": "mfma",
+    "c8_fused_batched_512x512x64_bf16out": "hbm",
 }
 
 
@@ -151,22 +154,36 @@ def main() -> int:
         print(json.dumps({"copy_probe_bytes": n, "launches": 5}))
         return 0
     binding.load()
-    w = gen.WORKLOADS[args.workload]
+    fused = args.workload in gen.FUSED_WORKLOADS
+    fw = gen.FUSED_WORKLOADS[args.workload] if fused else None
+    w = fw.base if fused else gen.WORKLOADS[args.workload]
+    job = fw if fused else w                       # flops and algorithmic bytes
     if w.dtype != "bf16":
         print("bench.py times the bf16 workloads", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
     M, N, K, batch = w.M, w.N, w.K, w.batch
+    stream = torch.cuda.current_stream()
+
+    def dev_bits(x):
+        return None if x is None else torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).to(dev)
 
     # ---- seeded synthetic inputs, generated on the host, resident in HBM before timing
-    A = gen.make_operand(w, "A")
-    B = gen.make_operand(w, "B")
-    bias = gen.make_bias(w)
-    dA = torch.from_numpy(A.view(np.int16)).to(dev)
-    dB = torch.from_numpy(B.view(np.int16)).to(dev)
-    dbias = None if bias is None else torch.from_numpy(bias).to(dev)
-    dC = torch.empty(batch, M, N, dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream()
+    if fused:
+        host = gen.make_fused_inputs(fw)
+        A, B, bias = host["A"], host["B"], host["bias"]
+        lda, ldb = A.shape[2], B.shape[2]
+        dA, dB, dbias = dev_bits(A), dev_bits(B), dev_bits(bias)
+        drs, dR = dev_bits(host["row_scale"]), dev_bits(host["residual"])
+        if dR is not None and fw.residual == "bf16":
+            dR = dR.view(torch.bfloat16)
+        dC = torch.empty(batch, M, N, dtype=torch.float32 if fw.out == "f32" else torch.bfloat16, device=dev)
+    else:
+        A = gen.make_operand(w, "A")
+        B = gen.make_operand(w, "B")
+        bias = gen.make_bias(w)
+        dA, dB, dbias = dev_bits(A), dev_bits(B), dev_bits(bias)
+        dC = torch.empty(batch, M, N, dtype=torch.float32, device=dev)
     sets = [(dA, dB, dC)]
     for _ in range(1, max(1, args.rotate)):
         sets.append((dA.clone(), dB.clone(), torch.empty_like(dC)))
@@ -175,7 +192,13 @@ def main() -> int:
     def step():
         a, b, c = sets[calls[0] % len(sets)]
         calls[0] += 1
-        binding.gemm_epilogue_bf16(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
+        if fused:
+            binding.gemm_epilogue_bf16_fused(M, N, K, a, lda, b, ldb, c, N, batch=batch, transA=fw.transA,
+                                             transB=fw.transB, alpha=w.alpha, row_scale=drs, bias=dbias,
+                                             residual=dR, ldr=N, beta=fw.beta, act=w.act, clamp=fw.clamp,
+                                             stream=stream)
+        else:
+            binding.gemm_epilogue_bf16(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -194,14 +217,14 @@ def main() -> int:
     ms_dev = ev0.elapsed_time(ev1) / args.steps     # HIP events on the launch stream
     config_name = binding.last_config()
 
-    tflops = w.flops / (ms_wall * 1e-3) / 1e12
+    tflops = job.flops / (ms_wall * 1e-3) / 1e12
     bound = BOUND[args.workload]
     if bound == "mfma":
-        achieved = w.flops / (ms_dev * 1e-3) / 1e12
+        achieved = job.flops / (ms_dev * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
     else:
-        achieved = w.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
+        achieved = job.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
     roofline["traffic"] = measured_traffic(args.workload)     # HBM-side bytes per launch, or null
@@ -218,15 +241,28 @@ def main() -> int:
     parity = None
     if args.oracle_rows > 0:
         import oracle
-        rows = sample_rows(M, args.oracle_rows)
+        # the widened operator's oracle walks every output with its own k loop: a smaller sample
+        rows = sample_rows(M, min(args.oracle_rows, 512) if fused else args.oracle_rows)
         nb = 1 if batch == 1 else min(batch, max(1, args.oracle_rows // len(rows)))
         bsel = np.unique(np.round(np.linspace(0, batch - 1, nb)).astype(np.int64))
-        got = dC[torch.from_numpy(bsel).to(dev)][:, torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
-        A_s = np.ascontiguousarray(A[bsel][:, rows])
+        got = dC[torch.from_numpy(bsel).to(dev)][:, torch.from_numpy(rows).to(dev)].to(torch.float32)
+        got = got.cpu().numpy().astype(np.float64)
         B_s = np.ascontiguousarray(B[bsel])
-        c0 = time.perf_counter()
-        ref = oracle.gemm_epilogue(A_s, B_s, bias, w.alpha, w.act)
-        c1 = time.perf_counter()
+        if fused:
+            # the sampled rows of A in A's own storage (columns of it when A is stored K x M)
+            A_s = np.ascontiguousarray(A[bsel][:, :, rows] if fw.transA else A[bsel][:, rows])
+            rs_s = None if host["row_scale"] is None else host["row_scale"][rows]
+            R_s = None if host["residual"] is None else np.ascontiguousarray(host["residual"][bsel][:, rows])
+            c0 = time.perf_counter()
+            ref = oracle.gemm_fused(len(rows), N, K, A_s, B_s, batch=len(bsel), transA=fw.transA, transB=fw.transB,
+                                    alpha=w.alpha, row_scale=rs_s, bias=bias, residual=R_s, beta=fw.beta,
+                                    act=w.act, clamp=fw.clamp, out=fw.out)
+            c1 = time.perf_counter()
+        else:
+            A_s = np.ascontiguousarray(A[bsel][:, rows])
+            c0 = time.perf_counter()
+            ref = oracle.gemm_epilogue(A_s, B_s, bias, w.alpha, w.act)
+            c1 = time.perf_counter()
         sample_flops = 2.0 * len(bsel) * len(rows) * N * K
         cpu_baseline = {"value": round(sample_flops / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s",
                         "cores": oracle.num_threads(), "kind": "oracle",
@@ -252,8 +288,11 @@ def main() -> int:
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "batch": batch,
-                   "alpha": w.alpha, "act": w.act, "bias": w.bias is not None, "out_dtype": "f32",
-                   "kernel": config_name},
+                   "alpha": w.alpha, "act": w.act, "bias": w.bias is not None,
+                   "out_dtype": fw.out if fused else "f32",
+                   "layout": ("t" if fused and fw.transA else "n") + ("t" if fused and fw.transB else "n"),
+                   "row_scale": bool(fused and fw.row_scale), "residual": fw.residual if fused else None,
+                   "clamp": fw.clamp if fused else None, "kernel": config_name},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": roofline,
         "ceilings": ceilings,

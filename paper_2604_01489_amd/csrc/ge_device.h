@@ -11,6 +11,8 @@ typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(8))) short short8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) int i32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2_t;
 
 #define GE_LDS __attribute__((address_space(3)))
 
@@ -46,6 +48,7 @@ struct GemmParams {
     float beta;
     float clampLo, clampHi;
     int cType;
+    int rVec;                  // a lane's 4 consecutive residual elements can be read in one piece
     int transA, transB;        // operand stored transposed (read by the guarded kernel; the main
                                // kernel takes them as template arguments)
 };
@@ -81,7 +84,18 @@ __device__ inline TileCoord map_block(const GemmParams &p, unsigned bid)
     return c;
 }
 
-__device__ inline TileCoord map_block(const GemmParams &p) { return map_block(p, blockIdx.x); }
+// The coordinates of the calling block.  The divisions above run on the vector unit; the results
+// are block-uniform, and pinning them to scalar registers here keeps everything derived from them
+// (tile origins, operand bases, buffer resources handed to inline assembly) scalar as well.
+__device__ inline TileCoord map_block(const GemmParams &p)
+{
+    TileCoord c = map_block(p, blockIdx.x);
+    c.tm = __builtin_amdgcn_readfirstlane(c.tm);
+    c.tn = __builtin_amdgcn_readfirstlane(c.tn);
+    c.b = __builtin_amdgcn_readfirstlane(c.b);
+    c.s = __builtin_amdgcn_readfirstlane(c.s);
+    return c;
+}
 
 // gelu_tanh(v) = 0.5 v (1 + tanh u) with u = sqrt(2/pi) (v + 0.044715 v^3).
 // Since 0.5 (1 + tanh u) = 1 / (1 + exp(-2u)) this is v / (1 + exp(-2u)): one
@@ -139,16 +153,135 @@ __device__ inline float fused_value(const GemmParams &p, float acc, float rowSca
     return v;
 }
 
-// Epilogue of the widened operator for a wave tile held as TM x TN accumulators of the 16x16 MFMA
-// (register r of lane l: row 4*(l/16) + r, column l%16 of its block).  rowLane / colLane are the
-// global row of register 0 and the global column of this lane in block (0, 0).
-// fp32 output: one dword per lane and row, 64 contiguous bytes per 16 lanes.
-// bf16 output: neighbouring lanes first trade two of their four rows, so that an even lane holds
-// columns (c, c+1) of rows 0 and 1 and its odd neighbour those of rows 2 and 3, and each stores
-// packed pairs (4 bytes): half the store instructions, 32 contiguous bytes per 8 lanes.
+// One row block (16 rows x TN blocks of 16 columns) of a wave tile through the chain, for
+// accumulators of the swapped product: the lane holds row m and, per block j, the 4 consecutive
+// columns from colLane + 16 j.  Residual type and activation are selected by uniform branches
+// around the loops, not per element: on the store-bound shapes the vector ALU work per output is
+// what the epilogue costs.
+template <int TN, bool EDGE>
+__device__ inline void chain_row_block(const GemmParams &p, int b, f32x4_t (&v)[TN], const float (&bv)[TN][4],
+                                       int m, int colLane)
+{
+    const bool rowOk = !EDGE || m < p.M;
+    const float scale = p.alpha * ((p.rowScale != nullptr && rowOk) ? p.rowScale[m] : 1.0f);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j][r]);
+
+    if (p.R != nullptr) {
+        const long long rowAt = (long long)b * p.strideR + (long long)m * p.ldr;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = colLane + j * 16;
+            if (EDGE && (!rowOk || n >= p.N)) continue;
+            float res[4];
+            if (p.rType == DT_BF16) {
+                if (p.rVec) {
+                    const u32x2_t t = *(const u32x2_t *)((const unsigned short *)p.R + rowAt + n);
+                    res[0] = __uint_as_float(t[0] << 16); res[1] = __uint_as_float(t[0] & 0xFFFF0000u);
+                    res[2] = __uint_as_float(t[1] << 16); res[3] = __uint_as_float(t[1] & 0xFFFF0000u);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) res[r] = load_as_f32(p.R, rowAt + n + r, DT_BF16);
+                }
+            } else if (p.rVec) {
+                const f32x4_t t = *(const f32x4_t *)((const float *)p.R + rowAt + n);
+                res[0] = t[0]; res[1] = t[1]; res[2] = t[2]; res[3] = t[3];
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) res[r] = ((const float *)p.R)[rowAt + n + r];
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(p.beta, res[r], v[j][r]);
+        }
+    }
+    if (p.act == ACT_RELU) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(__builtin_fmaxf(v[j][r], 0.0f), p.clampLo, p.clampHi);
+    } else if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], p.clampLo, p.clampHi);
+    }
+}
+
+__device__ inline unsigned pack_bf16_pair(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    const f32x2_t f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2_t));
+}
+
+// Epilogue of the widened operator with bf16 output, for a block tile whose accumulators were
+// produced with the operands of the 16x16 MFMA swapped, i.e. transposed blocks: lane l of a block
+// holds row l%16, register r column 4*(l/16) + r.  A lane then owns 4 consecutive columns of one
+// row, which is what the chain wants (one row scale per lane, bias and residual in pieces, bf16
+// conversions that pack pairs), and the tile goes to C through LDS: the waves park their values
+// in a row-major image of the tile (16-byte chunks XOR-swizzled by the row, so that the 16 rows a
+// write instruction touches fall in different banks), then every wave instruction moves 1 KB of
+// whole rows to C with 16 bytes per lane.  Each row block runs the whole chain and is parked
+// before the next one starts.  C must be able to take 16-byte row pieces (the host checks).
+// `lds` must hold BM*BN*2 bytes nobody reads any more; all NW waves of the block call this.
+// (tileRow, tileCol): row of this lane and first of its 4 columns in block (0, 0) of the wave
+// tile, relative to the block tile.
+template <int BM, int BN, int NW, int LDS_BYTES, int TM, int TN, bool EDGE>
+__device__ inline void fused_epilogue_bf16_through_lds(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], GE_LDS char *lds,
+                                                       int m0, int n0, int tileRow, int tileCol, int w, int lane)
+{
+    constexpr int PITCH = BN * 2, CHUNKS = PITCH / 16, ROWS_PER_INSTR = 1024 / PITCH;
+    static_assert(BM * PITCH <= LDS_BYTES, "bf16 image of the tile fits the stages");
+    const int colLane = n0 + tileCol;
+    float bv[TN][4];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = colLane + j * 16;
+        const bool ok = p.bias != nullptr && (!EDGE || n < p.N);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bv[j][r] = ok ? p.bias[n + r] : 0.0f;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // every wave is done with the stages
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = tileRow + i * 16;
+        chain_row_block<TN, EDGE>(p, b, acc[i], bv, m0 + row, colLane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int cb = (tileCol + j * 16) * 2;
+            u32x2_t v;
+            v[0] = pack_bf16_pair(acc[i][j][0], acc[i][j][1]);
+            v[1] = pack_bf16_pair(acc[i][j][2], acc[i][j][3]);
+            *(GE_LDS u32x2_t *)(lds + row * PITCH + (((cb >> 4) ^ (row & (CHUNKS - 1))) << 4) + (cb & 15)) = v;
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    unsigned short *cBase = (unsigned short *)p.C + (long long)b * p.strideC;
+    const int rowInGroup = lane / CHUNKS, chunk = lane % CHUNKS;
+#pragma unroll
+    for (int it = 0; it < BM / ROWS_PER_INSTR / NW; ++it) {
+        const int row = (it * NW + w) * ROWS_PER_INSTR + rowInGroup;
+        const i32x4_t v = *(const GE_LDS i32x4_t *)(lds + row * PITCH + ((chunk ^ (row & (CHUNKS - 1))) << 4));
+        const int m = m0 + row, n = n0 + chunk * 8;
+        if (!EDGE || (m < p.M && n < p.N)) *(i32x4_t *)(cBase + (long long)m * p.ldc + n) = v;
+    }
+}
+
+// Epilogue of the widened operator with fp32 output, straight from the accumulators of the plain
+// product (register r of lane l: row 4*(l/16) + r, column l%16 of its block).  One row block at a
+// time: the chain in registers (residual type and activation by uniform branches around the
+// loops), then one dword per lane and row, 64 contiguous bytes per 16 lanes, as in the plain kernel.
 template <int TM, int TN, bool EDGE>
-__device__ inline void fused_epilogue_16x16(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN],
-                                            int rowLane, int colLane, int lane)
+__device__ inline void fused_epilogue_f32_direct(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN],
+                                                 int rowLane, int colLane)
 {
     float bv[TN];
 #pragma unroll
@@ -156,59 +289,56 @@ __device__ inline void fused_epilogue_16x16(const GemmParams &p, int b, f32x4_t 
         const int n = colLane + j * 16;
         bv[j] = (p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
     }
-    const bool hasR = p.R != nullptr;
+    float *cBase = p.C + (long long)b * p.strideC;
     const long long rBase = (long long)b * p.strideR;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        f32x4_t (&v)[TN] = acc[i];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int m = rowLane + i * 16 + r;
-            const bool rowOk = !EDGE || m < p.M;
-            const float rs = (p.rowScale != nullptr && rowOk) ? p.rowScale[m] : 1.0f;
+            const float scale = p.alpha * ((p.rowScale != nullptr && (!EDGE || m < p.M)) ? p.rowScale[m] : 1.0f);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = colLane + j * 16;
-                const bool ok = rowOk && (!EDGE || n < p.N);
-                float res = 0.0f;
-                if (hasR && ok) res = load_as_f32(p.R, rBase + (long long)m * p.ldr + n, p.rType);
-                acc[i][j][r] = fused_value(p, acc[i][j][r], rs, bv[j], res);
-            }
+            for (int j = 0; j < TN; ++j) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j]);
         }
-    if (p.cType == DT_F32) {
-        float *cBase = p.C + (long long)b * p.strideC;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
+        if (p.R != nullptr) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int m = rowLane + i * 16 + r;
-                float *rowPtr = cBase + (long long)m * p.ldc + colLane;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = acc[i][j][r];
-            }
-    } else {
-        unsigned short *cBase = (unsigned short *)p.C + (long long)b * p.strideC;
-        const bool odd = lane & 1;
-        const int colPair = colLane & ~1;            // first column of this lane's pair in block 0
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mPair = rowLane + i * 16 + (odd ? 2 : 0);
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {            // the lane's two rows: mPair + h
-                const int m = mPair + h;
-                unsigned short *rowPtr = cBase + (long long)m * p.ldc + colPair;
+                const long long rowAt = rBase + (long long)m * p.ldr + colLane;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
-                    // give away row h of the other pair, receive the neighbour's value of my row
-                    const float send = odd ? acc[i][j][h] : acc[i][j][2 + h];
-                    const float got = __builtin_bit_cast(
-                        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
-                    const float mine = odd ? acc[i][j][2 + h] : acc[i][j][h];
-                    const float left = odd ? got : mine, right = odd ? mine : got;
-                    const unsigned packed = bf16_bits_rne(left) | (bf16_bits_rne(right) << 16);
-                    if (!EDGE || (m < p.M && colPair + j * 16 < p.N)) *(unsigned *)(rowPtr + j * 16) = packed;
+                    if (EDGE && (m >= p.M || colLane + j * 16 >= p.N)) continue;
+                    float res;
+                    if (p.rType == DT_BF16) res = load_as_f32(p.R, rowAt + j * 16, DT_BF16);
+                    else res = ((const float *)p.R)[rowAt + j * 16];
+                    v[j][r] = __builtin_fmaf(p.beta, res, v[j][r]);
                 }
             }
+        }
+        if (p.act == ACT_RELU) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(__builtin_fmaxf(v[j][r], 0.0f), p.clampLo, p.clampHi);
+        } else if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], p.clampLo, p.clampHi);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int m = rowLane + i * 16 + r;
+            float *rowPtr = cBase + (long long)m * p.ldc + colLane;
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v[j][r];
         }
     }
 }

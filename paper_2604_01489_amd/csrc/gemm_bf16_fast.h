@@ -107,17 +107,18 @@ struct Bf16Tile {
 // an operand whose rows run along k uses the "k-contiguous" stage (rows of 64 bytes, fragments
 // by ds_read_b128), one whose rows run along m or n the "k-strided" stage (k rows of the tile
 // width, fragments by transposing reads); the matrix instruction sees the same fragments.
-// FUSED: the run-time epilogue of the widened operator (row scale, residual, clamp, fp32 or bf16
-// output) instead of the compile-time scale/bias/activation.
+// FUSED: the run-time epilogue of the widened operator (row scale, residual, clamp) instead of the
+// compile-time scale/bias/activation, with fp32 output straight from the accumulators or
+// (OUTBF16) bf16 output through LDS, for which the operands of the MFMA are swapped.
 template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT, bool TA = false, bool TB = false,
-          bool FUSED = false>
+          bool FUSED = false, bool OUTBF16 = false>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmParams p)
 {
     using T = Bf16Tile<BM, BN, WM, WN>;
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
-    static_assert(!(RAW && FUSED), "partial tiles carry no epilogue");
+    static_assert(!(RAW && FUSED) && (FUSED || !OUTBF16), "partial tiles carry no epilogue; bf16 output is the fused one's");
     static_assert((BM & (BM - 1)) == 0 && ((T::WTM / 32) & (T::WTM / 32 - 1)) == 0, "k-strided A stage");
 
     // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages
@@ -265,13 +266,16 @@ gemm_bf16_kernel(const GemmParams p)
             else fb[j] = read_strided(bAddr[TB ? 0 : j] + (unsigned)(stage * T::B_BYTES), BN * 2);
         }
     };
-    // accumulator register r of lane l is C[m = 16 i + 4*(l/16) + r][n = 16 j + l%16]
+    // accumulator register r of lane l is C[m = 16 i + 4*(l/16) + r][n = 16 j + l%16]; with the
+    // operands swapped (OUTBF16) the block comes out transposed: C[m = 16 i + l%16][n = 16 j + 4*(l/16) + r]
     auto mma = [&]() {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+                if (OUTBF16) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
     };
 
     GE_LDS char *const ldsBase = (GE_LDS char *)smem;
@@ -352,7 +356,17 @@ gemm_bf16_kernel(const GemmParams p)
     const int rowLane = m0 + wm * T::WTM + 4 * (lane >> 4);
     const int colLane = n0 + wn * T::WTN + (lane & 15);
     if constexpr (FUSED) {
-        fused_epilogue_16x16<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane, lane);
+        if constexpr (OUTBF16) {
+            // the lane index as a value born here: nothing of the epilogue's address arithmetic can
+            // be hoisted above the main loop, where the accumulators leave no registers to hold it
+            int laneE = lane, waveE = (int)(threadIdx.x >> 6);
+            asm volatile("" : "+v"(laneE), "+v"(waveE));
+            fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, EDGE>(
+                p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / WN) * T::WTM + (laneE & 15),
+                (waveE % WN) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
+        } else {
+            fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
+        }
     } else {
         float *cBase;
         long long ldc;

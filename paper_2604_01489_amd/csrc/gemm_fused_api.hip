@@ -56,38 +56,43 @@ bool fast_ok(const ge_fused_args_t &a)
     if ((((uintptr_t)a.A) | ((uintptr_t)a.B)) & 15u) return false;
     if ((a.lda | a.ldb) & 7) return false;
     if ((a.transA ? a.M : a.K) & 7) return false;
-    if ((a.transB ? a.K : a.N) & 7) return false;
+    if ((a.K | a.N) & 7) return false;            // B's row payload; N also for the 16-byte pieces of a bf16 C
+    // bf16 output leaves the kernel in 16-byte row pieces
+    if (a.c_type == GE_DTYPE_BF16 && ((((uintptr_t)a.C) & 15u) || (a.ldc & 7))) return false;
     // per-lane byte offsets inside one tile panel must stay below 2^31
     const long long rowsA = a.transA ? 32 : 256, rowsB = a.transB ? 256 : 32;
     if ((long long)a.lda * 2 * rowsA + 1024 >= (1ll << 31)) return false;
     if ((long long)a.ldb * 2 * rowsB + 1024 >= (1ll << 31)) return false;
-    if (a.c_type == GE_DTYPE_BF16 && ((a.N | a.ldc) & 1 || (((uintptr_t)a.C) & 3u))) return false;   // packed pairs
     return true;
 }
 
-template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW>
+// MODE: 0 = fp32 partial tiles (split-K), 1 = fused epilogue with fp32 output, 2 = with bf16 output
+template <int BM, int BN, int WM, int WN, bool EDGE, int MODE>
 void launch_layout(const GemmParams &p, dim3 grid, hipStream_t st)
 {
     constexpr int threads = WM * WN * 64;
-    constexpr bool F = !RAW;
+    constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
     if (p.transA) {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, true, true, F>), grid, dim3(threads), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, true, false, F>), grid, dim3(threads), 0, st, p);
+        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(threads), 0, st, p);
+        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, false, F, H>), grid, dim3(threads), 0, st, p);
     } else {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, false, true, F>), grid, dim3(threads), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, RAW, ge::ACT_NONE, false, false, F>), grid, dim3(threads), 0, st, p);
+        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(threads), 0, st, p);
+        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(threads), 0, st, p);
     }
 }
 
 template <int BM, int BN, int WM, int WN>
 void launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
 {
+    const int mode = raw ? 0 : p.cType == ge::DT_BF16 ? 2 : 1;
     if (edge) {
-        if (raw) launch_layout<BM, BN, WM, WN, true, true>(p, grid, st);
-        else     launch_layout<BM, BN, WM, WN, true, false>(p, grid, st);
+        if (mode == 0)      launch_layout<BM, BN, WM, WN, true, 0>(p, grid, st);
+        else if (mode == 1) launch_layout<BM, BN, WM, WN, true, 1>(p, grid, st);
+        else                launch_layout<BM, BN, WM, WN, true, 2>(p, grid, st);
     } else {
-        if (raw) launch_layout<BM, BN, WM, WN, false, true>(p, grid, st);
-        else     launch_layout<BM, BN, WM, WN, false, false>(p, grid, st);
+        if (mode == 0)      launch_layout<BM, BN, WM, WN, false, 0>(p, grid, st);
+        else if (mode == 1) launch_layout<BM, BN, WM, WN, false, 1>(p, grid, st);
+        else                launch_layout<BM, BN, WM, WN, false, 2>(p, grid, st);
     }
 }
 
@@ -133,6 +138,8 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     p.clampLo = a.clamp_lo;
     p.clampHi = a.clamp_hi;
     p.cType = (int)a.c_type;
+    const int rElem = a.r_type == GE_DTYPE_BF16 ? 2 : 4;
+    p.rVec = (a.R && !(((uintptr_t)a.R) & 15u) && ((long long)a.ldr * rElem) % 16 == 0) ? 1 : 0;
     p.transA = a.transA ? 1 : 0;
     p.transB = a.transB ? 1 : 0;
 

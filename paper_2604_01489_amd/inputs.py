@@ -187,3 +187,76 @@ def make_operand(w: Workload, which: str, row_start: int = 0, rows: int | None =
 def make_inputs(w: Workload):
     """(A, B, bias) for the whole workload; A, B carry a leading batch axis."""
     return make_operand(w, "A"), make_operand(w, "B"), make_bias(w)
+
+
+# ---------------------------------------------------------------------------------------------
+# workloads of the widened operator (operands stored either way round, row scale, residual,
+# clamp, bf16 output): the same generator, plus the storage layout of each operand
+# ---------------------------------------------------------------------------------------------
+STREAM_ROW_SCALE = 7
+STREAM_RESIDUAL = 8
+
+
+@dataclass(frozen=True)
+class FusedWorkload:
+    name: str
+    base: Workload        # shapes, seed, distributions, alpha, bias, activation
+    transA: bool          # A stored K x M
+    transB: bool          # B stored N x K
+    row_scale: bool       # fp32[M] ~ U(0.5, 1.5)
+    residual: str | None  # None, "f32" or "bf16": [batch, M, N] ~ U(-1, 1)
+    beta: float
+    clamp: tuple | None
+    out: str              # "f32" or "bf16"
+
+    @property
+    def flops(self) -> float:
+        return self.base.flops
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        """Read A, B, bias, row scale and the residual once, write C once."""
+        w = self.base
+        mn = w.batch * w.M * w.N
+        r = 0 if self.residual is None else mn * (4 if self.residual == "f32" else 2)
+        return float(w.batch * (w.M * w.K + w.K * w.N) * 2 + mn * (4 if self.out == "f32" else 2) + r
+                     + (0 if w.bias is None else 4 * w.N) + (4 * w.M if self.row_scale else 0))
+
+
+def _fw(name, M, N, K, batch, seed, dist, scale, alpha, bias, act, **kw):
+    return FusedWorkload(name, Workload(name, "bf16", M, N, K, batch, seed, dist, scale, alpha, bias, act), **kw)
+
+
+FUSED_WORKLOADS = {
+    # a linear layer as frameworks store it (weights N x K), bf16 activations out
+    "c6_fused_nt_8192_bias_gelu_bf16out": _fw(
+        "c6_fused_nt_8192_bias_gelu_bf16out", 8192, 8192, 8192, 1, 6, "normal", 8192 ** -0.5, 0.5, (-0.1, 0.1),
+        "gelu_tanh", transA=False, transB=True, row_scale=False, residual=None, beta=0.0, clamp=None, out="bf16"),
+    # both operands stored against the grain of the matrix unit, full consumer chain
+    "c7_fused_tn_8192_chain": _fw(
+        "c7_fused_tn_8192_chain", 8192, 8192, 8192, 1, 7, "normal", 8192 ** -0.5, 1.0, (-0.1, 0.1),
+        "relu", transA=True, transB=False, row_scale=True, residual="bf16", beta=0.5, clamp=(0.0, 6.0), out="bf16"),
+    # the batched small-K shape with bf16 residual in and bf16 out: half the store stream
+    "c8_fused_batched_512x512x64_bf16out": _fw(
+        "c8_fused_batched_512x512x64_bf16out", 512, 512, 64, 256, 8, "normal", 1.0, 1.0, (-1.0, 1.0),
+        "relu", transA=False, transB=False, row_scale=False, residual=None, beta=0.0, clamp=None, out="bf16"),
+}
+
+
+def make_fused_inputs(fw: FusedWorkload):
+    """Storage arrays of a fused workload: dict with A (batch, rowsA, colsA), B, bias, row_scale,
+    residual (or None each).  bf16 arrays are uint16 bit patterns."""
+    w = fw.base
+    A = make_operand(w, "A")
+    B = make_operand(w, "B")
+    if fw.transA:
+        A = np.ascontiguousarray(A.transpose(0, 2, 1))
+    if fw.transB:
+        B = np.ascontiguousarray(B.transpose(0, 2, 1))
+    rs = uniform(w.seed, STREAM_ROW_SCALE, w.M, 0.5, 1.5) if fw.row_scale else None
+    R = None
+    if fw.residual is not None:
+        R = uniform(w.seed, STREAM_RESIDUAL, w.batch * w.M * w.N, -1.0, 1.0).reshape(w.batch, w.M, w.N)
+        if fw.residual == "bf16":
+            R = to_bf16_bits(R)
+    return {"A": A, "B": B, "bias": make_bias(w), "row_scale": rs, "residual": R}

@@ -1,4 +1,4 @@
-"""The five synthetic workloads at full size, in the launch configuration bench.py
+"""The synthetic workloads at full size, in the launch configuration bench.py
 times (plain gemm_epilogue_* calls, library-chosen plan), checked against the oracle
 on sampled rows of C (whole first and last tiles' rows included) -- the oracle computes
 each sampled row exactly as it would in a full run.  The small fp32 workload is compared
@@ -71,3 +71,54 @@ def test_c5_bf16_splitk(oracle):
     assert cfg.endswith("_splitk")
     C2, _, _ = _run_workload(oracle, "c5_bf16_splitk_1024x1024x65536", 32)
     assert torch.equal(C1, C2), "split-K result must be bitwise repeatable"
+
+
+# ---------------------------------------------------------------- the widened operator's workloads
+def _run_fused_workload(oracle, name, rows_wanted, batches_wanted=4):
+    """Full-size fused workload through gemm_epilogue_bf16_fused, sampled rows against its oracle
+    (a row of the sample is computed exactly as in a full run: the oracle has one k loop per output)."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    fw = gen.FUSED_WORKLOADS[name]
+    w = fw.base
+    host = gen.make_fused_inputs(fw)
+    A, B = host["A"], host["B"]
+    dA, dB, dbias = to_device(A), to_device(B), to_device(host["bias"])
+    drs, dR = to_device(host["row_scale"]), to_device(host["residual"])
+    if dR is not None and fw.residual == "bf16":
+        dR = dR.view(torch.bfloat16)
+    C = torch.empty(w.batch, w.M, w.N, dtype=torch.float32 if fw.out == "f32" else torch.bfloat16, device="cuda:0")
+    print(f"fused workload {name}", flush=True)
+    binding.gemm_epilogue_bf16_fused(w.M, w.N, w.K, dA, A.shape[2], dB, B.shape[2], C, w.N, batch=w.batch,
+                                     transA=fw.transA, transB=fw.transB, alpha=w.alpha, row_scale=drs, bias=dbias,
+                                     residual=dR, ldr=w.N, beta=fw.beta, act=w.act, clamp=fw.clamp)
+    torch.cuda.synchronize()
+    cfg = binding.last_config()
+    rows = _sample_rows(w.M, rows_wanted)
+    bsel = np.unique(np.round(np.linspace(0, w.batch - 1, min(w.batch, batches_wanted))).astype(np.int64))
+    got = C[torch.from_numpy(bsel).cuda()][:, torch.from_numpy(rows).cuda()].to(torch.float32).cpu().numpy()
+    A_s = np.ascontiguousarray(A[bsel][:, :, rows] if fw.transA else A[bsel][:, rows])
+    rs_s = None if host["row_scale"] is None else host["row_scale"][rows]
+    R_s = None if host["residual"] is None else np.ascontiguousarray(host["residual"][bsel][:, rows])
+    ref = oracle.gemm_fused(len(rows), w.N, w.K, A_s, np.ascontiguousarray(B[bsel]), batch=len(bsel),
+                            transA=fw.transA, transB=fw.transB, alpha=w.alpha, row_scale=rs_s, bias=host["bias"],
+                            residual=R_s, beta=fw.beta, act=w.act, clamp=fw.clamp, out=fw.out)
+    compare(got, ref, f"{name} [{cfg}]")
+    return C, cfg
+
+
+def test_c6_fused_nt_bf16out(oracle):
+    _, cfg = _run_fused_workload(oracle, "c6_fused_nt_8192_bias_gelu_bf16out", 96)
+    assert cfg == "bf16_fused_256x256x32_w8_nt"
+
+
+def test_c7_fused_tn_chain(oracle):
+    C, cfg = _run_fused_workload(oracle, "c7_fused_tn_8192_chain", 96)
+    assert cfg == "bf16_fused_256x256x32_w8_tn"
+    assert 0.0 <= float(C.float().min()) and float(C.float().max()) <= 6.0      # relu then clamp(0, 6), everywhere
+
+
+def test_c8_fused_batched_bf16out(oracle):
+    C, cfg = _run_fused_workload(oracle, "c8_fused_batched_512x512x64_bf16out", 512, batches_wanted=6)
+    assert cfg == "bf16_fused_256x256x32_w8_nn"
+    assert float(C.float().min()) >= 0.0
