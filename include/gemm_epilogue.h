@@ -186,6 +186,33 @@ typedef struct ge_fused_args {
 
 ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
 
+/*
+ * Structured operand: A = diag(d), an M x M matrix given by its diagonal.
+ *
+ *     C[b][m,n] = act( alpha * d[m] * B[b][m,n] + bias[n] )
+ *
+ * This is gemm_epilogue_bf16 with A = diag(d) (equally: the widened operator with
+ * A = I and row_scale = d) computed without the M*M*N products that are zero.
+ * The paper's optimisation prompt asks to exploit a known operand structure
+ * ("Rules for GEMM": use specific characteristics of the input matrices), and
+ * its largest matmul speedup is this diagonal-matrix multiply (Experiments,
+ * "Variance of Speedup Results").  The work left is one scaled copy of B:
+ * bound by HBM, 2 bytes read and 4 written per output.
+ *   M, N, batch >= 1
+ *   d                 device, fp32[M], shared by every batch
+ *   B, ldb            device, bf16 bits, [M, ldb >= N] per batch (packed: M*ldb)
+ *   bias              device, fp32[N] or NULL
+ *   C, ldc            device, fp32 [M, ldc >= N] per batch; only C[m, 0..N) is written
+ * Errors: GE_ERR_NULL (d, B or C), GE_ERR_SHAPE, GE_ERR_LD, GE_ERR_ACT, GE_ERR_ALIGN,
+ * GE_ERR_LAUNCH.  Any alignment of B and C that their element types allow is
+ * accepted (16-byte row pieces when N, ldb, ldc are multiples of 4 and the
+ * pointers allow it, element-wise otherwise).
+ */
+ge_status_t gemm_epilogue_diag_bf16(int M, int N, const float *d,
+                                    const uint16_t *B, int ldb,
+                                    const float *bias, float alpha, ge_act_t act,
+                                    float *C, int ldc, int batch, void *stream);
+
 /* Bytes of split-K workspace the bf16 call needs for this shape with `plan` and
  * `split_k` as above (0 when the chosen plan is direct).  Host only. */
 size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch,

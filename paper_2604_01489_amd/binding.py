@@ -21,7 +21,8 @@ GE_OK = 0
 SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
            "ge_release_workspace", "ge_status_string", "ge_last_config",
-           "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused")
+           "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused",
+           "gemm_epilogue_diag_bf16")
 
 DTYPE = {"f32": 0, "bf16": 1}
 
@@ -84,6 +85,9 @@ def load():
     lib.ge_last_config.argtypes = []
     lib.gemm_epilogue_bf16_fused.restype = c_int
     lib.gemm_epilogue_bf16_fused.argtypes = [ctypes.POINTER(FusedArgs), c_void]
+    lib.gemm_epilogue_diag_bf16.restype = c_int
+    lib.gemm_epilogue_diag_bf16.argtypes = [c_int, c_int, c_void, c_void, c_int, c_void, c_float, c_int,
+                                            c_void, c_int, c_int, c_void]
     lib.ge_probe_mfma_bf16.restype = c_int
     lib.ge_probe_mfma_bf16.argtypes = [c_void, c_void, c_int, c_int, c_void]
     lib.ge_probe_store_f32.restype = c_int
@@ -203,6 +207,18 @@ def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA
                       workspace_ptr=_addr(workspace),
                       workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     _check(load().gemm_epilogue_bf16_fused(ctypes.byref(args), _stream_handle(stream)))
+
+
+def gemm_epilogue_diag_bf16(M, N, d, B, ldb, bias, alpha, act, C, ldc, batch=1, stream=None):
+    """``C = act(alpha * d[m] * B + bias[n])``: the operator with A = diag(d), on device tensors."""
+    _require_device(d, B, bias, C)
+    _check(load().gemm_epilogue_diag_bf16(M, N, _ptr(d), _ptr(B), ldb, _ptr(bias), alpha, ACT[act], _ptr(C), ldc,
+                                          batch, _stream_handle(stream)))
+
+
+def raw_diag(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch) -> int:
+    """The status code of ``gemm_epilogue_diag_bf16`` (for argument-error tests)."""
+    return int(load().gemm_epilogue_diag_bf16(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch, None))
 
 
 def probe_mfma_bf16(operands, sink, blocks, iters, stream=None):

@@ -260,3 +260,25 @@ def make_fused_inputs(fw: FusedWorkload):
         if fw.residual == "bf16":
             R = to_bf16_bits(R)
     return {"A": A, "B": B, "bias": make_bias(w), "row_scale": rs, "residual": R}
+
+
+# ---------------------------------------------------------------------------------------------
+# structured operand: A = diag(d).  K = M for the GEMM this replaces; the entry point itself
+# touches only d, B, bias and C.
+# ---------------------------------------------------------------------------------------------
+DIAG_WORKLOADS = {
+    "c9_diag_bf16_8192": Workload("c9_diag_bf16_8192", "bf16", 8192, 8192, 8192, 1, 9, "normal", 1.0, 0.5,
+                                  (-0.1, 0.1), "relu"),
+}
+
+
+def make_diag_inputs(w: Workload):
+    """(d fp32[M] ~ U(0.5, 1.5), B bf16 bits [batch, M, N], bias)."""
+    d = uniform(w.seed, STREAM_ROW_SCALE, w.M, 0.5, 1.5)
+    parts = [to_bf16_bits(_draw(w, STREAM_B, w.M * w.N, b * w.M * w.N).reshape(w.M, w.N)) for b in range(w.batch)]
+    return d, np.stack(parts), make_bias(w)
+
+
+def diag_algorithmic_bytes(w: Workload) -> float:
+    """Read B, d and bias once, write C once."""
+    return float(w.batch * w.M * w.N * (2 + 4) + 4 * w.M + (0 if w.bias is None else 4 * w.N))

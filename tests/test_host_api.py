@@ -84,6 +84,22 @@ def test_fused_argument_errors_return_codes(lib):
     assert binding.load().gemm_epilogue_bf16_fused(None, None) == 1
 
 
+def test_diag_argument_errors_return_codes(lib):
+    ok = dict(M=64, N=48, d=P, B=P, ldb=48, bias=None, alpha=1.0, act=0, C=P, ldc=48, batch=1)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return binding.raw_diag(a["M"], a["N"], a["d"], a["B"], a["ldb"], a["bias"], a["alpha"], a["act"], a["C"],
+                                a["ldc"], a["batch"])
+
+    assert call(d=None) == 1 and call(B=None) == 1 and call(C=None) == 1
+    assert call(M=0) == 2 and call(N=0) == 2 and call(batch=0) == 2
+    assert call(ldb=47) == 3 and call(ldc=47) == 3
+    assert call(act=5) == 4
+    assert call(B=P + 1) == 5 and call(C=P + 2) == 5 and call(d=P + 2) == 5 and call(bias=P + 1) == 5
+
+
 def test_ex_plan_errors(lib):
     base = (64, 64, 64, P, 64, P, 64, None, 1.0, 0, P, 64, 1)
     assert binding.raw_call("gemm_epilogue_bf16_ex", *base, extra=(7, 0, None, 0)) == 8
