@@ -27,10 +27,13 @@ _KIND = {np.dtype(np.float64): 0, np.dtype(np.float32): 1, np.dtype(np.uint16): 
 
 _FUSED_SRC = os.path.join(_HERE, "gemm_fused_oracle.c")
 _FUSED_LIB = os.path.join(_HERE, "libgemm_fused_oracle.so")
+_CONV_SRC = os.path.join(_HERE, "conv_oracle.c")
+_CONV_LIB = os.path.join(_HERE, "libconv_oracle.so")
 OUT = {"f64": 0, "f32": 1, "bf16": 2}
 
 _lib = None
 _fused = None
+_conv = None
 
 
 def compile_source(src: str, out: str) -> str:
@@ -44,7 +47,7 @@ def compile_source(src: str, out: str) -> str:
 def build(force: bool = False) -> str:
     """Compile the oracles that are missing or older than their source. Returns the path of the
     plain operator's library."""
-    for src, lib in ((_SRC, _LIB), (_FUSED_SRC, _FUSED_LIB)):
+    for src, lib in ((_SRC, _LIB), (_FUSED_SRC, _FUSED_LIB), (_CONV_SRC, _CONV_LIB)):
         if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
             compile_source(src, lib)
     return _LIB
@@ -225,3 +228,76 @@ def gemm_fused(M, N, K, A, B, *, batch=1, transA=False, transB=False, lda=None, 
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return C.reshape(batch, M, N)
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution front-end (channels-last), same consumer chain
+# ---------------------------------------------------------------------------------------------
+def _bind_conv(lib):
+    c = ctypes
+    lib.oracle_conv2d_nhwc.restype = c.c_int
+    lib.oracle_conv2d_nhwc.argtypes = [c.c_int] * 13 + [
+        c.c_void_p, c.c_void_p, c.c_int, c.c_double, c.c_void_p,
+        c.c_void_p, c.c_int, c.c_double, c.c_int, c.c_double, c.c_double, c.c_int, c.c_void_p]
+    lib.oracle_conv_out_size.restype = c.c_int
+    lib.oracle_conv_out_size.argtypes = [c.c_int] * 5
+    return lib
+
+
+def use_conv_library(path: str | None) -> None:
+    """As ``use_library`` for the convolution oracle."""
+    global _conv
+    _conv = None if path is None else _bind_conv(ctypes.CDLL(path))
+
+
+def _load_conv():
+    global _conv
+    if _conv is None:
+        build()
+        _conv = _bind_conv(ctypes.CDLL(_CONV_LIB))
+    return _conv
+
+
+def conv_out_size(size: int, k: int, stride: int = 1, pad: int = 0, dil: int = 1) -> int:
+    return int(_load_conv().oracle_conv_out_size(size, k, stride, pad, dil))
+
+
+def conv2d_nhwc(X, Wt, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias=None, residual=None,
+                beta=1.0, act="none", clamp=None, out="f64"):
+    """Reference convolution, channels-last: ``X`` [N,H,W,Cin], ``Wt`` [Cout,KH,KW,Cin] of one dtype
+    among float64, float32, uint16 (bf16 bits); ``residual`` [N,OH,OW,Cout] of any of them.
+    Returns fp64 [N,OH,OW,Cout] (rounded to fp32 / bf16 when ``out`` says so)."""
+    lib = _load_conv()
+    X = np.ascontiguousarray(X)
+    Wt = np.ascontiguousarray(Wt)
+    if X.dtype != Wt.dtype or X.dtype not in _KIND or X.ndim != 4 or Wt.ndim != 4:
+        raise TypeError("X and Wt must be 4-D arrays of one dtype among float64, float32, uint16(bf16 bits)")
+    Nb, H, W, Cin = X.shape
+    Cout, KH, KW, Cin2 = Wt.shape
+    if Cin2 != Cin:
+        raise ValueError("channel mismatch")
+    OH = conv_out_size(H, KH, stride[0], pad[0], dil[0])
+    OW = conv_out_size(W, KW, stride[1], pad[1], dil[1])
+    if OH < 1 or OW < 1:
+        raise ValueError("empty output")
+    bias_p = None
+    if bias is not None:
+        bias64 = np.ascontiguousarray(np.asarray(bias), dtype=np.float64)
+        if bias64.shape != (Cout,):
+            raise ValueError("bias must have length Cout")
+        bias_p = bias64.ctypes.data_as(ctypes.c_void_p)
+    r_p, r_kind = None, 0
+    if residual is not None:
+        R = np.ascontiguousarray(residual)
+        if R.shape != (Nb, OH, OW, Cout) or R.dtype not in _KIND:
+            raise ValueError("residual must be [N,OH,OW,Cout]")
+        r_p, r_kind = R.ctypes.data_as(ctypes.c_void_p), _KIND[R.dtype]
+    lo, hi = (-np.inf, np.inf) if clamp is None else clamp
+    Y = np.full((Nb, OH, OW, Cout), np.nan, dtype=np.float64)
+    rc = lib.oracle_conv2d_nhwc(Nb, H, W, Cin, Cout, KH, KW, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1],
+                                X.ctypes.data_as(ctypes.c_void_p), Wt.ctypes.data_as(ctypes.c_void_p), _KIND[X.dtype],
+                                float(alpha), bias_p, r_p, r_kind, float(beta), ACT[act], float(lo), float(hi),
+                                OUT[out], Y.ctypes.data_as(ctypes.c_void_p))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return Y
