@@ -190,6 +190,77 @@ def bench_diag(args, torch, binding, gen) -> int:
     return 0 if parity is None or parity["ok"] else 1
 
 
+def bench_conv(args, torch, binding, gen) -> int:
+    """The convolution front-end (implicit GEMM on the main kernel, fused consumer chain)."""
+    import oracle
+    cw = gen.CONV_WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    host = gen.make_conv_inputs(cw)
+    oh, ow = cw.out_hw()
+
+    def dev_bits(x):
+        return None if x is None else torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).to(dev)
+
+    dX, dW, dbias, dR = dev_bits(host["X"]), dev_bits(host["Wt"]), dev_bits(host["bias"]), dev_bits(host["residual"])
+    if dR is not None and cw.residual == "bf16":
+        dR = dR.view(torch.bfloat16)
+    dY = torch.empty(cw.N, oh, ow, cw.Cout, dtype=torch.float32 if cw.out == "f32" else torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        binding.conv2d_epilogue_bf16(dX, dW, dY, stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha, bias=dbias,
+                                     residual=dR, beta=cw.beta, act=cw.act, clamp=cw.clamp, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms_wall = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_dev = e0.elapsed_time(e1) / args.steps
+    config_name = binding.last_config()
+    achieved = cw.flops / (ms_dev * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": config_name,
+                "ms_per_launch": round(ms_dev, 4)}
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measured_ceilings(torch, binding, dX, stream)
+        roofline["frac_of_measured"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
+    cpu_baseline = parity = None
+    if args.oracle_rows > 0:
+        imgs = sorted({0, cw.N - 1})                    # first and last image: first and last tiles of the GEMM
+        sub = gen.make_conv_inputs(cw, imgs)
+        got = dY[torch.tensor(imgs, device=dev)].to(torch.float32).cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ref = oracle.conv2d_nhwc(sub["X"], sub["Wt"], stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha,
+                                 bias=sub["bias"], residual=sub["residual"], beta=cw.beta, act=cw.act, clamp=cw.clamp,
+                                 out=cw.out)
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(cw.flops * len(imgs) / cw.N / (c1 - c0) / 1e12, 6), "unit": "TFLOP/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"images {imgs} of {cw.N}, all positions and channels; {c1 - c0:.1f} s"}
+        err = np.abs(got - ref)
+        rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+        parity = {"outputs_checked": int(ref.size), "rel_frobenius": rel, "max_abs_err": float(err.max()),
+                  "ok": bool(rel <= 1e-3 and np.all(err <= 1e-2 * np.maximum(1.0, np.abs(ref))))}
+    out = {"metric": "TFLOP/s of the implicit-GEMM convolution with fused epilogue",
+           "value": round(cw.flops / (ms_wall * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms_wall, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "N": cw.N, "H": cw.H, "W": cw.W, "Cin": cw.Cin, "Cout": cw.Cout,
+                      "KH": cw.KH, "KW": cw.KW, "stride": cw.stride, "pad": cw.pad, "dil": cw.dil, "act": cw.act,
+                      "residual": cw.residual, "out_dtype": cw.out, "layout": "NHWC", "kernel": config_name},
+           "roofline": roofline, "ceilings": ceilings, "cpu_baseline": cpu_baseline, "parity": parity}
+    print(json.dumps(out))
+    return 0 if parity is None or parity["ok"] else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +300,8 @@ def main() -> int:
     binding.load()
     if args.workload in gen.DIAG_WORKLOADS:
         return bench_diag(args, torch, binding, gen)
+    if args.workload in gen.CONV_WORKLOADS:
+        return bench_conv(args, torch, binding, gen)
     fused = args.workload in gen.FUSED_WORKLOADS
     fw = gen.FUSED_WORKLOADS[args.workload] if fused else None
     w = fw.base if fused else gen.WORKLOADS[args.workload]

@@ -187,6 +187,49 @@ typedef struct ge_fused_args {
 ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
 
 /*
+ * Convolution front-end of the fused operator (bf16 operands, fp32 accumulation), channels-last:
+ *
+ *     S[n,oh,ow,co] = sum_{kh,kw,c} X[n, oh*stride_h - pad_h + kh*dil_h,
+ *                                        ow*stride_w - pad_w + kw*dil_w, c] * Wt[co,kh,kw,c]
+ *     Y[n,oh,ow,co] = round( min(max(act(alpha*S + bias[co] + beta*R[n,oh,ow,co]), clamp_lo), clamp_hi) )
+ *
+ * X is read as zero outside [0,H) x [0,W); OH = (H + 2 pad_h - dil_h (KH-1) - 1) / stride_h + 1,
+ * OW likewise.  This is the cross-correlation deep-learning frameworks call convolution,
+ * evaluated as the implicit GEMM of the paper's convolution guidance (optimisation prompt,
+ * convolution section: output positions x output channels, K = KH*KW*Cin, the im2col tile
+ * gathered on the fly) on the same matrix-instruction core and with the same fused consumer
+ * chain as gemm_epilogue_bf16_fused.  Channels-last storage is this library's reading: 8
+ * consecutive channels of one tap are then 16 contiguous bytes.
+ *
+ *   X                 device, bf16 bits, [N, H, W, Cin] packed
+ *   Wt                device, bf16 bits, [Cout, KH, KW, Cin] packed
+ *   bias              device, fp32[Cout] or NULL
+ *   R, r_type, beta   device residual [N, OH, OW, Cout] packed, or NULL
+ *   Y, y_type         device result [N, OH, OW, Cout] packed; GE_DTYPE_BF16 rounds to nearest-even
+ *   the other fields  as in ge_fused_args_t
+ * `args` is a HOST pointer, read before the call returns.  The gathering kernel needs X and
+ * Wt 16-byte aligned, Cin a multiple of 32, Cout a multiple of 8, an input smaller than
+ * 2 GiB and (for bf16 output) Y 16-byte aligned; any other legal argument list takes a guarded
+ * kernel with the same result contract.
+ * Errors: GE_ERR_NULL, GE_ERR_SHAPE (a size < 1, an empty output, index ranges), GE_ERR_ACT,
+ * GE_ERR_EPILOGUE, GE_ERR_ALIGN, GE_ERR_LAUNCH.
+ */
+typedef struct ge_conv_args {
+    int N, H, W, Cin, Cout, KH, KW;
+    int stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+    const uint16_t *X;
+    const uint16_t *Wt;
+    float alpha;
+    const float *bias;
+    const void *R; ge_dtype_t r_type; float beta;
+    ge_act_t act;
+    float clamp_lo, clamp_hi;
+    void *Y; ge_dtype_t y_type;
+} ge_conv_args_t;
+
+ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *stream);
+
+/*
  * Structured operand: A = diag(d), an M x M matrix given by its diagonal.
  *
  *     C[b][m,n] = act( alpha * d[m] * B[b][m,n] + bias[n] )

@@ -22,7 +22,7 @@ SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
            "ge_release_workspace", "ge_status_string", "ge_last_config",
            "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused",
-           "gemm_epilogue_diag_bf16")
+           "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16")
 
 DTYPE = {"f32": 0, "bf16": 1}
 
@@ -43,6 +43,16 @@ class FusedArgs(ctypes.Structure):
         ("plan", ctypes.c_int), ("split_k", ctypes.c_int),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
     ]
+
+
+class ConvArgs(ctypes.Structure):
+    """Mirror of ``ge_conv_args_t`` (include/gemm_epilogue.h)."""
+    _fields_ = [(n, ctypes.c_int) for n in ("N", "H", "W", "Cin", "Cout", "KH", "KW", "stride_h", "stride_w",
+                                            "pad_h", "pad_w", "dil_h", "dil_w")] + [
+        ("X", ctypes.c_void_p), ("Wt", ctypes.c_void_p), ("alpha", ctypes.c_float), ("bias", ctypes.c_void_p),
+        ("R", ctypes.c_void_p), ("r_type", ctypes.c_int), ("beta", ctypes.c_float),
+        ("act", ctypes.c_int), ("clamp_lo", ctypes.c_float), ("clamp_hi", ctypes.c_float),
+        ("Y", ctypes.c_void_p), ("y_type", ctypes.c_int)]
 
 
 _lib = None
@@ -85,6 +95,8 @@ def load():
     lib.ge_last_config.argtypes = []
     lib.gemm_epilogue_bf16_fused.restype = c_int
     lib.gemm_epilogue_bf16_fused.argtypes = [ctypes.POINTER(FusedArgs), c_void]
+    lib.conv2d_epilogue_bf16.restype = c_int
+    lib.conv2d_epilogue_bf16.argtypes = [ctypes.POINTER(ConvArgs), c_void]
     lib.gemm_epilogue_diag_bf16.restype = c_int
     lib.gemm_epilogue_diag_bf16.argtypes = [c_int, c_int, c_void, c_void, c_int, c_void, c_float, c_int,
                                             c_void, c_int, c_int, c_void]
@@ -207,6 +219,39 @@ def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA
                       workspace_ptr=_addr(workspace),
                       workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     _check(load().gemm_epilogue_bf16_fused(ctypes.byref(args), _stream_handle(stream)))
+
+
+def conv_args(shape, X_ptr, Wt_ptr, Y_ptr, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias_ptr=None,
+              R_ptr=None, r_type="f32", beta=1.0, act="none", clamp=None, y_type="f32") -> ConvArgs:
+    """Fill a ``ge_conv_args_t`` from raw addresses; ``shape`` = (N, H, W, Cin, Cout, KH, KW)."""
+    lo, hi = (-float("inf"), float("inf")) if clamp is None else clamp
+    return ConvArgs(*shape, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], X_ptr, Wt_ptr, alpha, bias_ptr,
+                    R_ptr, DTYPE[r_type], beta, ACT[act] if isinstance(act, str) else int(act), lo, hi, Y_ptr,
+                    DTYPE[y_type] if isinstance(y_type, str) else int(y_type))
+
+
+def raw_conv(args: ConvArgs) -> int:
+    """The status code of ``conv2d_epilogue_bf16`` (for argument-error tests)."""
+    return int(load().conv2d_epilogue_bf16(ctypes.byref(args), None))
+
+
+def conv2d_epilogue_bf16(X, Wt, Y, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias=None, residual=None,
+                         beta=1.0, act="none", clamp=None, stream=None):
+    """Channels-last convolution with the fused consumer chain on device tensors: ``X`` [N,H,W,Cin] and
+    ``Wt`` [Cout,KH,KW,Cin] hold bf16 (bits), ``Y`` [N,OH,OW,Cout] is float32 or bfloat16."""
+    import torch
+    _require_device(X, Wt, Y, bias, residual)
+
+    def kind(t):
+        return "f32" if t.dtype == torch.float32 else "bf16"
+
+    Nb, H, W, Cin = X.shape
+    Cout, KH, KW, _ = Wt.shape
+    args = conv_args((Nb, H, W, Cin, Cout, KH, KW), _addr(X), _addr(Wt), _addr(Y), stride=stride, pad=pad, dil=dil,
+                     alpha=alpha, bias_ptr=_addr(bias), R_ptr=_addr(residual),
+                     r_type=kind(residual) if residual is not None else "f32", beta=beta, act=act, clamp=clamp,
+                     y_type=kind(Y))
+    _check(load().conv2d_epilogue_bf16(ctypes.byref(args), _stream_handle(stream)))
 
 
 def gemm_epilogue_diag_bf16(M, N, d, B, ldb, bias, alpha, act, C, ldc, batch=1, stream=None):

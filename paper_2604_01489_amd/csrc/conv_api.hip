@@ -1,0 +1,124 @@
+// C-ABI of the convolution front-end: a channels-last convolution evaluated as an implicit GEMM
+// on the main bf16 kernel (rows = output positions gathered on the fly, columns = output
+// channels, k = filter tap x input channel) with the fused consumer chain.  See
+// include/gemm_epilogue.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/gemm_epilogue.h"
+#include "gemm_bf16_fast.h"
+#include "gemm_fused.h"
+#include "ge_host.h"
+
+namespace {
+
+using ge::GemmParams;
+using namespace ge_host;
+
+int out_size(int in, int k, int stride, int pad, int dil)
+{
+    const long long span = (long long)in + 2ll * pad - (long long)dil * (k - 1) - 1;
+    return span < 0 ? 0 : (int)(span / stride + 1);
+}
+
+template <int BM, int BN, int WM, int WN>
+void launch_conv(const GemmParams &p, bool edge, dim3 grid, hipStream_t st)
+{
+    constexpr int threads = WM * WN * 64;
+    const bool h = p.cType == ge::DT_BF16;
+    if (edge) {
+        if (h) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
+        else   hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
+    } else {
+        if (h) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
+        else   hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
+    }
+}
+
+}  // namespace
+
+extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *stream)
+{
+    if (!args) return GE_ERR_NULL;
+    const ge_conv_args_t &a = *args;
+    if (!a.X || !a.Wt || !a.Y) return GE_ERR_NULL;
+    if (a.N < 1 || a.H < 1 || a.W < 1 || a.Cin < 1 || a.Cout < 1 || a.KH < 1 || a.KW < 1) return GE_ERR_SHAPE;
+    if (a.stride_h < 1 || a.stride_w < 1 || a.pad_h < 0 || a.pad_w < 0 || a.dil_h < 1 || a.dil_w < 1) return GE_ERR_SHAPE;
+    const int OH = out_size(a.H, a.KH, a.stride_h, a.pad_h, a.dil_h), OW = out_size(a.W, a.KW, a.stride_w, a.pad_w, a.dil_w);
+    if (OH < 1 || OW < 1) return GE_ERR_SHAPE;
+    const long long M = (long long)a.N * OH * OW, K = (long long)a.KH * a.KW * a.Cin;
+    const long long xElems = (long long)a.N * a.H * a.W * a.Cin;
+    // the kernels index positions and k with 32-bit integers
+    if (M > 0x7fffffffll / 2 || K > 0x7fffffffll / 2 || xElems > (1ll << 40) || M * a.Cout > (1ll << 40)) return GE_ERR_SHAPE;
+    if (a.pad_h > (1 << 20) || a.pad_w > (1 << 20) || (long long)a.dil_h * a.KH > (1 << 20) || (long long)a.dil_w * a.KW > (1 << 20))
+        return GE_ERR_SHAPE;
+    if (a.act != GE_ACT_NONE && a.act != GE_ACT_RELU && a.act != GE_ACT_GELU_TANH) return GE_ERR_ACT;
+    if (a.y_type != GE_DTYPE_F32 && a.y_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
+    if (a.R && a.r_type != GE_DTYPE_F32 && a.r_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
+    if (!(a.clamp_lo <= a.clamp_hi)) return GE_ERR_EPILOGUE;
+    const uintptr_t yMask = a.y_type == GE_DTYPE_F32 ? 3u : 1u, rMask = a.r_type == GE_DTYPE_F32 ? 3u : 1u;
+    if ((((uintptr_t)a.X) & 1u) || (((uintptr_t)a.Wt) & 1u) || (((uintptr_t)a.Y) & yMask)) return GE_ERR_ALIGN;
+    if (a.R && (((uintptr_t)a.R) & rMask)) return GE_ERR_ALIGN;
+    if (a.bias && (((uintptr_t)a.bias) & 3u)) return GE_ERR_ALIGN;
+
+    // gathering kernel: a K step is 32 channels of one tap, chunks of 8 channels are 16 aligned
+    // bytes, byte offsets into the input fit 31 bits; bf16 output leaves in 16-byte row pieces
+    bool fast = !((((uintptr_t)a.X) | ((uintptr_t)a.Wt)) & 15u) && (a.Cin % 32 == 0) && (a.Cout % 8 == 0) &&
+                xElems * 2 < (1ll << 31) - (1 << 20) && K * 2 * 256 + 1024 < (1ll << 31);
+    if (a.y_type == GE_DTYPE_BF16 && (((uintptr_t)a.Y) & 15u)) fast = false;
+    Plan pl;
+    ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_DIRECT, 0, &pl);
+    if (st != GE_OK) return st;
+
+    GemmParams p{};
+    p.A = a.X; p.B = a.Wt; p.bias = a.bias; p.C = (float *)a.Y;
+    p.M = (int)M; p.N = a.Cout; p.K = (int)K;
+    p.lda = (int)K; p.ldb = (int)K; p.ldc = a.Cout;
+    p.strideA = 0; p.strideB = 0; p.strideC = 0;
+    p.batch = 1;
+    p.splitK = 1;
+    p.kPerSlice = pl.kPerSlice;
+    p.tilesM = pl.tilesM;
+    p.tilesN = pl.tilesN;
+    p.groupM = choose_group_m(pl.tilesM, pl.tilesN);
+    p.alpha = a.alpha;
+    p.act = (int)a.act;
+    p.bytesA = xElems * 2;
+    p.bytesB = (long long)a.Cout * K * 2;
+    p.R = a.R;
+    p.strideR = 0;
+    p.ldr = a.Cout;
+    p.rType = (int)a.r_type;
+    p.beta = a.R ? a.beta : 0.0f;
+    const int rElem = a.r_type == GE_DTYPE_BF16 ? 2 : 4;
+    p.rVec = (a.R && !(((uintptr_t)a.R) & 15u) && ((long long)a.Cout * rElem) % 16 == 0) ? 1 : 0;
+    p.clampLo = a.clamp_lo;
+    p.clampHi = a.clamp_hi;
+    p.cType = (int)a.y_type;
+    p.transA = 0;
+    p.transB = 1;
+    p.convH = a.H; p.convW = a.W; p.convCin = a.Cin; p.convKH = a.KH; p.convKW = a.KW;
+    p.convOH = OH; p.convOW = OW;
+    p.convSh = a.stride_h; p.convSw = a.stride_w; p.convPh = a.pad_h; p.convPw = a.pad_w;
+    p.convDh = a.dil_h; p.convDw = a.dil_w;
+
+    const dim3 grid((unsigned)((long long)pl.tilesM * pl.tilesN));
+    hipStream_t hs = (hipStream_t)stream;
+    switch (pl.tile) {
+    case TILE_256:
+        launch_conv<256, 256, 2, 4>(p, pl.edge, grid, hs);
+        g_last_config = "conv_bf16_256x256x32_w8";
+        break;
+    case TILE_128:
+        launch_conv<128, 128, 2, 2>(p, pl.edge, grid, hs);
+        g_last_config = "conv_bf16_128x128x32_w4";
+        break;
+    default:
+        hipLaunchKernelGGL(ge::conv_bf16_generic_kernel, grid, dim3(256), 0, hs, p);
+        g_last_config = "conv_bf16_generic_64x64x32";
+        break;
+    }
+    return hipGetLastError() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
+}

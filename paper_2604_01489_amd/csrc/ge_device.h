@@ -49,6 +49,9 @@ struct GemmParams {
     float clampLo, clampHi;
     int cType;
     int rVec;                  // a lane's 4 consecutive residual elements can be read in one piece
+    // convolution front-end only: geometry of the channels-last input and of the filter
+    int convH, convW, convCin, convKH, convKW, convOH, convOW;
+    int convSh, convSw, convPh, convPw, convDh, convDw;
     int transA, transB;        // operand stored transposed (read by the guarded kernel; the main
                                // kernel takes them as template arguments)
 };

@@ -110,8 +110,14 @@ struct Bf16Tile {
 // FUSED: the run-time epilogue of the widened operator (row scale, residual, clamp) instead of the
 // compile-time scale/bias/activation, with fp32 output straight from the accumulators or
 // (OUTBF16) bf16 output through LDS, for which the operands of the MFMA are swapped.
+// CONV: implicit-GEMM convolution (optimisation prompt, convolution section): the rows of A are
+// output positions of a channels-last input and are gathered on the fly -- K step t covers 32
+// channels of one filter tap, so the lane's chunk of a row is 16 contiguous bytes at
+// position base + tap offset, or zeros where the tap falls into the padding (the out-of-range
+// offset of the buffer load).  B is the filter bank stored [Cout][KH*KW*Cin] (TB), C the
+// channels-last output.
 template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT, bool TA = false, bool TB = false,
-          bool FUSED = false, bool OUTBF16 = false>
+          bool FUSED = false, bool OUTBF16 = false, bool CONV = false>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmParams p)
 {
@@ -119,6 +125,7 @@ gemm_bf16_kernel(const GemmParams p)
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
     static_assert(!(RAW && FUSED) && (FUSED || !OUTBF16), "partial tiles carry no epilogue; bf16 output is the fused one's");
+    static_assert(!CONV || (!TA && TB && FUSED), "convolution: gathered k-contiguous A, filters as N x K");
     static_assert((BM & (BM - 1)) == 0 && ((T::WTM / 32) & (T::WTM / 32 - 1)) == 0, "k-strided A stage");
 
     // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages
@@ -136,7 +143,7 @@ gemm_bf16_kernel(const GemmParams p)
     const int kLen = min(p.K - kBegin, p.kPerSlice);
     const int nk = (kLen + BK - 1) / BK;
 
-    const long long offA = 2 * ((long long)tc.b * p.strideA +
+    const long long offA = CONV ? 0ll : 2 * ((long long)tc.b * p.strideA +
                                 (TA ? (long long)kBegin * p.lda + m0 : (long long)m0 * p.lda + kBegin));
     const long long offB = 2 * ((long long)tc.b * p.strideB +
                                 (TB ? (long long)n0 * p.ldb + kBegin : (long long)kBegin * p.ldb + n0));
@@ -148,9 +155,25 @@ gemm_bf16_kernel(const GemmParams p)
     // the chunk along k (k-contiguous stage) or the k row (k-strided stage) ---------------
     unsigned voffA[T::A_LOADS], voffB[T::B_LOADS];
     int kA[T::A_LOADS], kB[T::B_LOADS];
+    // convolution: input row and column of filter tap (0, 0) for the lane's output position
+    // (far out of range for rows past M, so that every tap test fails)
+    int ih0[CONV ? T::A_LOADS : 1], iw0[CONV ? T::A_LOADS : 1];
 #pragma unroll
     for (int j = 0; j < T::A_LOADS; ++j) {
-        if (!TA) {
+        if (CONV) {
+            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);
+            const int m = m0 + row;
+            const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
+            const int oh = pos / p.convOW, ow = pos % p.convOW;
+            const int ihTap0 = oh * p.convSh - p.convPh;
+            ih0[j] = m < p.M ? ihTap0 : -(1 << 24);
+            iw0[j] = ow * p.convSw - p.convPw;
+            kA[j] = c * 8;
+            // byte offset of (img, ih0, iw0, channel 8c) modulo 2^32: it may be "negative" for a tap
+            // in the padding, and adding the tap offset of an inside tap brings it back into
+            // [0, 2^31) (the host checks that the input is smaller than that)
+            voffA[j] = ((unsigned)((img * p.convH + ihTap0) * p.convW + iw0[j]) * (unsigned)p.convCin + (unsigned)(c * 8)) * 2u;
+        } else if (!TA) {
             const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);   // 1 KB slab = 16 rows
             kA[j] = c * 8;
             voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
@@ -180,26 +203,46 @@ gemm_bf16_kernel(const GemmParams p)
     // Tiles past the end of the K range are fetched through a zero-length resource:
     // every lane is out of range, nothing is read and zeros land in a stage nobody
     // consumes, so the number of loads in flight is the same in every step.
+    // convolution: filter tap and first channel of the next K step to be issued (the steps are
+    // issued in ascending order, so the state advances by 32 channels per call, on the scalar unit)
+    int tapH = 0, tapW = 0, tapC = 0;
+    if (CONV) {
+        const int tap = kBegin / p.convCin;
+        tapC = kBegin % p.convCin;
+        tapH = tap / p.convKW;
+        tapW = tap % p.convKW;
+    }
     auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
-        const long long stepA = TA ? (long long)kt * BK * p.lda * 2 : (long long)kt * (BK * 2);
+        const long long stepA = CONV ? 0ll : TA ? (long long)kt * BK * p.lda * 2 : (long long)kt * (BK * 2);
         const long long stepB = TB ? (long long)kt * (BK * 2) : (long long)kt * BK * p.ldb * 2;
         // Full tiles: every offset lies inside the operand by construction, and the exact extent
         // (ten scalar instructions per step, measured at 1-3 % of the 8192^3 run) is skipped.
         // Edge tiles: the resource ends where the operand ends, so a lane that is not masked for
         // whatever reason reads zeros instead of memory beyond the allocation.  Computed
         // unconditionally, then selected: a conditional around it would be a scalar branch.
-        const unsigned leftA = EDGE ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
+        const unsigned leftA = (EDGE || CONV) ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
         const unsigned leftB = EDGE ? records_left(p.bytesB, offB + stepB) : RSRC_RECORDS;
         const unsigned recA = kt < nk ? leftA : 0u;
         const unsigned recB = kt < nk ? leftB : 0u;
         const rsrc_words_t rA = make_rsrc(gA + stepA, recA);
         const rsrc_words_t rB = make_rsrc(gB + stepB, recB);
         const int kLeft = kLen - kt * BK;            // valid k in this tile (EDGE only)
+        const int dIh = tapH * p.convDh, dIw = tapW * p.convDw;
+        const unsigned tapOff = (unsigned)(((dIh * p.convW + dIw) * p.convCin + tapC) * 2);
 #pragma unroll
         for (int j = 0; j < T::A_LOADS; ++j) {
             unsigned v = voffA[j];
+            if (CONV) {
+                const bool inside = (unsigned)(ih0[j] + dIh) < (unsigned)p.convH && (unsigned)(iw0[j] + dIw) < (unsigned)p.convW;
+                v = inside ? v + tapOff : OOB_OFFSET;
+            }
             if (EDGE && kA[j] >= kLeft) v = OOB_OFFSET;
             lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
+        }
+        if (CONV) {
+            tapC += BK;
+            if (tapC >= p.convCin) { tapC = 0; ++tapW; }
+            if (tapW >= p.convKW) { tapW = 0; ++tapH; }
         }
 #pragma unroll
         for (int j = 0; j < T::B_LOADS; ++j) {

@@ -2,6 +2,8 @@
 // lists the direct-to-LDS kernel does not take (odd sizes, unaligned pointers, odd leading
 // dimensions), with operands stored either way round, and the second pass of split-K with
 // the run-time epilogue.  Every global access is predicated (Debugging guide, checklist "Edges").
+// (The two kernels that are not templates have internal linkage: this header is included by
+// more than one translation unit.)
 #pragma once
 #include "ge_device.h"
 
@@ -93,10 +95,78 @@ gemm_bf16_fused_generic_kernel(const GemmParams p)
     }
 }
 
+// Convolution for argument lists the gathering main kernel does not take (channel counts that are
+// not multiples of 32, unaligned pointers): the same implicit GEMM (rows = output positions,
+// columns = output channels, k = (tap, channel)) with every element of the im2col tile fetched
+// under its own bounds test.  64x64 tile, K step 32, 4 waves; B is the filter bank [Cout][K].
+static __global__ void __launch_bounds__(256)
+conv_bf16_generic_kernel(const GemmParams p)
+{
+    constexpr int BM = 64, BN = 64, BK = 32, LD = BK + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LD];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LD];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    const TileCoord tc = map_block(p);
+    const int m0 = tc.tm * BM, n0 = tc.tn * BN;
+    const uint16_t *X = (const uint16_t *)p.A;
+    const uint16_t *Wt = (const uint16_t *)p.B;
+
+    // the output position of the A row this thread fills (threads walk k fastest: row = e / BK)
+    f32x16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+
+    for (int k0 = 0; k0 < p.K; k0 += BK) {
+#pragma unroll
+        for (int i = 0; i < BM * BK / 256; ++i) {
+            const int e = tid + i * 256, row = e / BK, k = e % BK;
+            const int m = m0 + row, kk = k0 + k;
+            uint16_t v = 0;
+            if (m < p.M && kk < p.K) {
+                const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
+                const int oh = pos / p.convOW, ow = pos % p.convOW;
+                const int tap = kk / p.convCin, c = kk % p.convCin;
+                const int ih = oh * p.convSh - p.convPh + (tap / p.convKW) * p.convDh;
+                const int iw = ow * p.convSw - p.convPw + (tap % p.convKW) * p.convDw;
+                if (ih >= 0 && ih < p.convH && iw >= 0 && iw < p.convW)
+                    v = X[(((long long)img * p.convH + ih) * p.convW + iw) * p.convCin + c];
+            }
+            sA[row * LD + k] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < BK * BN / 256; ++i) {
+            const int e = tid + i * 256, col = e / BK, k = e % BK;
+            const int n = n0 + col, kk = k0 + k;
+            uint16_t v = 0;
+            if (n < p.N && kk < p.K) v = Wt[(long long)n * p.K + kk];
+            sB[col * LD + k] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int kk = ks * 16 + (lane >> 5) * 8;
+            bf16x8_t a = *(const bf16x8_t *)&sA[(wm * 32 + (lane & 31)) * LD + kk];
+            bf16x8_t b = *(const bf16x8_t *)&sB[(wn * 32 + (lane & 31)) * LD + kk];
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    const int n = n0 + wn * 32 + (lane & 31);
+    if (n >= p.N) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < p.M) fused_store(p, 0, m, n, acc[r]);
+    }
+}
+
 // Split-K second pass of the widened operator: slices added in ascending order by one thread
 // per output (no atomics: bitwise repeatable), then the run-time epilogue.  W holds
 // [slice][batch][M][N] fp32 partial sums.
-__global__ void __launch_bounds__(256)
+static __global__ void __launch_bounds__(256)
 splitk_reduce_fused_kernel(const GemmParams p, const float *__restrict__ W)
 {
     const long long total = (long long)p.batch * p.M * p.N;

@@ -282,3 +282,74 @@ def make_diag_inputs(w: Workload):
 def diag_algorithmic_bytes(w: Workload) -> float:
     """Read B, d and bias once, write C once."""
     return float(w.batch * w.M * w.N * (2 + 4) + 4 * w.M + (0 if w.bias is None else 4 * w.N))
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution front-end (channels-last): a 3x3 layer of a residual network's middle stage
+# ---------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class ConvWorkload:
+    name: str
+    N: int
+    H: int
+    W: int
+    Cin: int
+    Cout: int
+    KH: int
+    KW: int
+    stride: tuple
+    pad: tuple
+    dil: tuple
+    seed: int
+    alpha: float
+    bias: tuple | None
+    residual: str | None
+    beta: float
+    act: str
+    clamp: tuple | None
+    out: str
+
+    def out_hw(self):
+        oh = (self.H + 2 * self.pad[0] - self.dil[0] * (self.KH - 1) - 1) // self.stride[0] + 1
+        ow = (self.W + 2 * self.pad[1] - self.dil[1] * (self.KW - 1) - 1) // self.stride[1] + 1
+        return oh, ow
+
+    @property
+    def flops(self) -> float:
+        oh, ow = self.out_hw()
+        return 2.0 * self.N * oh * ow * self.Cout * self.KH * self.KW * self.Cin
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        oh, ow = self.out_hw()
+        y = self.N * oh * ow * self.Cout
+        r = 0 if self.residual is None else y * (4 if self.residual == "f32" else 2)
+        return float(self.N * self.H * self.W * self.Cin * 2 + self.Cout * self.KH * self.KW * self.Cin * 2
+                     + y * (4 if self.out == "f32" else 2) + r + (0 if self.bias is None else 4 * self.Cout))
+
+
+CONV_WORKLOADS = {
+    "c10_conv3x3_256_bf16out": ConvWorkload("c10_conv3x3_256_bf16out", 32, 56, 56, 256, 256, 3, 3, (1, 1), (1, 1), (1, 1),
+                                            10, 1.0, (-0.1, 0.1), "bf16", 1.0, "relu", None, "bf16"),
+}
+
+
+def make_conv_inputs(cw: ConvWorkload, images=None):
+    """X [n,H,W,Cin] ~ N(0,1), Wt [Cout,KH,KW,Cin] ~ N(0,1)/sqrt(KH*KW*Cin) (bf16 bits), bias, residual
+    [n,OH,OW,Cout] ~ U(-1,1); ``images`` selects image indices (default all), each image's values
+    being the same whichever subset is produced."""
+    images = range(cw.N) if images is None else images
+    oh, ow = cw.out_hw()
+    per_x, per_y = cw.H * cw.W * cw.Cin, oh * ow * cw.Cout
+    X = np.stack([to_bf16_bits(normal(cw.seed, STREAM_A, per_x, 1.0, i * per_x).reshape(cw.H, cw.W, cw.Cin))
+                  for i in images])
+    kk = cw.KH * cw.KW * cw.Cin
+    Wt = to_bf16_bits(normal(cw.seed, STREAM_B, cw.Cout * kk, kk ** -0.5).reshape(cw.Cout, cw.KH, cw.KW, cw.Cin))
+    bias = None if cw.bias is None else uniform(cw.seed, STREAM_BIAS, cw.Cout, cw.bias[0], cw.bias[1])
+    R = None
+    if cw.residual is not None:
+        R = np.stack([uniform(cw.seed, STREAM_RESIDUAL, per_y, -1.0, 1.0, i * per_y).reshape(oh, ow, cw.Cout)
+                      for i in images])
+        if cw.residual == "bf16":
+            R = to_bf16_bits(R)
+    return {"X": X, "Wt": Wt, "bias": bias, "residual": R}

@@ -1,0 +1,85 @@
+"""GPU parity of the convolution front-end (conv2d_epilogue_bf16) against the direct-convolution
+oracle: the gathering implicit-GEMM kernel on both tile shapes, full and ragged tiles, strides,
+paddings, dilations, the consumer chain with fp32 and bf16 output, and the guarded kernel."""
+import numpy as np
+import pytest
+
+from gpu_util import compare, to_device, torch_device
+
+pytestmark = pytest.mark.gpu
+
+
+def run_conv_case(oracle, shape, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, with_bias=True,
+                  residual=None, beta=1.0, act="none", clamp=None, out="f32", seed=0, expect=None):
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    Nb, H, W, Cin, Cout, KH, KW = shape
+    OH = oracle.conv_out_size(H, KH, stride[0], pad[0], dil[0])
+    OW = oracle.conv_out_size(W, KW, stride[1], pad[1], dil[1])
+    X = gen.to_bf16_bits(gen.normal(seed, gen.STREAM_A, Nb * H * W * Cin, 1.0).reshape(Nb, H, W, Cin))
+    Wt = gen.to_bf16_bits(gen.normal(seed, gen.STREAM_B, Cout * KH * KW * Cin, (KH * KW * Cin) ** -0.5)
+                          .reshape(Cout, KH, KW, Cin))
+    bias = gen.uniform(seed, gen.STREAM_BIAS, Cout, -1.0, 1.0) if with_bias else None
+    R = None
+    if residual is not None:
+        R = gen.uniform(seed, gen.STREAM_RESIDUAL, Nb * OH * OW * Cout, -1.0, 1.0).reshape(Nb, OH, OW, Cout)
+        if residual == "bf16":
+            R = gen.to_bf16_bits(R)
+    dX, dW, dbias, dR = to_device(X), to_device(Wt), to_device(bias), to_device(R)
+    if dR is not None and residual == "bf16":
+        dR = dR.view(torch.bfloat16)
+    ydtype = torch.float32 if out == "f32" else torch.bfloat16
+    Y = torch.full((Nb, OH, OW, Cout), -7.0e30, dtype=ydtype, device=torch_device())
+    print(f"conv case {shape} stride={stride} pad={pad} dil={dil} act={act} out={out} res={residual} clamp={clamp}",
+          flush=True)
+    binding.conv2d_epilogue_bf16(dX, dW, Y, stride=stride, pad=pad, dil=dil, alpha=alpha, bias=dbias, residual=dR,
+                                 beta=beta, act=act, clamp=clamp)
+    torch.cuda.synchronize()
+    cfg = binding.last_config()
+    if expect is not None:
+        assert cfg == expect, cfg
+    got = Y.to(torch.float32).cpu().numpy()
+    ref = oracle.conv2d_nhwc(X, Wt, stride=stride, pad=pad, dil=dil, alpha=alpha, bias=bias, residual=R, beta=beta,
+                             act=act, clamp=clamp, out=out)
+    compare(got.reshape(1, -1, Cout), ref.reshape(1, -1, Cout), f"{cfg} conv {shape}")
+    return cfg
+
+
+def test_conv_3x3_tiles_128(oracle):
+    run_conv_case(oracle, (2, 20, 20, 64, 64, 3, 3), pad=(1, 1), act="relu", seed=1, expect="conv_bf16_128x128x32_w4")
+    run_conv_case(oracle, (1, 16, 16, 32, 128, 3, 3), pad=(1, 1), seed=2, expect="conv_bf16_128x128x32_w4")   # 256 x 128: full tiles
+
+
+def test_conv_3x3_tiles_256(oracle):
+    run_conv_case(oracle, (4, 16, 16, 32, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=3,
+                  expect="conv_bf16_256x256x32_w8")                                                      # 1024 x 256: full tiles
+    run_conv_case(oracle, (1, 18, 19, 64, 264, 3, 3), pad=(1, 1), act="relu", seed=4, expect="conv_bf16_256x256x32_w8")
+
+
+@pytest.mark.parametrize("stride,pad,dil,k", [
+    ((2, 2), (1, 1), (1, 1), (3, 3)),
+    ((2, 1), (0, 2), (1, 1), (3, 5)),
+    ((1, 2), (2, 0), (2, 1), (3, 2)),
+    ((3, 2), (0, 3), (1, 2), (1, 4)),
+    ((1, 1), (0, 0), (1, 1), (1, 1)),
+    ((1, 1), (3, 3), (2, 2), (3, 3)),
+])
+def test_conv_geometry(oracle, stride, pad, dil, k):
+    run_conv_case(oracle, (2, 17, 23, 32, 72, k[0], k[1]), stride=stride, pad=pad, dil=dil, act="relu",
+                  seed=10 + k[0] + 3 * k[1], expect="conv_bf16_128x128x32_w4")
+
+
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("residual", [None, "f32", "bf16"])
+def test_conv_chain(oracle, out, residual):
+    for shape in [(2, 14, 14, 64, 256, 3, 3), (1, 15, 13, 32, 64, 3, 3)]:
+        run_conv_case(oracle, shape, pad=(1, 1), alpha=0.75, residual=residual, beta=0.5, act="relu",
+                      clamp=(0.0, 1.5), out=out, seed=20)
+
+
+def test_conv_guarded_kernel(oracle):
+    run_conv_case(oracle, (2, 21, 19, 3, 10, 7, 7), stride=(2, 2), pad=(3, 3), act="relu", seed=30,
+                  expect="conv_bf16_generic_64x64x32")                                    # first-layer shape: Cin = 3
+    run_conv_case(oracle, (1, 9, 9, 40, 24, 3, 3), pad=(1, 1), residual="f32", out="bf16", seed=31,
+                  expect="conv_bf16_generic_64x64x32")                                    # Cin not a multiple of 32
+    run_conv_case(oracle, (1, 8, 8, 32, 12, 1, 1), seed=32, expect="conv_bf16_generic_64x64x32")   # Cout not a multiple of 8

@@ -22,7 +22,7 @@ def test_exports_every_declared_symbol(lib):
     inc = os.path.join(ROOT, "include")
     header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*)\s*\(", header))
+    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*|conv2d_epilogue\w*)\s*\(", header))
     assert declared == set(binding.SYMBOLS), declared ^ set(binding.SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -98,6 +98,21 @@ def test_diag_argument_errors_return_codes(lib):
     assert call(ldb=47) == 3 and call(ldc=47) == 3
     assert call(act=5) == 4
     assert call(B=P + 1) == 5 and call(C=P + 2) == 5 and call(d=P + 2) == 5 and call(bias=P + 1) == 5
+
+
+def test_conv_argument_errors_return_codes(lib):
+    def call(shape=(1, 8, 8, 32, 16, 3, 3), X=P, Wt=P, Y=P, **kw):
+        return binding.raw_conv(binding.conv_args(shape, X, Wt, Y, **kw))
+
+    assert call(X=None) == 1 and call(Wt=None) == 1 and call(Y=None) == 1
+    assert binding.load().conv2d_epilogue_bf16(None, None) == 1
+    assert call(shape=(0, 8, 8, 32, 16, 3, 3)) == 2 and call(shape=(1, 8, 8, 0, 16, 3, 3)) == 2
+    assert call(shape=(1, 2, 2, 32, 16, 3, 3)) == 2                 # kernel larger than the input: empty output
+    assert call(shape=(1, 2, 2, 32, 16, 3, 3), pad=(1, 1)) == 7     # with padding it fits (no device here: launch fails)
+    assert call(stride=(0, 1)) == 2 and call(pad=(-1, 0)) == 2 and call(dil=(1, 0)) == 2
+    assert call(act=3) == 4
+    assert call(clamp=(2.0, 1.0)) == 9 and call(y_type=2) == 9
+    assert call(X=P + 1) == 5 and call(Y=P + 2) == 5 and call(bias_ptr=P + 1) == 5 and call(R_ptr=P + 2) == 5
 
 
 def test_ex_plan_errors(lib):
