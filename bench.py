@@ -46,17 +46,20 @@ BOUND = {
 # WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
 # dropped (reported as null) as soon as the hash of csrc/ changes.
 TRAFFIC = {
-    "source_hash": "37dc9d1e20e834d5",
+    "source_hash": "091c9914a1fa185a",
     "bytes_per_launch": {
-        "c3_bf16_8192_bias_gelu": (814763 * 2.0 + 263117 * 1.0) * 1024,
-        "c4_bf16_batched_512x512x64": (16484 * 2.0 + 262152 * 1.0) * 1024,
+        "c3_bf16_8192_bias_gelu": (802885 * 2.0 + 263557 * 1.0) * 1024,
+        "c4_bf16_batched_512x512x64": (16483 * 2.0 + 262155 * 1.0) * 1024,
+        "c6_fused_nt_8192_bias_gelu_bf16out": (879397 * 2.0 + 131072 * 1.0) * 1024,
+        "c8_fused_batched_512x512x64_bf16out": (16620 * 2.0 + 131072 * 1.0) * 1024,
+        "c10_conv3x3_256_bf16out": (100063 * 2.0 + 50176 * 1.0) * 1024,
     },
 }
 
 
 # the sources the GEMM kernels and their dispatch are built from (the probes are not among them)
-KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h",
-                  "gemm_epilogue_api.hip")
+KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "ge_host.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h",
+                  "gemm_fused.h", "gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip")
 
 
 def kernel_source_hash() -> str:
@@ -226,8 +229,8 @@ def bench_conv(args, torch, binding, gen) -> int:
     config_name = binding.last_config()
     achieved = cw.flops / (ms_dev * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None, "kernel": config_name,
-                "ms_per_launch": round(ms_dev, 4)}
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
+                "kernel": config_name, "ms_per_launch": round(ms_dev, 4)}
     ceilings = None
     if not args.no_ceilings:
         ceilings = measured_ceilings(torch, binding, dX, stream)
