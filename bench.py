@@ -367,6 +367,14 @@ def main() -> int:
     ms_wall = (t1 - t0) * 1e3 / args.steps
     ms_dev = ev0.elapsed_time(ev1) / args.steps     # HIP events on the launch stream
     config_name = binding.last_config()
+    # spread of single launches (outside the timed region): an event pair around each of 20 launches
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+    for a, b in pairs:
+        a.record(stream)
+        step()
+        b.record(stream)
+    torch.cuda.synchronize()
+    singles = sorted(a.elapsed_time(b) for a, b in pairs)
 
     tflops = job.flops / (ms_wall * 1e-3) / 1e12
     bound = BOUND[args.workload]
@@ -381,6 +389,7 @@ def main() -> int:
     roofline["traffic"] = measured_traffic(args.workload)     # HBM-side bytes per launch, or null
     roofline["kernel"] = config_name
     roofline["ms_per_launch"] = round(ms_dev, 4)
+    roofline["ms_single_launch"] = {"median": round(singles[len(singles) // 2], 4), "min": round(singles[0], 4)}
     ceilings = None
     if not args.no_ceilings:
         ceilings = measured_ceilings(torch, binding, dA, stream)
