@@ -1,0 +1,53 @@
+"""The entry points enqueue kernels only (no allocation, no memset, no synchronisation when the
+caller provides the split-K workspace), so a stream capture of them replays correctly.  Every
+replay is checked against the eager result, with eager work and synchronisations between replays."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+def test_calls_replay_from_a_captured_graph():
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    dev = torch.device("cuda:0")
+    M, N, K = 512, 512, 256
+    A = torch.from_numpy(gen.to_bf16_bits(gen.normal(70, 0, M * K, K ** -0.5).reshape(M, K)).view(np.int16)).to(dev)
+    B = torch.from_numpy(gen.to_bf16_bits(gen.normal(70, 1, K * N, 1.0).reshape(K, N)).view(np.int16)).to(dev)
+    bias = torch.from_numpy(gen.uniform(70, 2, N, -1.0, 1.0)).to(dev)
+    Kbig = 8192
+    A2 = torch.from_numpy(gen.to_bf16_bits(gen.normal(71, 0, 256 * Kbig, Kbig ** -0.5).reshape(256, Kbig)).view(np.int16)).to(dev)
+    B2 = torch.from_numpy(gen.to_bf16_bits(gen.normal(71, 1, Kbig * 256, 1.0).reshape(Kbig, 256)).view(np.int16)).to(dev)
+    split = 8
+    ws = torch.empty(binding.workspace_bytes(256, 256, Kbig, 1, "splitk", split) // 4, dtype=torch.float32, device=dev)
+
+    def enqueue(C1, C2, C3, stream):
+        binding.gemm_epilogue_bf16(M, N, K, A, K, B, N, bias, 0.5, "gelu_tanh", C1, N, stream=stream)
+        binding.gemm_epilogue_bf16_ex(256, 256, Kbig, A2, Kbig, B2, 256, None, 1.0, "none", C2, 256, plan="splitk",
+                                      split_k=split, workspace=ws, stream=stream)
+        binding.gemm_epilogue_bf16_fused(M, N, K, A, K, B, N, C3, N, alpha=0.5, bias=bias, act="relu", clamp=(0.0, 1.0),
+                                         stream=stream)
+
+    eager = [torch.empty(M, N, device=dev), torch.empty(256, 256, device=dev), torch.empty(M, N, dtype=torch.bfloat16, device=dev)]
+    enqueue(*eager, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+
+    out = [torch.zeros_like(t) for t in eager]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        print("capturing", flush=True)
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(*out, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in out:
+            t.fill_(-1.0)                    # eager work between replays
+        torch.cuda.synchronize()
+        print(f"replay {replay}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(out, eager):
+            assert torch.equal(got, want), f"replay {replay} differs from the eager result"
