@@ -35,4 +35,10 @@ size_t partial_bytes(int M, int N, int batch, int splitK);
 int choose_group_m(int tilesM, int tilesN);
 ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void **out);
 
+// The plain operator C = act(alpha A B + bias) (row-major operands, fp32 out): what the plain
+// entry points call, and what the widened one calls when none of its extras is in use.
+ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
+                     const float *bias, float alpha, ge_act_t act, float *C, int ldc, int batch,
+                     ge_plan_t plan, int split_k, void *workspace, size_t workspace_bytes, void *stream);
+
 }  // namespace ge_host

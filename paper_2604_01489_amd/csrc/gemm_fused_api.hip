@@ -104,6 +104,12 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     const ge_fused_args_t &a = *args;
     ge_status_t st = validate(a);
     if (st != GE_OK) return st;
+    // nothing but scale, bias and activation on row-major operands with fp32 output: the plain
+    // operator, whose kernels carry the activation as a compile-time choice
+    if (!a.transA && !a.transB && !a.row_scale && !a.R && a.c_type == GE_DTYPE_F32 && std::isinf(a.clamp_lo) &&
+        a.clamp_lo < 0 && std::isinf(a.clamp_hi) && a.clamp_hi > 0)
+        return run_bf16(a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb, a.bias, a.alpha, a.act, (float *)a.C, a.ldc, a.batch, a.plan,
+                        a.split_k, a.workspace, a.workspace_bytes, stream);
     Plan pl;
     st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a), a.plan, a.split_k, &pl);
     if (st != GE_OK) return st;

@@ -19,14 +19,15 @@ def test_layouts_tile_256(oracle, transA, transB):
     """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded."""
     for M, N, K, pad in [(256, 256, 64, (0, 0, 0, 0)), (512, 768, 256, (8, 16, 0, 4)), (520, 776, 328, (24, 8, 0, 0))]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, act="gelu_tanh",
-                                      pad=pad, seed=M + K + 2 * transA + transB)
+                                      with_row_scale=True, pad=pad, seed=M + K + 2 * transA + transB)
         assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}"
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
 def test_layouts_tile_128(oracle, transA, transB):
     for M, N, K in [(128, 128, 192), (136, 248, 200), (8, 8, 8), (64, 384, 40)]:
-        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", seed=3 * M + K)
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", with_row_scale=True,
+                                      seed=3 * M + K)
         assert cfg == f"bf16_fused_128x128x32_w4_{NAME[transA, transB]}"
 
 
@@ -75,16 +76,20 @@ def test_split_k(oracle, transA, transB):
                                   plan="splitk", split_k=0, seed=41)
     assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}_splitk"
     _, _, _, cfg = run_fused_case(oracle, 130, 70, 1500, transA=transA, transB=transB, alpha=1.0 / 32,
-                                  plan="splitk", split_k=3, seed=42)
+                                  with_row_scale=True, plan="splitk", split_k=3, seed=42)
     assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}_splitk"
 
 
 def test_plain_operator_is_the_special_case(oracle):
-    """Extras off, fp32 output, both operands as stored by the plain entry point: same bits."""
+    """Extras off, fp32 output, both operands as stored by the plain entry point: the call is routed to
+    the plain operator's kernels (same bits); one extra switched on keeps the fused kernel."""
     for M, N, K in [(512, 512, 256), (200, 136, 72), (67, 45, 33)]:
-        got_f, _, _, _ = run_fused_case(oracle, M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
-        got_p, _, _, _ = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
+        got_f, _, _, cfg_f = run_fused_case(oracle, M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
+        got_p, _, _, cfg_p = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=5)
+        assert cfg_f == cfg_p and not cfg_f.startswith("bf16_fused")
         assert np.array_equal(got_f, got_p)
+    _, _, _, cfg = run_fused_case(oracle, 512, 512, 256, alpha=0.5, act="gelu_tanh", clamp=(-1.0, 1.0), seed=5)
+    assert cfg == "bf16_fused_256x256x32_w8_nn"
 
 
 def test_diagonal_times_dense(oracle):
