@@ -46,20 +46,20 @@ BOUND = {
 # WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
 # dropped (reported as null) as soon as the hash of csrc/ changes.
 TRAFFIC = {
-    "source_hash": "091c9914a1fa185a",
+    "source_hash": "0343af25283dc64a",
+    # workload -> (kernel configuration the counters were taken on, bytes per launch)
     "bytes_per_launch": {
-        "c3_bf16_8192_bias_gelu": (802885 * 2.0 + 263557 * 1.0) * 1024,
-        "c4_bf16_batched_512x512x64": (16483 * 2.0 + 262155 * 1.0) * 1024,
-        "c6_fused_nt_8192_bias_gelu_bf16out": (879397 * 2.0 + 131072 * 1.0) * 1024,
-        "c8_fused_batched_512x512x64_bf16out": (16620 * 2.0 + 131072 * 1.0) * 1024,
-        "c10_conv3x3_256_bf16out": (100063 * 2.0 + 50176 * 1.0) * 1024,
+        "c3_bf16_8192_bias_gelu": ("bf16_256x256x32_w8", (802885 * 2.0 + 263557 * 1.0) * 1024),
+        "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", (16483 * 2.0 + 262155 * 1.0) * 1024),
+        "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x32_w8_nt", (879397 * 2.0 + 131072 * 1.0) * 1024),
+        "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", (16620 * 2.0 + 131072 * 1.0) * 1024),
+        "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (100063 * 2.0 + 50176 * 1.0) * 1024),
     },
 }
 
 
-# the sources the GEMM kernels and their dispatch are built from (the probes are not among them)
-KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "ge_host.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h",
-                  "gemm_fused.h", "gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip")
+# the device code of the GEMM kernels (host-side dispatch is covered by the kernel name stored with each entry)
+KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h", "gemm_fused.h")
 
 
 def kernel_source_hash() -> str:
@@ -100,11 +100,13 @@ def measured_ceilings(torch, binding, dA, stream):
                    "fp32 store of 256 MiB, 16 B per lane"}
 
 
-def measured_traffic(workload: str):
+def measured_traffic(workload: str, config_name: str):
+    """HBM-side bytes per launch from the stored counters, or None when the kernel sources or the
+    kernel chosen for the workload are no longer the ones the counters were taken on."""
     if kernel_source_hash() != TRAFFIC["source_hash"]:
         return None
     v = TRAFFIC["bytes_per_launch"].get(workload)
-    return None if v is None else float(v)
+    return None if v is None or v[0] != config_name else float(v[1])
 
 
 def sample_rows(M: int, count: int) -> np.ndarray:
@@ -229,7 +231,7 @@ def bench_conv(args, torch, binding, gen) -> int:
     config_name = binding.last_config()
     achieved = cw.flops / (ms_dev * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload),
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": measured_traffic(args.workload, config_name),
                 "kernel": config_name, "ms_per_launch": round(ms_dev, 4)}
     ceilings = None
     if not args.no_ceilings:
@@ -386,7 +388,7 @@ def main() -> int:
         achieved = job.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
-    roofline["traffic"] = measured_traffic(args.workload)     # HBM-side bytes per launch, or null
+    roofline["traffic"] = measured_traffic(args.workload, config_name)     # HBM-side bytes per launch, or null
     roofline["kernel"] = config_name
     roofline["ms_per_launch"] = round(ms_dev, 4)
     roofline["ms_single_launch"] = {"median": round(singles[len(singles) // 2], 4), "min": round(singles[0], 4)}
