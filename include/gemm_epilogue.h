@@ -210,7 +210,9 @@ ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
  * `args` is a HOST pointer, read before the call returns.  The gathering kernel needs X and
  * Wt 16-byte aligned, Cin a multiple of 32, Cout a multiple of 8, an input smaller than
  * 2 GiB and (for bf16 output) Y 16-byte aligned; any other legal argument list takes a guarded
- * kernel with the same result contract.
+ * kernel with the same result contract.  Shapes with few output tiles and a long K are split
+ * over K into the library-owned workspace (as gemm_epilogue_bf16 does) and summed in slice order:
+ * bitwise repeatable; such calls must be ordered on one stream at a time.
  * Errors: GE_ERR_NULL, GE_ERR_SHAPE (a size < 1, an empty output, index ranges), GE_ERR_ACT,
  * GE_ERR_EPILOGUE, GE_ERR_ALIGN, GE_ERR_LAUNCH.
  */

@@ -24,11 +24,14 @@ int out_size(int in, int k, int stride, int pad, int dil)
 }
 
 template <int BM, int BN, int WM, int WN>
-void launch_conv(const GemmParams &p, bool edge, dim3 grid, hipStream_t st)
+void launch_conv(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
 {
     constexpr int threads = WM * WN * 64;
     const bool h = p.cType == ge::DT_BF16;
-    if (edge) {
+    if (raw) {
+        if (edge) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
+        else      hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
+    } else if (edge) {
         if (h) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
         else   hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
     } else {
@@ -69,7 +72,7 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
                 xElems * 2 < (1ll << 31) - (1 << 20) && K * 2 * 256 + 1024 < (1ll << 31);
     if (a.y_type == GE_DTYPE_BF16 && (((uintptr_t)a.Y) & 15u)) fast = false;
     Plan pl;
-    ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_DIRECT, 0, &pl);
+    ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &pl);
     if (st != GE_OK) return st;
 
     GemmParams p{};
@@ -78,8 +81,9 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
     p.lda = (int)K; p.ldb = (int)K; p.ldc = a.Cout;
     p.strideA = 0; p.strideB = 0; p.strideC = 0;
     p.batch = 1;
-    p.splitK = 1;
+    p.splitK = pl.splitK;
     p.kPerSlice = pl.kPerSlice;
+    p.sliceStride = M * a.Cout;
     p.tilesM = pl.tilesM;
     p.tilesN = pl.tilesN;
     p.groupM = choose_group_m(pl.tilesM, pl.tilesN);
@@ -104,21 +108,40 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
     p.convSh = a.stride_h; p.convSw = a.stride_w; p.convPh = a.pad_h; p.convPw = a.pad_w;
     p.convDh = a.dil_h; p.convDw = a.dil_w;
 
-    const dim3 grid((unsigned)((long long)pl.tilesM * pl.tilesN));
+    // few output tiles and a long K (late layers: small images, many channels): K slices into the
+    // library's workspace, summed in slice order by the second pass, which also runs the chain
+    const bool raw = pl.splitK > 1;
+    void *ws = nullptr;
+    GemmParams pg = p;
+    if (raw) {
+        st = acquire_workspace(partial_bytes((int)M, a.Cout, 1, pl.splitK), nullptr, 0, &ws);
+        if (st != GE_OK) return st;
+        pg.C = (float *)ws;
+    }
+    const dim3 grid((unsigned)((long long)pl.tilesM * pl.tilesN * pl.splitK));
     hipStream_t hs = (hipStream_t)stream;
     switch (pl.tile) {
     case TILE_256:
-        launch_conv<256, 256, 2, 4>(p, pl.edge, grid, hs);
-        g_last_config = "conv_bf16_256x256x32_w8";
+        launch_conv<256, 256, 2, 4>(pg, pl.edge, raw, grid, hs);
+        g_last_config = raw ? "conv_bf16_256x256x32_w8_splitk" : "conv_bf16_256x256x32_w8";
         break;
     case TILE_128:
-        launch_conv<128, 128, 2, 2>(p, pl.edge, grid, hs);
-        g_last_config = "conv_bf16_128x128x32_w4";
+        launch_conv<128, 128, 2, 2>(pg, pl.edge, raw, grid, hs);
+        g_last_config = raw ? "conv_bf16_128x128x32_w4_splitk" : "conv_bf16_128x128x32_w4";
         break;
     default:
-        hipLaunchKernelGGL(ge::conv_bf16_generic_kernel, grid, dim3(256), 0, hs, p);
-        g_last_config = "conv_bf16_generic_64x64x32";
+        if (raw) hipLaunchKernelGGL(ge::conv_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
+        else     hipLaunchKernelGGL(ge::conv_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
+        g_last_config = raw ? "conv_bf16_generic_64x64x32_splitk" : "conv_bf16_generic_64x64x32";
         break;
     }
-    return hipGetLastError() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
+    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    if (raw) {
+        const long long total = M * a.Cout;
+        long long blocks = (total + 255) / 256;
+        if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
+        hipLaunchKernelGGL(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
+        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    }
+    return GE_OK;
 }

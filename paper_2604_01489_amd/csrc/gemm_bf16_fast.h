@@ -125,7 +125,7 @@ gemm_bf16_kernel(const GemmParams p)
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
     static_assert(!(RAW && FUSED) && (FUSED || !OUTBF16), "partial tiles carry no epilogue; bf16 output is the fused one's");
-    static_assert(!CONV || (!TA && TB && FUSED), "convolution: gathered k-contiguous A, filters as N x K");
+    static_assert(!CONV || (!TA && TB && (FUSED || RAW)), "convolution: gathered k-contiguous A, filters as N x K");
     static_assert((BM & (BM - 1)) == 0 && ((T::WTM / 32) & (T::WTM / 32 - 1)) == 0, "k-strided A stage");
 
     // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages

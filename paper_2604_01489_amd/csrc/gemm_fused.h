@@ -2,8 +2,8 @@
 // lists the direct-to-LDS kernel does not take (odd sizes, unaligned pointers, odd leading
 // dimensions), with operands stored either way round, and the second pass of split-K with
 // the run-time epilogue.  Every global access is predicated (Debugging guide, checklist "Edges").
-// (The two kernels that are not templates have internal linkage: this header is included by
-// more than one translation unit.)
+// (The kernel that is not a template has internal linkage: this header is included by more than
+// one translation unit.)
 #pragma once
 #include "ge_device.h"
 
@@ -99,7 +99,9 @@ gemm_bf16_fused_generic_kernel(const GemmParams p)
 // not multiples of 32, unaligned pointers): the same implicit GEMM (rows = output positions,
 // columns = output channels, k = (tap, channel)) with every element of the im2col tile fetched
 // under its own bounds test.  64x64 tile, K step 32, 4 waves; B is the filter bank [Cout][K].
-static __global__ void __launch_bounds__(256)
+// RAW: fp32 partial sums of one K slice for split-K instead of the epilogue.
+template <bool RAW>
+__global__ void __launch_bounds__(256)
 conv_bf16_generic_kernel(const GemmParams p)
 {
     constexpr int BM = 64, BN = 64, BK = 32, LD = BK + 8;
@@ -112,19 +114,21 @@ conv_bf16_generic_kernel(const GemmParams p)
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
     const uint16_t *X = (const uint16_t *)p.A;
     const uint16_t *Wt = (const uint16_t *)p.B;
+    const int kBegin = tc.s * p.kPerSlice;
+    const int kEnd = min(p.K, kBegin + p.kPerSlice);
 
     // the output position of the A row this thread fills (threads walk k fastest: row = e / BK)
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 
-    for (int k0 = 0; k0 < p.K; k0 += BK) {
+    for (int k0 = kBegin; k0 < kEnd; k0 += BK) {
 #pragma unroll
         for (int i = 0; i < BM * BK / 256; ++i) {
             const int e = tid + i * 256, row = e / BK, k = e % BK;
             const int m = m0 + row, kk = k0 + k;
             uint16_t v = 0;
-            if (m < p.M && kk < p.K) {
+            if (m < p.M && kk < kEnd) {
                 const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
                 const int oh = pos / p.convOW, ow = pos % p.convOW;
                 const int tap = kk / p.convCin, c = kk % p.convCin;
@@ -140,7 +144,7 @@ conv_bf16_generic_kernel(const GemmParams p)
             const int e = tid + i * 256, col = e / BK, k = e % BK;
             const int n = n0 + col, kk = k0 + k;
             uint16_t v = 0;
-            if (n < p.N && kk < p.K) v = Wt[(long long)n * p.K + kk];
+            if (n < p.N && kk < kEnd) v = Wt[(long long)n * p.K + kk];
             sB[col * LD + k] = v;
         }
         __syncthreads();
@@ -159,7 +163,9 @@ conv_bf16_generic_kernel(const GemmParams p)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < p.M) fused_store(p, 0, m, n, acc[r]);
+        if (m >= p.M) continue;
+        if (RAW) p.C[(long long)tc.s * p.sliceStride + (long long)m * p.N + n] = acc[r];
+        else fused_store(p, 0, m, n, acc[r]);
     }
 }
 

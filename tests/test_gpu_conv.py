@@ -83,3 +83,25 @@ def test_conv_guarded_kernel(oracle):
     run_conv_case(oracle, (1, 9, 9, 40, 24, 3, 3), pad=(1, 1), residual="f32", out="bf16", seed=31,
                   expect="conv_bf16_generic_64x64x32")                                    # Cin not a multiple of 32
     run_conv_case(oracle, (1, 8, 8, 32, 12, 1, 1), seed=32, expect="conv_bf16_generic_64x64x32")   # Cout not a multiple of 8
+
+
+def test_conv_split_k_for_few_tiles_and_long_k(oracle):
+    """Late-layer shapes: a handful of output tiles and K = KH*KW*Cin in the thousands -> K slices,
+    summed in slice order by the second pass, which also runs the consumer chain."""
+    cfg = run_conv_case(oracle, (1, 8, 8, 512, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=40)
+    assert cfg == "conv_bf16_128x128x32_w4_splitk"
+    cfg = run_conv_case(oracle, (4, 9, 9, 256, 512, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=41)
+    assert cfg == "conv_bf16_256x256x32_w8_splitk"
+    cfg = run_conv_case(oracle, (1, 7, 7, 200, 100, 3, 3), pad=(1, 1), stride=(2, 2), act="relu", clamp=(0.0, 1.0), seed=42)
+    assert cfg == "conv_bf16_generic_64x64x32_splitk"
+    # repeatable bit for bit
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    X = torch.from_numpy(gen.to_bf16_bits(gen.normal(43, 0, 8 * 8 * 512, 1.0).reshape(1, 8, 8, 512)).view(np.int16)).cuda()
+    Wt = torch.from_numpy(gen.to_bf16_bits(gen.normal(43, 1, 256 * 9 * 512, 0.02).reshape(256, 3, 3, 512)).view(np.int16)).cuda()
+    Y1 = torch.empty(1, 8, 8, 256, device="cuda")
+    Y2 = torch.empty_like(Y1)
+    binding.conv2d_epilogue_bf16(X, Wt, Y1, pad=(1, 1))
+    binding.conv2d_epilogue_bf16(X, Wt, Y2, pad=(1, 1))
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
