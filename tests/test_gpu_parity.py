@@ -155,3 +155,14 @@ def test_integer_inputs_are_exact(oracle):
         binding.gemm_epilogue_f32(M, N, K, to_device(Ai), K, to_device(Bi), N, None, 1.0, "none", C32, N)
         torch.cuda.synchronize()
         assert np.array_equal(C32.cpu().numpy().astype(np.float64), oracle.gemm_epilogue(Ai, Bi))
+
+
+def test_planning_rule_is_close_to_the_timed_search():
+    """The fixed split-K rule against a search by timing (paper: structure first, counters later): for a
+    few shapes the library's choice is within 25 % of the fastest slice count found."""
+    from paper_2604_01489_amd import tune
+    for M, N, K in [(256, 256, 8192), (1024, 2048, 4096), (2048, 2048, 2048)]:
+        best, auto, table = tune.sweep_split_k(M, N, K, reps=20)
+        times = dict(table)
+        print(f"{M}x{N}x{K}: auto {auto}, fastest {best}, table {[(s, round(t, 1)) for s, t in table]}", flush=True)
+        assert times[auto] <= 1.25 * times[best], (M, N, K, auto, best, table)
