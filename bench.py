@@ -100,6 +100,29 @@ def measured_ceilings(torch, binding, dA, stream):
                    "fp32 store of 256 MiB, 16 B per lane"}
 
 
+def blas_yardstick(torch, dA, dB, transA: bool, transB: bool, flops: float, warmup: int, steps: int):
+    """The same product through the BLAS that ships with PyTorch-ROCm, on the operands as they are stored
+    (a transposed operand is passed as a transposed view, not copied), bf16 output, no bias or activation:
+    less work than the timed operator does, so a yardstick for the box, not a like-for-like baseline."""
+    a = dA.view(torch.bfloat16)
+    b = dB.view(torch.bfloat16)
+    a = a.transpose(-1, -2) if transA else a
+    b = b.transpose(-1, -2) if transB else b
+    fn = torch.bmm if a.shape[0] > 1 else (lambda x, y: torch.matmul(x[0], y[0]))
+    for _ in range(warmup):
+        fn(a, b)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        fn(a, b)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return {"call": "torch.bmm" if a.shape[0] > 1 else "torch.matmul", "out_dtype": "bf16", "epilogue": None,
+            "ms_per_launch": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 2)}
+
+
 def measured_traffic(workload: str, config_name: str):
     """HBM-side bytes per launch from the stored counters, or None when the kernel sources or the
     kernel chosen for the workload are no longer the ones the counters were taken on."""
@@ -278,6 +301,9 @@ def main() -> int:
                     help="cycle through R copies of A, B and C (R x the footprint) so that no launch finds "
                          "its inputs in the 256 MB memory-side cache")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the measured-ceiling probes")
+    ap.add_argument("--blas", action="store_true",
+                    help="also time the BLAS that ships with PyTorch-ROCm (torch.matmul / torch.bmm, bf16 output, no "
+                         "epilogue) on the same operands in the same run: a yardstick for what this box sustains")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times "
                          "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -398,6 +424,9 @@ def main() -> int:
         top = ceilings["mfma_bf16_tflops"] if bound == "mfma" else ceilings["store_gbs"]
         roofline["frac_of_measured"] = round(achieved / top, 4)
 
+    blas = blas_yardstick(torch, dA, dB, bool(fused and fw.transA), bool(fused and fw.transB), job.flops,
+                          args.warmup, args.steps) if args.blas else None
+
     # ---- CPU oracle on a bounded sample of the same workload, and parity on that sample
     cpu_baseline = None
     parity = None
@@ -458,6 +487,7 @@ def main() -> int:
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": roofline,
         "ceilings": ceilings,
+        "blas_yardstick": blas,
         "cpu_baseline": cpu_baseline,
         "parity": parity,
     }
