@@ -156,73 +156,165 @@ __device__ inline float fused_value(const GemmParams &p, float acc, float rowSca
     return v;
 }
 
-// One row block (16 rows x TN blocks of 16 columns) of a wave tile through the chain, for
-// accumulators of the swapped product: the lane holds row m and, per block j, the 4 consecutive
-// columns from colLane + 16 j.  Residual type and activation are selected by uniform branches
-// around the loops, not per element: on the store-bound shapes the vector ALU work per output is
-// what the epilogue costs.
-template <int TN, bool EDGE>
-__device__ inline void chain_row_block(const GemmParams &p, int b, f32x4_t (&v)[TN], const float (&bv)[TN][4],
-                                       int m, int colLane)
-{
-    const bool rowOk = !EDGE || m < p.M;
-    const float scale = p.alpha * ((p.rowScale != nullptr && rowOk) ? p.rowScale[m] : 1.0f);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j][r]);
-
-    if (p.R != nullptr) {
-        const long long rowAt = (long long)b * p.strideR + (long long)m * p.ldr;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = colLane + j * 16;
-            if (EDGE && (!rowOk || n >= p.N)) continue;
-            float res[4];
-            if (p.rType == DT_BF16) {
-                if (p.rVec) {
-                    const u32x2_t t = *(const u32x2_t *)((const unsigned short *)p.R + rowAt + n);
-                    res[0] = __uint_as_float(t[0] << 16); res[1] = __uint_as_float(t[0] & 0xFFFF0000u);
-                    res[2] = __uint_as_float(t[1] << 16); res[3] = __uint_as_float(t[1] & 0xFFFF0000u);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) res[r] = load_as_f32(p.R, rowAt + n + r, DT_BF16);
-                }
-            } else if (p.rVec) {
-                const f32x4_t t = *(const f32x4_t *)((const float *)p.R + rowAt + n);
-                res[0] = t[0]; res[1] = t[1]; res[2] = t[2]; res[3] = t[3];
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) res[r] = ((const float *)p.R)[rowAt + n + r];
-            }
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(p.beta, res[r], v[j][r]);
-        }
-    }
-    if (p.act == ACT_RELU) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(__builtin_fmaxf(v[j][r], 0.0f), p.clampLo, p.clampHi);
-    } else if (p.act == ACT_GELU_TANH) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
-    } else {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], p.clampLo, p.clampHi);
-    }
-}
-
 __device__ inline unsigned pack_bf16_pair(float lo, float hi)
 {
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
     typedef __attribute__((ext_vector_type(2))) float f32x2_t;
     const f32x2_t f = {lo, hi};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2_t));
+}
+
+// How a fused epilogue reads its residual.  The mode is block-uniform; the epilogues branch on it
+// once, around the whole walk over the row blocks, so that inside a walk the fetches of row block
+// i + 1 (row scale, residual) can be issued ahead of the arithmetic of row block i: with a fetch
+// right before each use, a tile pays one round trip to L2 or HBM per row block, which a short-K
+// (store-bound) shape notices and a residual doubles.
+enum { RES_NONE = 0, RES_BF16 = 1, RES_F32 = 2, RES_BF16_SCALAR = 3, RES_F32_SCALAR = 4 };
+
+__device__ inline float bf16_bits_as_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
+
+// Activation and clamp of one row block, the activation by a uniform branch around the loops.
+// relu needs no instruction of its own: clamp(max(v, 0), lo, hi) with lo <= hi is the clamp of v to
+// [max(lo, 0), hi], or the constant hi where that interval is empty (hi < 0), so the bounds are
+// adjusted once, on the scalar unit, and each value costs one median-of-three either way (on a
+// store-bound shape the epilogue's vector instructions are time nothing else overlaps).
+template <int TN>
+__device__ __forceinline__ void act_clamp_row_block(const GemmParams &p, f32x4_t (&v)[TN])
+{
+    if (p.act == ACT_GELU_TANH) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
+    } else {
+        float lo = p.clampLo, hi = p.clampHi;
+        if (p.act == ACT_RELU) {
+            lo = lo > 0.0f ? lo : 0.0f;
+            lo = hi < lo ? hi : lo;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], lo, hi);
+    }
+}
+
+// ---- bf16 output: accumulators of the swapped product (lane: one row, 4 consecutive columns per block)
+
+// What row block (row m of this lane) needs from memory: its row scale and, per column block, the
+// lane's 4 residual elements as raw words (RES_BF16: two words of packed pairs; RES_F32: four).
+template <int RES, int TN, bool EDGE>
+__device__ __forceinline__ void fetch_row_block_t(const GemmParams &p, int b, int m, int colLane, float &rs, unsigned (&raw)[TN][4])
+{
+    const bool rowOk = !EDGE || m < p.M;
+    rs = (p.rowScale != nullptr && rowOk) ? p.rowScale[m] : 1.0f;
+    if constexpr (RES == RES_BF16 || RES == RES_F32) {
+        const long long rowAt = (long long)b * p.strideR + (long long)m * p.ldr;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = colLane + j * 16;
+            const bool inside = !EDGE || (rowOk && n < p.N);
+            if constexpr (RES == RES_BF16) {
+                u32x2_t t = {0u, 0u};
+                if (inside) t = *(const u32x2_t *)((const unsigned short *)p.R + rowAt + n);
+                raw[j][0] = t[0];
+                raw[j][1] = t[1];
+            } else {
+                i32x4_t t = {0, 0, 0, 0};
+                if (inside) t = *(const i32x4_t *)((const float *)p.R + rowAt + n);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw[j][r] = (unsigned)t[r];
+            }
+        }
+    }
+}
+
+template <int RES, int TN, bool EDGE>
+__device__ __forceinline__ void apply_row_block_t(const GemmParams &p, int b, f32x4_t (&v)[TN], const float (&bv)[TN][4],
+                                         float rs, const unsigned (&raw)[TN][4], int m, int colLane)
+{
+    const float scale = p.alpha * rs;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j][r]);
+    if constexpr (RES == RES_BF16) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            v[j][0] = __builtin_fmaf(p.beta, __uint_as_float(raw[j][0] << 16), v[j][0]);
+            v[j][1] = __builtin_fmaf(p.beta, __uint_as_float(raw[j][0] & 0xFFFF0000u), v[j][1]);
+            v[j][2] = __builtin_fmaf(p.beta, __uint_as_float(raw[j][1] << 16), v[j][2]);
+            v[j][3] = __builtin_fmaf(p.beta, __uint_as_float(raw[j][1] & 0xFFFF0000u), v[j][3]);
+        }
+    } else if constexpr (RES == RES_F32) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_fmaf(p.beta, __uint_as_float(raw[j][r]), v[j][r]);
+    } else if constexpr (RES == RES_BF16_SCALAR || RES == RES_F32_SCALAR) {
+        // a residual whose rows cannot be read in 8- or 16-byte pieces: element by element, at the use
+        const long long rowAt = (long long)b * p.strideR + (long long)m * p.ldr;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = colLane + j * 16;
+            if (EDGE && (m >= p.M || n >= p.N)) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float res = RES == RES_BF16_SCALAR ? bf16_bits_as_f32(((const unsigned short *)p.R)[rowAt + n + r])
+                                                         : ((const float *)p.R)[rowAt + n + r];
+                v[j][r] = __builtin_fmaf(p.beta, res, v[j][r]);
+            }
+        }
+    }
+    act_clamp_row_block<TN>(p, v);
+}
+
+// The lane's bias values for the swapped product: 4 consecutive columns from colLane + 16 j per
+// column block (colLane is a multiple of 4), in one piece where the pointer allows.
+template <int TN, bool EDGE>
+__device__ __forceinline__ void fetch_bias_t(const GemmParams &p, int colLane, float (&bv)[TN][4])
+{
+    const bool biasVec = (((unsigned long long)p.bias) & 15ull) == 0ull;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = colLane + j * 16;
+        const bool ok = p.bias != nullptr && (!EDGE || n < p.N);
+        if (biasVec) {
+            f32x4_t t = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (ok) t = *(const f32x4_t *)(p.bias + n);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bv[j][r] = t[r];
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bv[j][r] = ok ? p.bias[n + r] : 0.0f;
+        }
+    }
+}
+
+// The chain over all row blocks of a wave tile and the parking of the results, as bf16, in the
+// row-major LDS image of the block tile.
+template <int RES, int BN, int TM, int TN, bool EDGE>
+__device__ __forceinline__ void chain_and_park_t(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], const float (&bv)[TN][4],
+                                        GE_LDS char *lds, int m0, int colLane, int tileRow, int tileCol)
+{
+    constexpr int PITCH = BN * 2, CHUNKS = PITCH / 16;
+    float rs[2];
+    unsigned raw[2][TN][4];
+    fetch_row_block_t<RES, TN, EDGE>(p, b, m0 + tileRow, colLane, rs[0], raw[0]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row = tileRow + i * 16;
+        if (i + 1 < TM) fetch_row_block_t<RES, TN, EDGE>(p, b, m0 + row + 16, colLane, rs[(i + 1) & 1], raw[(i + 1) & 1]);
+        apply_row_block_t<RES, TN, EDGE>(p, b, acc[i], bv, rs[i & 1], raw[i & 1], m0 + row, colLane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int cb = (tileCol + j * 16) * 2;
+            u32x2_t v;
+            v[0] = pack_bf16_pair(acc[i][j][0], acc[i][j][1]);
+            v[1] = pack_bf16_pair(acc[i][j][2], acc[i][j][3]);
+            *(GE_LDS u32x2_t *)(lds + row * PITCH + (((cb >> 4) ^ (row & (CHUNKS - 1))) << 4) + (cb & 15)) = v;
+        }
+    }
 }
 
 // Epilogue of the widened operator with bf16 output, for a block tile whose accumulators were
@@ -238,34 +330,25 @@ __device__ inline unsigned pack_bf16_pair(float lo, float hi)
 // (tileRow, tileCol): row of this lane and first of its 4 columns in block (0, 0) of the wave
 // tile, relative to the block tile.
 template <int BM, int BN, int NW, int LDS_BYTES, int TM, int TN, bool EDGE>
-__device__ inline void fused_epilogue_bf16_through_lds(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], GE_LDS char *lds,
+__device__ __forceinline__ void fused_epilogue_bf16_through_lds(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], GE_LDS char *lds,
                                                        int m0, int n0, int tileRow, int tileCol, int w, int lane)
 {
     constexpr int PITCH = BN * 2, CHUNKS = PITCH / 16, ROWS_PER_INSTR = 1024 / PITCH;
     static_assert(BM * PITCH <= LDS_BYTES, "bf16 image of the tile fits the stages");
     const int colLane = n0 + tileCol;
     float bv[TN][4];
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = colLane + j * 16;
-        const bool ok = p.bias != nullptr && (!EDGE || n < p.N);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) bv[j][r] = ok ? p.bias[n + r] : 0.0f;
-    }
+    fetch_bias_t<TN, EDGE>(p, colLane, bv);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // every wave is done with the stages
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int row = tileRow + i * 16;
-        chain_row_block<TN, EDGE>(p, b, acc[i], bv, m0 + row, colLane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int cb = (tileCol + j * 16) * 2;
-            u32x2_t v;
-            v[0] = pack_bf16_pair(acc[i][j][0], acc[i][j][1]);
-            v[1] = pack_bf16_pair(acc[i][j][2], acc[i][j][3]);
-            *(GE_LDS u32x2_t *)(lds + row * PITCH + (((cb >> 4) ^ (row & (CHUNKS - 1))) << 4) + (cb & 15)) = v;
-        }
-    }
+    if (p.R == nullptr)
+        chain_and_park_t<RES_NONE, BN, TM, TN, EDGE>(p, b, acc, bv, lds, m0, colLane, tileRow, tileCol);
+    else if (p.rVec && p.rType == DT_BF16)
+        chain_and_park_t<RES_BF16, BN, TM, TN, EDGE>(p, b, acc, bv, lds, m0, colLane, tileRow, tileCol);
+    else if (p.rVec)
+        chain_and_park_t<RES_F32, BN, TM, TN, EDGE>(p, b, acc, bv, lds, m0, colLane, tileRow, tileCol);
+    else if (p.rType == DT_BF16)
+        chain_and_park_t<RES_BF16_SCALAR, BN, TM, TN, EDGE>(p, b, acc, bv, lds, m0, colLane, tileRow, tileCol);
+    else
+        chain_and_park_t<RES_F32_SCALAR, BN, TM, TN, EDGE>(p, b, acc, bv, lds, m0, colLane, tileRow, tileCol);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     unsigned short *cBase = (unsigned short *)p.C + (long long)b * p.strideC;
     const int rowInGroup = lane / CHUNKS, chunk = lane % CHUNKS;
@@ -278,63 +361,71 @@ __device__ inline void fused_epilogue_bf16_through_lds(const GemmParams &p, int 
     }
 }
 
-// Epilogue of the widened operator with fp32 output, straight from the accumulators of the plain
-// product (register r of lane l: row 4*(l/16) + r, column l%16 of its block).  One row block at a
-// time: the chain in registers (residual type and activation by uniform branches around the
-// loops), then one dword per lane and row, 64 contiguous bytes per 16 lanes, as in the plain kernel.
-template <int TM, int TN, bool EDGE>
-__device__ inline void fused_epilogue_f32_direct(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN],
-                                                 int rowLane, int colLane)
+// ---- fp32 output: accumulators of the plain product (register r of lane l: row 4*(l/16) + r,
+// column l%16 of its block)
+
+// Row scales of the lane's 4 rows and, per row and column block, its residual element as a raw fp32 word.
+template <int RES, int TN, bool EDGE>
+__device__ __forceinline__ void fetch_row_block_n(const GemmParams &p, int b, int mFirst, int colLane, float (&rs)[4],
+                                         unsigned (&raw)[4][TN])
 {
-    float bv[TN];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = colLane + j * 16;
-        bv[j] = (p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
+    for (int r = 0; r < 4; ++r) {
+        const int m = mFirst + r;
+        rs[r] = (p.rowScale != nullptr && (!EDGE || m < p.M)) ? p.rowScale[m] : 1.0f;
     }
-    float *cBase = p.C + (long long)b * p.strideC;
-    const long long rBase = (long long)b * p.strideR;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        f32x4_t (&v)[TN] = acc[i];
+    if constexpr (RES != RES_NONE) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int m = rowLane + i * 16 + r;
-            const float scale = p.alpha * ((p.rowScale != nullptr && (!EDGE || m < p.M)) ? p.rowScale[m] : 1.0f);
+            const int m = mFirst + r;
+            const long long rowAt = (long long)b * p.strideR + (long long)m * p.ldr + colLane;
 #pragma unroll
-            for (int j = 0; j < TN; ++j) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j]);
-        }
-        if (p.R != nullptr) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = rowLane + i * 16 + r;
-                const long long rowAt = rBase + (long long)m * p.ldr + colLane;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if (EDGE && (m >= p.M || colLane + j * 16 >= p.N)) continue;
-                    float res;
-                    if (p.rType == DT_BF16) res = load_as_f32(p.R, rowAt + j * 16, DT_BF16);
-                    else res = ((const float *)p.R)[rowAt + j * 16];
-                    v[j][r] = __builtin_fmaf(p.beta, res, v[j][r]);
+            for (int j = 0; j < TN; ++j) {
+                const bool inside = !EDGE || (m < p.M && colLane + j * 16 < p.N);
+                unsigned t = 0u;
+                if constexpr (RES == RES_BF16) {
+                    if (inside) t = (unsigned)((const unsigned short *)p.R)[rowAt + j * 16];
+                    raw[r][j] = t << 16;
+                } else {
+                    if (inside) t = ((const unsigned *)p.R)[rowAt + j * 16];
+                    raw[r][j] = t;
                 }
             }
         }
-        if (p.act == ACT_RELU) {
+    }
+}
+
+// One row block at a time: chain, then stores, with the fetches of row block i + 1 issued ahead of
+// the arithmetic of block i.  (Loads and stores share one completion counter on this hardware and
+// complete out of order with respect to each other, so a fetch issued among stores is waited for
+// together with them; a pass of fetches over the whole tile ahead of a pass of stores avoids that
+// but made the register allocator spill the accumulators, and fetching all row scales up front
+// measured slower.)
+template <int RES, int TM, int TN, bool EDGE>
+__device__ __forceinline__ void chain_and_store_n(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], const float (&bv)[TN],
+                                         int rowLane, int colLane)
+{
+    float *cBase = p.C + (long long)b * p.strideC;
+    float rs[2][4];
+    unsigned raw[2][4][TN];
+    fetch_row_block_n<RES, TN, EDGE>(p, b, rowLane, colLane, rs[0], raw[0]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+    for (int i = 0; i < TM; ++i) {
+        f32x4_t (&v)[TN] = acc[i];
+        if (i + 1 < TM) fetch_row_block_n<RES, TN, EDGE>(p, b, rowLane + (i + 1) * 16, colLane, rs[(i + 1) & 1], raw[(i + 1) & 1]);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(__builtin_fmaxf(v[j][r], 0.0f), p.clampLo, p.clampHi);
-        } else if (p.act == ACT_GELU_TANH) {
+        for (int r = 0; r < 4; ++r) {
+            const float scale = p.alpha * rs[i & 1][r];
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], p.clampLo, p.clampHi);
+            for (int j = 0; j < TN; ++j) v[j][r] = __builtin_fmaf(v[j][r], scale, bv[j]);
         }
+        if constexpr (RES != RES_NONE) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) v[j][r] = __builtin_fmaf(p.beta, __uint_as_float(raw[i & 1][r][j]), v[j][r]);
+        }
+        act_clamp_row_block<TN>(p, v);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int m = rowLane + i * 16 + r;
@@ -344,6 +435,24 @@ __device__ inline void fused_epilogue_f32_direct(const GemmParams &p, int b, f32
                 if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v[j][r];
         }
     }
+}
+
+// Epilogue of the widened operator with fp32 output, straight from the accumulators: the chain in
+// registers, then one dword per lane and row, 64 contiguous bytes per 16 lanes, as in the plain
+// kernel.
+template <int TM, int TN, bool EDGE>
+__device__ __forceinline__ void fused_epilogue_f32_direct(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN],
+                                                 int rowLane, int colLane)
+{
+    float bv[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = colLane + j * 16;
+        bv[j] = (p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
+    }
+    if (p.R == nullptr) chain_and_store_n<RES_NONE, TM, TN, EDGE>(p, b, acc, bv, rowLane, colLane);
+    else if (p.rType == DT_BF16) chain_and_store_n<RES_BF16, TM, TN, EDGE>(p, b, acc, bv, rowLane, colLane);
+    else chain_and_store_n<RES_F32, TM, TN, EDGE>(p, b, acc, bv, rowLane, colLane);
 }
 
 }  // namespace ge

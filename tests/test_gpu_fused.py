@@ -53,6 +53,21 @@ def test_epilogue_chain(oracle, out, residual):
         assert got.max() <= 1.25 + 1e-6
 
 
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("clamp", [(-0.5, 0.75), (0.25, 0.75), (-0.75, -0.25), (0.0, 0.0), None])
+def test_relu_then_clamp(oracle, out, clamp):
+    """relu followed by a clamp whose interval lies across, above or below zero (the kernels fold the
+    relu into the bounds: below zero the result is the constant upper bound)."""
+    got, ref, _, cfg = run_fused_case(oracle, 264, 264, 72, act="relu", clamp=clamp, residual="bf16", out=out,
+                                      seed=31)
+    assert "generic" not in cfg
+    if clamp == (-0.75, -0.25):
+        assert (got == np.float32(-0.25)).all()
+    if clamp == (0.25, 0.75):
+        assert got.min() == np.float32(0.25) and got.max() == np.float32(0.75)
+    run_fused_case(oracle, 45, 67, 33, act="relu", clamp=clamp, out=out, seed=32)       # guarded kernel
+
+
 def test_bf16_output_all_paths(oracle):
     run_fused_case(oracle, 512, 512, 128, out="bf16", act="relu", seed=21)                       # 256 tile, full
     run_fused_case(oracle, 264, 520, 72, out="bf16", act="none", pad=(0, 0, 0, 6), seed=22)      # 256 tile, ragged, ldc even
