@@ -70,4 +70,22 @@ GE_HD constexpr int b_frag_offset(int colBase, int lane, int r)
     return lds_b_offset<BN>(k, n >> 3) + (n & 7) * 2;
 }
 
+// ---- k-contiguous stage of 64 k (rows of 128 bytes, eight 16-byte chunks) -----------------------
+// For an operand whose memory rows run along k a stage that spans 64 k lets eight neighbouring
+// lanes of a direct-to-LDS load fetch one whole 128-byte line (two requests of 64 bytes to the
+// same line, K steps apart, otherwise).  Chunk c of row r sits at r*128 + (c ^ r[3:1])*16: the 16
+// rows a fragment read touches (same chunk) fall in 16 different 16-byte bank groups.
+GE_HD constexpr int lds_a64_offset(int r, int c) { return r * 128 + ((c ^ ((r >> 1) & 7)) * 16); }
+
+// row and chunk fetched by lane `lane` of the load that fills 1 KB slab `wl` (8 rows) of such a stage
+GE_HD constexpr int a64_slot_row(int wl, int lane) { return wl * 8 + (lane >> 3); }
+GE_HD constexpr int a64_slot_chunk(int wl, int lane) { return (lane & 7) ^ ((a64_slot_row(wl, lane) >> 1) & 7); }
+
+// Fragment of the 16x16x32 MFMA for the k half h (k = 32 h + 8*(l/16) + e): lane l reads row
+// rowBase + l%16, chunk 4 h + l/16.  rowBase is a multiple of 16.
+GE_HD constexpr int a64_frag_offset(int rowBase, int lane, int h)
+{
+    return lds_a64_offset(rowBase + (lane & 15), 4 * h + (lane >> 4));
+}
+
 }  // namespace ge

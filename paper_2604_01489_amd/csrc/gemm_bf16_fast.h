@@ -116,16 +116,26 @@ struct Bf16Tile {
 // position base + tap offset, or zeros where the tap falls into the padding (the out-of-range
 // offset of the buffer load).  B is the filter bank stored [Cout][KH*KW*Cin] (TB), C the
 // channels-last output.
+// K64: the loads move 64 k at a time into a ring of two stages (same LDS as four of 32).  A
+// k-contiguous operand is then staged in rows of 128 bytes, so that eight neighbouring lanes of a
+// load fetch one whole line of the operand instead of half of it now and the other half a step
+// later; a k-strided operand keeps its layout (a 64-k stage is two of its 32-k stages back to back).
+// The multiply still advances 32 k per phase.  One tile of 64 is in flight while one is consumed:
+// less slack than the three-of-four ring, which the full lines more than repay when both operands
+// are k-contiguous (measured: 8192^3 with both operands k-contiguous 0.85 -> 0.81 ms; with one
+// or none 0.75 -> 0.81 ms; the 3x3 convolution over 256 channels 0.139 -> 0.147 ms, so it is used
+// for the first only).  The K range of a block must be a multiple of 64 unless EDGE.
 template <int BM, int BN, int WM, int WN, bool EDGE, bool RAW, int ACT, bool TA = false, bool TB = false,
-          bool FUSED = false, bool OUTBF16 = false, bool CONV = false>
+          bool FUSED = false, bool OUTBF16 = false, bool CONV = false, bool K64 = false>
 __global__ void __launch_bounds__(WM * WN * 64)
 gemm_bf16_kernel(const GemmParams p)
 {
     using T = Bf16Tile<BM, BN, WM, WN>;
     constexpr int BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN, LOADS = T::LOADS;
     constexpr bool PINGPONG = T::PINGPONG;
+    constexpr bool A64 = K64 && !TA, B64 = K64 && TB;     // operands staged in 128-byte rows
     static_assert(!(RAW && FUSED) && (FUSED || !OUTBF16), "partial tiles carry no epilogue; bf16 output is the fused one's");
-    static_assert(!CONV || (!TA && TB && (FUSED || RAW)), "convolution: gathered k-contiguous A, filters as N x K");
+    static_assert(!CONV || (!TA && TB && (FUSED || RAW) && !K64), "convolution: gathered k-contiguous A, filters as N x K, 32 k per step");
     static_assert((BM & (BM - 1)) == 0 && ((T::WTM / 32) & (T::WTM / 32 - 1)) == 0, "k-strided A stage");
 
     // One LDS object with a fixed layout: A stages 0..3, then B stages 0..3.  Every fragment read is then "lane base + immediate" (the A stages
@@ -153,15 +163,17 @@ gemm_bf16_kernel(const GemmParams p)
     // ---- per-lane global offsets of the 16-byte chunks this lane fetches (inverse of
     // the LDS layout: slot -> (row, chunk)); kA / kB hold what the K-edge mask compares:
     // the chunk along k (k-contiguous stage) or the k row (k-strided stage) ---------------
-    unsigned voffA[T::A_LOADS], voffB[T::B_LOADS];
-    int kA[T::A_LOADS], kB[T::B_LOADS];
+    constexpr int NLA = A64 ? 2 * T::A_LOADS : T::A_LOADS, NLB = B64 ? 2 * T::B_LOADS : T::B_LOADS;
+    unsigned voffA[NLA], voffB[NLB];
+    int kA[NLA], kB[NLB];
     // convolution: input row and column of filter tap (0, 0) for the lane's output position
     // (far out of range for rows past M, so that every tap test fails)
-    int ih0[CONV ? T::A_LOADS : 1], iw0[CONV ? T::A_LOADS : 1];
+    int ih0[CONV ? NLA : 1], iw0[CONV ? NLA : 1];
 #pragma unroll
-    for (int j = 0; j < T::A_LOADS; ++j) {
+    for (int j = 0; j < NLA; ++j) {
         if (CONV) {
-            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);
+            const int row = A64 ? a64_slot_row(j * NW + w, lane) : a_slot_row(j * NW + w, lane);
+            const int c = A64 ? a64_slot_chunk(j * NW + w, lane) : a_slot_chunk(lane);
             const int m = m0 + row;
             const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
             const int oh = pos / p.convOW, ow = pos % p.convOW;
@@ -174,7 +186,9 @@ gemm_bf16_kernel(const GemmParams p)
             // [0, 2^31) (the host checks that the input is smaller than that)
             voffA[j] = ((unsigned)((img * p.convH + ihTap0) * p.convW + iw0[j]) * (unsigned)p.convCin + (unsigned)(c * 8)) * 2u;
         } else if (!TA) {
-            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);   // 1 KB slab = 16 rows
+            // 1 KB slab = 16 rows of 64 bytes, or 8 rows of 128
+            const int row = A64 ? a64_slot_row(j * NW + w, lane) : a_slot_row(j * NW + w, lane);
+            const int c = A64 ? a64_slot_chunk(j * NW + w, lane) : a_slot_chunk(lane);
             kA[j] = c * 8;
             voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
             if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
@@ -186,14 +200,15 @@ gemm_bf16_kernel(const GemmParams p)
         }
     }
 #pragma unroll
-    for (int j = 0; j < T::B_LOADS; ++j) {
+    for (int j = 0; j < NLB; ++j) {
         if (!TB) {
             const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
             kB[j] = k;
             voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
             if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
         } else {
-            const int row = a_slot_row(j * NW + w, lane), c = a_slot_chunk(lane);
+            const int row = B64 ? a64_slot_row(j * NW + w, lane) : a_slot_row(j * NW + w, lane);
+            const int c = B64 ? a64_slot_chunk(j * NW + w, lane) : a_slot_chunk(lane);
             kB[j] = c * 8;
             voffB[j] = (unsigned)row * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
             if (EDGE && n0 + row >= p.N) voffB[j] = OOB_OFFSET;
@@ -252,6 +267,65 @@ gemm_bf16_kernel(const GemmParams p)
         }
     };
 
+    // K64: tile t64 (64 k from kBegin + 64 t64) into stage `stage` of two.  A k-strided operand
+    // goes in as its two 32-k halves, each through a resource of its own.
+    const int nk64 = (kLen + 63) / 64;
+    auto issue64 = [&](int t64, int stage) {
+        GE_LDS char *dA = (GE_LDS char *)smem + stage * 2 * T::A_BYTES;
+        GE_LDS char *dB = (GE_LDS char *)smem + 4 * T::A_BYTES + stage * 2 * T::B_BYTES;
+        const int kLeft = kLen - t64 * 64;           // valid k in this tile (EDGE only)
+        if constexpr (A64) {
+            const long long stepA = (long long)t64 * 128;
+            const unsigned leftA = EDGE ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
+            const rsrc_words_t rA = make_rsrc(gA + stepA, t64 < nk64 ? leftA : 0u);
+#pragma unroll
+            for (int j = 0; j < NLA; ++j) {
+                unsigned v = voffA[j];
+                if (EDGE && kA[j] >= kLeft) v = OOB_OFFSET;
+                lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const long long stepA = (long long)(t64 * 64 + h * 32) * p.lda * 2;
+                const bool live = t64 < nk64 && (h == 0 || !EDGE || kLeft > 32);
+                const unsigned leftA = (EDGE && live) ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
+                const rsrc_words_t rA = make_rsrc(gA + stepA, live ? leftA : 0u);
+#pragma unroll
+                for (int j = 0; j < NLA; ++j) {
+                    unsigned v = voffA[j];
+                    if (EDGE && kA[j] + 32 * h >= kLeft) v = OOB_OFFSET;
+                    lds_dma16(rA, (unsigned)(size_t)(dA + h * T::A_BYTES + (j * NW + w) * 1024), v);
+                }
+            }
+        }
+        if constexpr (B64) {
+            const long long stepB = (long long)t64 * 128;
+            const unsigned leftB = EDGE ? records_left(p.bytesB, offB + stepB) : RSRC_RECORDS;
+            const rsrc_words_t rB = make_rsrc(gB + stepB, t64 < nk64 ? leftB : 0u);
+#pragma unroll
+            for (int j = 0; j < NLB; ++j) {
+                unsigned v = voffB[j];
+                if (EDGE && kB[j] >= kLeft) v = OOB_OFFSET;
+                lds_dma16(rB, (unsigned)(size_t)(dB + (j * NW + w) * 1024), v);
+            }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const long long stepB = (long long)(t64 * 64 + h * 32) * p.ldb * 2;
+                const bool live = t64 < nk64 && (h == 0 || !EDGE || kLeft > 32);
+                const unsigned leftB = (EDGE && live) ? records_left(p.bytesB, offB + stepB) : RSRC_RECORDS;
+                const rsrc_words_t rB = make_rsrc(gB + stepB, live ? leftB : 0u);
+#pragma unroll
+                for (int j = 0; j < NLB; ++j) {
+                    unsigned v = voffB[j];
+                    if (EDGE && kB[j] + 32 * h >= kLeft) v = OOB_OFFSET;
+                    lds_dma16(rB, (unsigned)(size_t)(dB + h * T::B_BYTES + (j * NW + w) * 1024), v);
+                }
+            }
+        }
+    };
+
     // ---- per-lane LDS read addresses ---------------------------------------------
     // k-contiguous stage, fragment i: rows base + 16 i + lane%16, k chunk lane/16
     // (k = 8*(lane/16) + e): one ds_read_b128, stepping i adds 1 KB.
@@ -260,9 +334,11 @@ gemm_bf16_kernel(const GemmParams p)
     // the 4 columns from 4*(i%4), and receives column i of the 4x16 block (k = 8g + 4r + e).
     // Stepping j moves 16 columns: an XOR with 32 j on the hashed half (bit 5) and segment
     // (bits 6..8) fields; stepping r adds 4 k rows.
+    // 128-byte-row stage (K64): the k half is carried by the lane part of the address (an XOR),
+    // so there is one lane base per half; stepping the row block adds 2 KB.
     const unsigned aBase = TA ? (unsigned)b_frag_offset<BM>(wm * T::WTM, lane, 0)
-                              : (unsigned)a_frag_offset(wm * T::WTM, lane);
-    const unsigned bBase = TB ? (unsigned)a_frag_offset(wn * T::WTN, lane)
+                              : A64 ? (unsigned)a64_frag_offset(wm * T::WTM, lane, 0) : (unsigned)a_frag_offset(wm * T::WTM, lane);
+    const unsigned bBase = TB ? (B64 ? (unsigned)a64_frag_offset(wn * T::WTN, lane, 0) : (unsigned)a_frag_offset(wn * T::WTN, lane))
                               : (unsigned)b_frag_offset<BN>(wn * T::WTN, lane, 0);
 
     f32x4_t acc[TM][TN];
@@ -278,16 +354,18 @@ gemm_bf16_kernel(const GemmParams p)
     // Lane bases held in registers the compiler cannot see through, so that each read below is
     // "base + immediate": one base covers every fragment of a k-contiguous operand, a
     // k-strided operand needs one per 16-column block (its stepping is an XOR, not an add).
-    constexpr int NA = TA ? TM : 1, NB = TB ? 1 : TN;
+    constexpr int NA = TA ? TM : A64 ? 2 : 1, NB = TB ? (B64 ? 2 : 1) : TN;
     unsigned aAddr[NA], bAddr[NB];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        aAddr[i] = (unsigned)(size_t)(GE_LDS char *)smem + (aBase ^ (unsigned)(i * 32));
+        if (A64) aAddr[i] = (unsigned)(size_t)(GE_LDS char *)smem + (unsigned)a64_frag_offset(wm * T::WTM, lane, i);
+        else aAddr[i] = (unsigned)(size_t)(GE_LDS char *)smem + (aBase ^ (unsigned)(i * 32));
         asm volatile("" : "+v"(aAddr[i]));
     }
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        bAddr[j] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(j * 32));
+        if (B64) bAddr[j] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (unsigned)a64_frag_offset(wn * T::WTN, lane, j);
+        else bAddr[j] = (unsigned)(size_t)(GE_LDS char *)smem + 4 * T::A_BYTES + (bBase ^ (unsigned)(j * 32));
         asm volatile("" : "+v"(bAddr[j]));
     }
     auto read_strided = [&](unsigned addr, int rowBytes) {
@@ -299,13 +377,16 @@ gemm_bf16_kernel(const GemmParams p)
     };
     auto read_frags = [&](int stage) {
 #pragma unroll
+        // `stage` counts 32-k pieces: under K64, piece q is half q%2 of the 64-k stage q/2
         for (int i = 0; i < TM; ++i) {
             if (TA) fa[i] = read_strided(aAddr[TA ? i : 0] + (unsigned)(stage * T::A_BYTES), BM * 2);
+            else if (A64) fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr[A64 ? (stage & 1) : 0] + (unsigned)((stage >> 1) * 2 * T::A_BYTES + i * 2048));
             else fa[i] = *(const GE_LDS bf16x8_t *)(size_t)(aAddr[0] + (unsigned)(stage * T::A_BYTES + i * 1024));
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            if (TB) fb[j] = *(const GE_LDS bf16x8_t *)(size_t)(bAddr[0] + (unsigned)(stage * T::B_BYTES + j * 1024));
+            if (B64) fb[j] = *(const GE_LDS bf16x8_t *)(size_t)(bAddr[B64 ? (stage & 1) : 0] + (unsigned)((stage >> 1) * 2 * T::B_BYTES + j * 2048));
+            else if (TB) fb[j] = *(const GE_LDS bf16x8_t *)(size_t)(bAddr[0] + (unsigned)(stage * T::B_BYTES + j * 1024));
             else fb[j] = read_strided(bAddr[TB ? 0 : j] + (unsigned)(stage * T::B_BYTES), BN * 2);
         }
     };
@@ -359,7 +440,69 @@ gemm_bf16_kernel(const GemmParams p)
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
-    if (nk <= 4) {
+    // K64, piece Q (compile time) of the ring, belonging to 64-k tile t64.  Loads of tile t64 + 1
+    // are issued in the even piece, into the stage whose second half every wave finished reading
+    // before the last barrier, and awaited in the odd piece.
+    //  8 waves: [LDS reads, (loads | wait)] barrier [MFMAs] barrier, the two groups half a piece apart;
+    //  4 waves: even piece [wait own part of this tile] barrier [loads t64+1, LDS reads, MFMAs],
+    //           odd piece [LDS reads, MFMAs].
+#define GE_BF16_STEP64(Q, t64)                                                                      \
+    if (PINGPONG) {                                                                                 \
+        read_frags(Q);                                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        if (((Q) & 1) == 0) {                                                                       \
+            issue64((t64) + 1, (((Q) >> 1) ^ 1));                                                   \
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");                         \
+        } else {                                                                                    \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");                \
+        }                                                                                           \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        __builtin_amdgcn_s_setprio(1);                                                              \
+        mma();                                                                                      \
+        __builtin_amdgcn_s_setprio(0);                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        asm volatile("s_barrier" ::: "memory");                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+    } else {                                                                                        \
+        if (((Q) & 1) == 0) {                                                                       \
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");                \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+            issue64((t64) + 1, (((Q) >> 1) ^ 1));                                                   \
+        }                                                                                           \
+        read_frags(Q);                                                                              \
+        mma();                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+    }
+
+    if constexpr (K64) {
+        if (nk64 <= 2) {
+            // the whole K range (K <= 128) fits the two stages: one load phase, then the multiply
+            issue64(0, 0);
+            if (nk64 > 1) issue64(1, 1);
+            asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (t < nk) {
+                    read_frags(t);
+                    mma();
+                }
+        } else {
+            issue64(0, 0);
+            if (PINGPONG) {
+                asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+                if (group == 1) asm volatile("s_barrier" ::: "memory");
+            }
+            for (int t = 0;; t += 2) {
+                GE_BF16_STEP64(0, t);
+                GE_BF16_STEP64(1, t);
+                if (t + 1 >= nk64) break;
+                GE_BF16_STEP64(2, t + 1);
+                GE_BF16_STEP64(3, t + 1);
+                if (t + 2 >= nk64) break;
+            }
+            if (PINGPONG && group == 0) asm volatile("s_barrier" ::: "memory");
+        }
+    } else if (nk <= 4) {
         // The whole K range fits the four stages (K <= 128, always bound by the C stores): one
         // load phase, one barrier, then the multiply; no ring, no phase groups.
 #pragma unroll
@@ -443,5 +586,6 @@ gemm_bf16_kernel(const GemmParams p)
 }
 
 #undef GE_BF16_STEP
+#undef GE_BF16_STEP64
 
 }  // namespace ge

@@ -44,6 +44,42 @@ template <int BM> void check_a()
     }
 }
 
+// the 64-k stage of a k-contiguous operand: slot map, both fragment halves, banks
+template <int BM> void check_a64()
+{
+    std::vector<int> lds(BM * 64, -1);
+    for (int wl = 0; wl < BM / 8; ++wl)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int row = a64_slot_row(wl, lane), c = a64_slot_chunk(wl, lane);
+            CHECK(row >= 0 && row < BM && c >= 0 && c < 8, "A64 slot out of tile wl=%d lane=%d", wl, lane);
+            const int slot = wl * 1024 + lane * 16;
+            CHECK(slot == lds_a64_offset(row, c), "A64 slot/offset mismatch wl=%d lane=%d", wl, lane);
+            // eight neighbouring lanes cover one row: one 128-byte line of the operand
+            CHECK(row == a64_slot_row(wl, lane & ~7), "A64 lanes of a line");
+            for (int e = 0; e < 8; ++e) {
+                CHECK(lds[slot / 2 + e] == -1, "A64 slot written twice");
+                lds[slot / 2 + e] = (row << 8) | (c * 8 + e);
+            }
+        }
+    for (int v : lds) CHECK(v != -1, "A64 stage not fully covered");
+    for (int rowBase = 0; rowBase < BM; rowBase += 16)
+        for (int h = 0; h < 2; ++h) {
+            std::set<int> banks[4];
+            for (int lane = 0; lane < 64; ++lane) {
+                const int off = a64_frag_offset(rowBase, lane, h);
+                CHECK(off % 16 == 0 && off >= 0 && off + 16 <= BM * 128, "A64 fragment address");
+                // what the kernel relies on: the row block and the lane part separate, the k half is
+                // carried by the lane part alone
+                CHECK(off == rowBase * 128 + a64_frag_offset(0, lane, h), "A64 fragment base + immediate");
+                for (int e = 0; e < 8; ++e) {
+                    const int want = ((rowBase + (lane & 15)) << 8) | (32 * h + 8 * (lane >> 4) + e);
+                    CHECK(lds[off / 2 + e] == want, "A64 fragment lane %d elem %d holds %x want %x", lane, e, lds[off / 2 + e], want);
+                }
+                CHECK(banks[lane >> 4].insert((off % 256) / 16).second, "A64 fragment bank conflict rowBase=%d lane=%d", rowBase, lane);
+            }
+        }
+}
+
 template <int BN> void check_b()
 {
     std::vector<int> lds(32 * BN, -1);
@@ -154,6 +190,8 @@ int main()
     check_a<128>();
     check_b<256>();
     check_b<128>();
+    check_a64<256>();
+    check_a64<128>();
     if (fails) { printf("%d checks failed\n", fails); return 1; }
     printf("layout checks passed\n");
     return 0;

@@ -54,6 +54,8 @@ def test_conv_3x3_tiles_256(oracle):
     run_conv_case(oracle, (4, 16, 16, 32, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=3,
                   expect="conv_bf16_256x256x32_w8")                                                      # 1024 x 256: full tiles
     run_conv_case(oracle, (1, 18, 19, 64, 264, 3, 3), pad=(1, 1), act="relu", seed=4, expect="conv_bf16_256x256x32_w8")
+    run_conv_case(oracle, (2, 16, 16, 128, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=5,
+                  expect="conv_bf16_256x256x32_w8_splitk")                                # 512 x 256: two full tiles, K = 1152
 
 
 @pytest.mark.parametrize("stride,pad,dil,k", [
@@ -67,6 +69,9 @@ def test_conv_3x3_tiles_256(oracle):
 def test_conv_geometry(oracle, stride, pad, dil, k):
     run_conv_case(oracle, (2, 17, 23, 32, 72, k[0], k[1]), stride=stride, pad=pad, dil=dil, act="relu",
                   seed=10 + k[0] + 3 * k[1], expect="conv_bf16_128x128x32_w4")
+    cfg = run_conv_case(oracle, (1, 17, 23, 128, 40, k[0], k[1]), stride=stride, pad=pad, dil=dil, out="bf16",
+                        seed=12 + k[0] + 3 * k[1])
+    assert cfg in ("conv_bf16_128x128x32_w4", "conv_bf16_128x128x32_w4_splitk")     # K slices where K is long
 
 
 @pytest.mark.parametrize("out", ["f32", "bf16"])

@@ -2,6 +2,7 @@
 operands stored either way round, row scale, residual, clamp, fp32 and bf16 output, on the
 direct-to-LDS kernels (256 and 128 tiles), the guarded kernel and the split-K path."""
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -14,13 +15,21 @@ LAYOUTS = list(itertools.product([False, True], repeat=2))
 NAME = {(False, False): "nn", (False, True): "nt", (True, False): "tn", (True, True): "tt"}
 
 
+def stage_k(transA, transB):
+    """k per load phase the library picks for a layout (64 where both operands' rows run along k);
+    GE_STAGE_K=32 switches that off for timing runs."""
+    if os.environ.get("GE_STAGE_K") == "32":
+        return 32
+    return 64 if (not transA and transB) else 32
+
+
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
 def test_layouts_tile_256(oracle, transA, transB):
     """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded."""
     for M, N, K, pad in [(256, 256, 64, (0, 0, 0, 0)), (512, 768, 256, (8, 16, 0, 4)), (520, 776, 328, (24, 8, 0, 0))]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, act="gelu_tanh",
                                       with_row_scale=True, pad=pad, seed=M + K + 2 * transA + transB)
-        assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}"
+        assert cfg == f"bf16_fused_256x256x{stage_k(transA, transB)}_w8_{NAME[transA, transB]}"
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
@@ -28,7 +37,7 @@ def test_layouts_tile_128(oracle, transA, transB):
     for M, N, K in [(128, 128, 192), (136, 248, 200), (8, 8, 8), (64, 384, 40)]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", with_row_scale=True,
                                       seed=3 * M + K)
-        assert cfg == f"bf16_fused_128x128x32_w4_{NAME[transA, transB]}"
+        assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB)}_w4_{NAME[transA, transB]}"
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
@@ -89,7 +98,7 @@ def test_split_k(oracle, transA, transB):
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
                                   with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
                                   plan="splitk", split_k=0, seed=41)
-    assert cfg == f"bf16_fused_256x256x32_w8_{NAME[transA, transB]}_splitk"
+    assert cfg == f"bf16_fused_256x256x{stage_k(transA, transB)}_w8_{NAME[transA, transB]}_splitk"
     _, _, _, cfg = run_fused_case(oracle, 130, 70, 1500, transA=transA, transB=transB, alpha=1.0 / 32,
                                   with_row_scale=True, plan="splitk", split_k=3, seed=42)
     assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}_splitk"
@@ -104,7 +113,7 @@ def test_plain_operator_is_the_special_case(oracle):
         assert cfg_f == cfg_p and not cfg_f.startswith("bf16_fused")
         assert np.array_equal(got_f, got_p)
     _, _, _, cfg = run_fused_case(oracle, 512, 512, 256, alpha=0.5, act="gelu_tanh", clamp=(-1.0, 1.0), seed=5)
-    assert cfg == "bf16_fused_256x256x32_w8_nn"
+    assert cfg == f"bf16_fused_256x256x{stage_k(False, False)}_w8_nn"
 
 
 def test_diagonal_times_dense(oracle):

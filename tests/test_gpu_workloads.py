@@ -109,7 +109,7 @@ def _run_fused_workload(oracle, name, rows_wanted, batches_wanted=4):
 
 def test_c6_fused_nt_bf16out(oracle):
     _, cfg = _run_fused_workload(oracle, "c6_fused_nt_8192_bias_gelu_bf16out", 96)
-    assert cfg == "bf16_fused_256x256x32_w8_nt"
+    assert cfg == "bf16_fused_256x256x64_w8_nt"
 
 
 def test_c7_fused_tn_chain(oracle):
