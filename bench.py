@@ -327,6 +327,9 @@ def main() -> int:
     ap.add_argument("--no-blas", action="store_true",
                     help="skip the yardstick: the BLAS that ships with PyTorch-ROCm (torch.matmul / torch.bmm, bf16 "
                          "output, no epilogue) timed on the same operands in the same run")
+    ap.add_argument("--blas-probe", action="store_true",
+                    help="only run the yardstick's BLAS call on this workload's operands, six times (for hardware "
+                         "counters of that kernel under rocprofv3)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB five times "
                          "(calibrates the FETCH_SIZE / WRITE_SIZE counters under rocprofv3)")
@@ -386,6 +389,10 @@ def main() -> int:
         bias = gen.make_bias(w)
         dA, dB, dbias = dev_bits(A), dev_bits(B), dev_bits(bias)
         dC = torch.empty(batch, M, N, dtype=torch.float32, device=dev)
+    if args.blas_probe:
+        y = blas_yardstick(torch, dA, dB, bool(fused and fw.transA), bool(fused and fw.transB), job.flops, 1, 5)
+        print(json.dumps({"blas_probe": args.workload, "launches": 6, **y}))
+        return 0
     sets = [(dA, dB, dC)]
     for _ in range(1, max(1, args.rotate)):
         sets.append((dA.clone(), dB.clone(), torch.empty_like(dC)))
