@@ -54,6 +54,11 @@ TRAFFIC = {
         "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w8_nt", (852384 * 2.0 + 131072 * 1.0) * 1024),
         "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", (16568 * 2.0 + 131072 * 1.0) * 1024),
         "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (100015 * 2.0 + 50176 * 1.0) * 1024),
+        "c2_bf16_4096": ("bf16_256x256x32_w8", (98382 * 2.0 + 65545 * 1.0) * 1024),
+        # the GEMM pass of the pair (the reduce pass: 32824 * 2.0 + 4096 KiB)
+        "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x32_w8_splitk", (131362 * 2.0 + 65536 * 1.0) * 1024),
+        "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", (853189 * 2.0 + 131072 * 1.0) * 1024),
+        "c9_diag_bf16_8192": ("diag_rows_vec4", (65730 * 2.0 + 262144 * 1.0) * 1024),
     },
 }
 
@@ -177,7 +182,8 @@ def bench_diag(args, torch, binding, gen) -> int:
     nbytes = gen.diag_algorithmic_bytes(w)
     achieved = nbytes / (ms_dev * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None, "kernel": config_name,
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(args.workload, config_name),
+                "kernel": config_name,
                 "ms_per_launch": round(ms_dev, 4)}
     # the same product as a dense GEMM: A = diag(d) rounded to bf16 (context only; d is fp32 in the entry point)
     dense = None
