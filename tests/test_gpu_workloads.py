@@ -122,3 +122,53 @@ def test_c8_fused_batched_bf16out(oracle):
     C, cfg = _run_fused_workload(oracle, "c8_fused_batched_512x512x64_bf16out", 512, batches_wanted=6)
     assert cfg == "bf16_fused_256x256x32_w8_nn"
     assert float(C.float().min()) >= 0.0
+
+
+# ---------------------------------------------------------------- structured operand and convolution
+def test_c9_diag_full(oracle):
+    """C = relu(alpha diag(d) B + bias) at 8192^2: every row of a sample against the operator's definition
+    with the dense matrix diag(d) as A (the fused oracle with A = I and row scale d)."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    w = gen.DIAG_WORKLOADS["c9_diag_bf16_8192"]
+    d, B, bias = gen.make_diag_inputs(w)
+    dd, dB, dbias = to_device(d), to_device(B), to_device(bias)
+    C = torch.empty(w.batch, w.M, w.N, dtype=torch.float32, device="cuda:0")
+    print("workload c9_diag_bf16_8192", flush=True)
+    binding.gemm_epilogue_diag_bf16(w.M, w.N, dd, dB, w.N, dbias, w.alpha, w.act, C, w.N, w.batch)
+    torch.cuda.synchronize()
+    assert binding.last_config() == "diag_rows_vec4"
+    rows = _sample_rows(w.M, 256)
+    got = C[:, torch.from_numpy(rows).cuda()].cpu().numpy()
+    # row m of diag(d) B is d[m] times row m of B: as a GEMM over the sampled rows, A = I (K = rows), scaled per row
+    eye = gen.to_bf16_bits(np.eye(len(rows), dtype=np.float64))[None]
+    ref = oracle.gemm_fused(len(rows), w.N, len(rows), eye, np.ascontiguousarray(B[:, rows]), batch=w.batch,
+                            alpha=w.alpha, row_scale=d[rows], bias=bias, act=w.act, out="f32")
+    compare(got, ref, "c9_diag_bf16_8192 [diag_rows_vec4]")
+
+
+def test_c10_conv_full(oracle):
+    """The 3x3 convolution workload at full size: first and last image (first and last tiles of the implicit
+    GEMM) against the convolution oracle, every position and channel."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    cw = gen.CONV_WORKLOADS["c10_conv3x3_256_bf16out"]
+    host = gen.make_conv_inputs(cw)
+    oh, ow = cw.out_hw()
+    dX, dW, dbias, dR = to_device(host["X"]), to_device(host["Wt"]), to_device(host["bias"]), to_device(host["residual"])
+    if dR is not None and cw.residual == "bf16":
+        dR = dR.view(torch.bfloat16)
+    Y = torch.empty(cw.N, oh, ow, cw.Cout, dtype=torch.float32 if cw.out == "f32" else torch.bfloat16, device="cuda:0")
+    print("workload c10_conv3x3_256_bf16out", flush=True)
+    binding.conv2d_epilogue_bf16(dX, dW, Y, stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha, bias=dbias,
+                                 residual=dR, beta=cw.beta, act=cw.act, clamp=cw.clamp)
+    torch.cuda.synchronize()
+    cfg = binding.last_config()
+    assert cfg == "conv_bf16_256x256x32_w8"
+    imgs = [0, cw.N - 1]
+    sub = gen.make_conv_inputs(cw, imgs)
+    got = Y[torch.tensor(imgs, device="cuda:0")].to(torch.float32).cpu().numpy()
+    ref = oracle.conv2d_nhwc(sub["X"], sub["Wt"], stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha,
+                             bias=sub["bias"], residual=sub["residual"], beta=cw.beta, act=cw.act, clamp=cw.clamp,
+                             out=cw.out)
+    compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"c10_conv3x3_256_bf16out [{cfg}]")
