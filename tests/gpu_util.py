@@ -14,7 +14,12 @@ import numpy as np
 
 REL_FRO_TOL = 1e-3
 ELEM_TOL = 1e-2
-SANITY_FRO = 1e-4
+SANITY_FRO = 1e-4            # fp32 output: accumulation noise is a few 1e-6, 1e-5 with a GELU
+# bf16 output: both sides round an fp32 value to bf16, and where the two fp32 values lie on either side of
+# a rounding boundary the results differ by one bf16 ulp (3.9e-3 relative).  A fraction f of such elements
+# gives a Frobenius error of about sqrt(f) * 2.3e-3 (an ulp error averaged over the mantissa); f is the
+# fp32 error over the bf16 spacing, up to about 1e-5 / 3.9e-3 = 0.3 %, i.e. 1.2e-4: the band is 5e-4.
+SANITY_FRO_BF16_OUT = 5e-4
 CANARY = -7.0e30
 
 
@@ -34,7 +39,7 @@ def to_device(x):
     return torch.from_numpy(np.ascontiguousarray(x)).to(torch_device())
 
 
-def compare(got: np.ndarray, ref: np.ndarray, what: str = ""):
+def compare(got: np.ndarray, ref: np.ndarray, what: str = "", bf16_out: bool = False):
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert got.shape == ref.shape, (got.shape, ref.shape)
@@ -52,7 +57,8 @@ def compare(got: np.ndarray, ref: np.ndarray, what: str = ""):
         return 0.0
     rel = nerr / nref
     assert rel <= REL_FRO_TOL, f"{what}: relative Frobenius error {rel:.3e}"
-    assert rel <= SANITY_FRO, f"{what}: error {rel:.3e} is far above fp32 accumulation noise"
+    band = SANITY_FRO_BF16_OUT if bf16_out else SANITY_FRO
+    assert rel <= band, f"{what}: error {rel:.3e} is far above fp32 accumulation noise"
     return rel
 
 
@@ -203,6 +209,6 @@ def run_fused_case(oracle, M, N, K, *, batch=1, transA=False, transB=False, alph
     ref = oracle.gemm_fused(M, N, K, As, Bs, batch=batch, transA=transA, transB=transB, lda=lda, ldb=ldb,
                             alpha=alpha, row_scale=rs, bias=bias, residual=Rs, ldr=ldr, beta=beta, act=act,
                             clamp=clamp, out=out)
-    rel = compare(got, ref, f"{cfg} fused {M}x{N}x{K}x{batch}")
+    rel = compare(got, ref, f"{cfg} fused {M}x{N}x{K}x{batch}", bf16_out=(out == "bf16"))
     del keepA, keepB
     return got, ref, rel, cfg

@@ -41,7 +41,7 @@ def run_conv_case(oracle, shape, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha
     got = Y.to(torch.float32).cpu().numpy()
     ref = oracle.conv2d_nhwc(X, Wt, stride=stride, pad=pad, dil=dil, alpha=alpha, bias=bias, residual=R, beta=beta,
                              act=act, clamp=clamp, out=out)
-    compare(got.reshape(1, -1, Cout), ref.reshape(1, -1, Cout), f"{cfg} conv {shape}")
+    compare(got.reshape(1, -1, Cout), ref.reshape(1, -1, Cout), f"{cfg} conv {shape}", bf16_out=(out == "bf16"))
     return cfg
 
 

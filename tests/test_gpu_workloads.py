@@ -103,7 +103,7 @@ def _run_fused_workload(oracle, name, rows_wanted, batches_wanted=4):
     ref = oracle.gemm_fused(len(rows), w.N, w.K, A_s, np.ascontiguousarray(B[bsel]), batch=len(bsel),
                             transA=fw.transA, transB=fw.transB, alpha=w.alpha, row_scale=rs_s, bias=host["bias"],
                             residual=R_s, beta=fw.beta, act=w.act, clamp=fw.clamp, out=fw.out)
-    compare(got, ref, f"{name} [{cfg}]")
+    compare(got, ref, f"{name} [{cfg}]", bf16_out=(fw.out == "bf16"))
     return C, cfg
 
 
@@ -171,4 +171,5 @@ def test_c10_conv_full(oracle):
     ref = oracle.conv2d_nhwc(sub["X"], sub["Wt"], stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha,
                              bias=sub["bias"], residual=sub["residual"], beta=cw.beta, act=cw.act, clamp=cw.clamp,
                              out=cw.out)
-    compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"c10_conv3x3_256_bf16out [{cfg}]")
+    compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"c10_conv3x3_256_bf16out [{cfg}]",
+            bf16_out=(cw.out == "bf16"))
