@@ -37,6 +37,7 @@ BOUND = {
     "c6_fused_nt_8192_bias_gelu_bf16out": "mfma",
     "c7_fused_tn_8192_chain": "mfma",
     "c8_fused_batched_512x512x64_bf16out": "hbm",
+    "c11_fused_lower_8192_bias_relu": "mfma",
 }
 
 
@@ -46,19 +47,20 @@ BOUND = {
 # WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
 # dropped (reported as null) as soon as the hash of csrc/ changes.
 TRAFFIC = {
-    "source_hash": "9ec8f4cc0e0207bf",
+    "source_hash": "e3ec85eecfe1ed95",
     # workload -> (kernel configuration the counters were taken on, bytes per launch)
     "bytes_per_launch": {
-        "c3_bf16_8192_bias_gelu": ("bf16_256x256x32_w8", (858565 * 2.0 + 263181 * 1.0) * 1024),
-        "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", (16484 * 2.0 + 262163 * 1.0) * 1024),
-        "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w8_nt", (852384 * 2.0 + 131072 * 1.0) * 1024),
-        "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", (16568 * 2.0 + 131072 * 1.0) * 1024),
-        "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (100015 * 2.0 + 50176 * 1.0) * 1024),
-        "c2_bf16_4096": ("bf16_256x256x32_w8", (98382 * 2.0 + 65545 * 1.0) * 1024),
+        "c2_bf16_4096": ("bf16_256x256x32_w8", (98374 * 2.0 + 65544 * 1.0) * 1024),
+        "c3_bf16_8192_bias_gelu": ("bf16_256x256x32_w8", (847800 * 2.0 + 263235 * 1.0) * 1024),
+        "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", (16480 * 2.0 + 262152 * 1.0) * 1024),
         # the GEMM pass of the pair (the reduce pass: 32824 * 2.0 + 4096 KiB)
-        "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x32_w8_splitk", (131362 * 2.0 + 65536 * 1.0) * 1024),
-        "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", (853189 * 2.0 + 131072 * 1.0) * 1024),
-        "c9_diag_bf16_8192": ("diag_rows_vec4", (65730 * 2.0 + 262144 * 1.0) * 1024),
+        "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x32_w8_splitk", (131533 * 2.0 + 65557 * 1.0) * 1024),
+        "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w8_nt", (816998 * 2.0 + 131072 * 1.0) * 1024),
+        "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", (854673 * 2.0 + 131072 * 1.0) * 1024),
+        "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", (16573 * 2.0 + 131072 * 1.0) * 1024),
+        "c9_diag_bf16_8192": ("diag_rows_vec4", (65732 * 2.0 + 262144 * 1.0) * 1024),
+        "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (99466 * 2.0 + 50176 * 1.0) * 1024),
+        "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x32_w8_nn", (686048 * 2.0 + 262146 * 1.0) * 1024),
     },
 }
 
@@ -403,6 +405,7 @@ def main() -> int:
     for _ in range(1, max(1, args.rotate)):
         sets.append((dA.clone(), dB.clone(), torch.empty_like(dC)))
     calls = [0]
+    structure = [fw.a_structure if fused else "general"]       # what step() promises about A
 
     def step():
         a, b, c = sets[calls[0] % len(sets)]
@@ -411,7 +414,7 @@ def main() -> int:
             binding.gemm_epilogue_bf16_fused(M, N, K, a, lda, b, ldb, c, N, batch=batch, transA=fw.transA,
                                              transB=fw.transB, alpha=w.alpha, row_scale=drs, bias=dbias,
                                              residual=dR, ldr=N, beta=fw.beta, act=w.act, clamp=fw.clamp,
-                                             stream=stream)
+                                             stream=stream, a_structure=structure[0])
         else:
             binding.gemm_epilogue_bf16(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
 
@@ -460,6 +463,24 @@ def main() -> int:
         top = ceilings["mfma_bf16_tflops"] if bound == "mfma" else ceilings["store_gbs"]
         roofline["frac_of_measured"] = round(achieved / top, 4)
 
+    # a structured A: the same call without the promise (every multiply-add of the full product), for scale
+    general = None
+    if structure[0] != "general":
+        structure[0] = "general"
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record(stream)
+        for _ in range(args.steps):
+            step()
+        g1.record(stream)
+        torch.cuda.synchronize()
+        general = {"ms_per_launch": round(g0.elapsed_time(g1) / args.steps, 4), "kernel": binding.last_config(),
+                   "speedup_of_the_promise": round(g0.elapsed_time(g1) / args.steps / ms_dev, 3)}
+        structure[0] = fw.a_structure
+        step()                                                  # leave the promised call's result in C
+        torch.cuda.synchronize()
     blas = None
     if not args.no_blas:
         try:
@@ -524,10 +545,12 @@ def main() -> int:
                    "out_dtype": fw.out if fused else "f32",
                    "layout": ("t" if fused and fw.transA else "n") + ("t" if fused and fw.transB else "n"),
                    "row_scale": bool(fused and fw.row_scale), "residual": fw.residual if fused else None,
-                   "clamp": fw.clamp if fused else None, "kernel": config_name},
+                   "clamp": fw.clamp if fused else None, "a_structure": fw.a_structure if fused else "general",
+                   "kernel": config_name},
         "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": roofline,
         "ceilings": ceilings,
+        "general_call": general,
         "blas_yardstick": blas,
         "cpu_baseline": cpu_baseline,
         "parity": parity,

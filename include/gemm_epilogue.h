@@ -157,6 +157,15 @@ ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K,
  *   C, ldc, c_type    device result [M, ldc >= N] per batch; GE_DTYPE_BF16 rounds the fp32
  *                     value to nearest-even.  Only C[m, 0..N) is written
  *   plan, split_k, workspace, workspace_bytes   as for gemm_epilogue_bf16_ex
+ *   a_structure       what the caller knows about opA(A) (optimisation prompt, "Rules for GEMM":
+ *                     use a stated characteristic of an operand, never an assumed one):
+ *                     GE_A_GENERAL nothing; GE_A_LOWER: opA(A)[m,k] == 0 for k > m;
+ *                     GE_A_UPPER: opA(A)[m,k] == 0 for k < m.  A promise about the VALUES, in
+ *                     every batch: the operand is still a full M x K array holding those zeros,
+ *                     the result is that of the general call bit for bit, and the library skips
+ *                     the K ranges in which a whole tile row of A is zero (about half the
+ *                     multiply-adds of a square product).  With a false promise the skipped
+ *                     terms are missing from the result.  Not with GE_PLAN_SPLITK.
  * Batches are packed: A advances by (transA ? K : M)*lda elements, B by
  * (transB ? N : K)*ldb, R by M*ldr, C by M*ldc.  C must not overlap any input.
  *
@@ -168,6 +177,7 @@ ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K,
  * Errors: as gemm_epilogue_bf16, plus GE_ERR_EPILOGUE.
  */
 typedef enum { GE_DTYPE_F32 = 0, GE_DTYPE_BF16 = 1 } ge_dtype_t;
+typedef enum { GE_A_GENERAL = 0, GE_A_LOWER = 1, GE_A_UPPER = 2 } ge_structure_t;
 
 typedef struct ge_fused_args {
     int M, N, K, batch;
@@ -182,6 +192,7 @@ typedef struct ge_fused_args {
     void *C; int ldc; ge_dtype_t c_type;
     ge_plan_t plan; int split_k;
     void *workspace; size_t workspace_bytes;
+    ge_structure_t a_structure;
 } ge_fused_args_t;
 
 ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);

@@ -25,6 +25,7 @@ SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16")
 
 DTYPE = {"f32": 0, "bf16": 1}
+STRUCTURE = {"general": 0, "lower": 1, "upper": 2}
 
 
 class FusedArgs(ctypes.Structure):
@@ -42,6 +43,7 @@ class FusedArgs(ctypes.Structure):
         ("C", ctypes.c_void_p), ("ldc", ctypes.c_int), ("c_type", ctypes.c_int),
         ("plan", ctypes.c_int), ("split_k", ctypes.c_int),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("a_structure", ctypes.c_int),
     ]
 
 
@@ -184,7 +186,7 @@ def release_workspace():
 def fused_args(M, N, K, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, *, batch=1, transA=False, transB=False,
                alpha=1.0, row_scale_ptr=None, bias_ptr=None, R_ptr=None, ldr=0, r_type="f32", beta=1.0,
                act="none", clamp=None, c_type="f32", plan="auto", split_k=0, workspace_ptr=None,
-               workspace_bytes=0) -> FusedArgs:
+               workspace_bytes=0, a_structure="general") -> FusedArgs:
     """Fill a ``ge_fused_args_t`` from raw addresses (no checks: that is the library's job)."""
     lo, hi = (-float("inf"), float("inf")) if clamp is None else clamp
     return FusedArgs(M, N, K, batch, A_ptr, lda, int(bool(transA)), B_ptr, ldb, int(bool(transB)),
@@ -192,7 +194,8 @@ def fused_args(M, N, K, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, *, batch=1, transA=F
                      ACT[act] if isinstance(act, str) else int(act), lo, hi,
                      C_ptr, ldc, DTYPE[c_type] if isinstance(c_type, str) else int(c_type),
                      PLAN[plan] if isinstance(plan, str) else int(plan), split_k,
-                     workspace_ptr, workspace_bytes)
+                     workspace_ptr, workspace_bytes,
+                     STRUCTURE[a_structure] if isinstance(a_structure, str) else int(a_structure))
 
 
 def raw_fused(args: FusedArgs, stream_handle=None) -> int:
@@ -202,10 +205,12 @@ def raw_fused(args: FusedArgs, stream_handle=None) -> int:
 
 def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA=False, transB=False,
                              alpha=1.0, row_scale=None, bias=None, residual=None, ldr=0, beta=1.0,
-                             act="none", clamp=None, plan="auto", split_k=0, workspace=None, stream=None):
+                             act="none", clamp=None, plan="auto", split_k=0, workspace=None, stream=None,
+                             a_structure="general"):
     """``C = round(clamp(act(alpha*row_scale[m]*(opA(A) @ opB(B)) + bias[n] + beta*R)))`` on device
     tensors.  A and B hold bf16 bits (int16/uint16/bfloat16 tensors); the output type follows
-    ``C.dtype`` (float32 or bfloat16/int16), the residual's its tensor's."""
+    ``C.dtype`` (float32 or bfloat16/int16), the residual's its tensor's.  ``a_structure``:
+    "general", or the caller's promise that opA(A) is "lower" / "upper" triangular."""
     import torch
     _require_device(A, B, C, row_scale, bias, residual, workspace)
 
@@ -217,7 +222,8 @@ def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA
                       R_ptr=_addr(residual), ldr=ldr, r_type=kind(residual) if residual is not None else "f32",
                       beta=beta, act=act, clamp=clamp, c_type=kind(C), plan=plan, split_k=split_k,
                       workspace_ptr=_addr(workspace),
-                      workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+                      workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size(),
+                      a_structure=a_structure)
     _check(load().gemm_epilogue_bf16_fused(ctypes.byref(args), _stream_handle(stream)))
 
 

@@ -54,7 +54,21 @@ struct GemmParams {
     int convSh, convSw, convPh, convPw, convDh, convDw;
     int transA, transB;        // operand stored transposed (read by the guarded kernel; the main
                                // kernel takes them as template arguments)
+    int triA;                  // TRI_LOWER / TRI_UPPER: opA(A) is promised triangular (0: nothing known)
 };
+
+enum { TRI_NONE = 0, TRI_LOWER = 1, TRI_UPPER = 2 };
+
+// The K range of a block whose tile covers rows [m0, m0 + BM) when opA(A) is promised triangular:
+// a lower-triangular A is zero for k > m, so nothing beyond k = m0 + BM - 1 contributes; an
+// upper-triangular one is zero for k < m, so nothing before k = m0 does.  m0 and BM are multiples
+// of every kernel's K step, so the range stays aligned to it.
+__device__ inline void triangular_k_range(const GemmParams &p, int m0, int BM, int &kBegin, int &kEnd)
+{
+    if (p.triA == TRI_LOWER) kEnd = min(kEnd, m0 + BM);
+    if (p.triA == TRI_UPPER) kBegin = max(kBegin, m0);
+    if (kEnd < kBegin) kEnd = kBegin;
+}
 
 struct TileCoord {
     int tm, tn, b, s;
@@ -76,6 +90,24 @@ __device__ inline TileCoord map_block(const GemmParams &p, unsigned bid)
     TileCoord c;
     c.b = (int)(rest % (unsigned)p.batch);
     c.s = (int)(rest / (unsigned)p.batch);
+    if (p.triA != TRI_NONE) {
+        // Tiles of a triangular A differ in work by their tile row (the K range grows or shrinks
+        // with it).  Walk the tiles in groups of four tile columns, every tile row of a group from
+        // the longest K range to the shortest: each XCD's run of logical ids then holds the same mix
+        // of long and short tiles, the long ones start first, and the tiles resident on an XCD at a
+        // time still form a block of tile rows x 4 tile columns that shares panels in its L2.
+        const unsigned groupN = 4u;
+        const unsigned perColGroup = groupN * (unsigned)p.tilesM;
+        const unsigned gc = t / perColGroup;
+        const unsigned firstN = gc * groupN;
+        unsigned cols = (unsigned)p.tilesN - firstN;
+        if (cols > groupN) cols = groupN;
+        const unsigned inc = t - gc * perColGroup;
+        const unsigned r = inc / cols;
+        c.tn = (int)(firstN + inc % cols);
+        c.tm = p.triA == TRI_LOWER ? (int)((unsigned)p.tilesM - 1u - r) : (int)r;
+        return c;
+    }
     const unsigned perGroup = (unsigned)(p.groupM * p.tilesN);
     const unsigned g = t / perGroup;
     const unsigned first = g * (unsigned)p.groupM;

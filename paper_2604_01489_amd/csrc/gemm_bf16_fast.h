@@ -149,8 +149,10 @@ gemm_bf16_kernel(const GemmParams p)
 
     const TileCoord tc = map_block(p);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
-    const int kBegin = tc.s * p.kPerSlice;
-    const int kLen = min(p.K - kBegin, p.kPerSlice);
+    int kBegin = tc.s * p.kPerSlice;
+    int kEnd = min(p.K, kBegin + p.kPerSlice);
+    if constexpr (FUSED && !CONV) triangular_k_range(p, m0, BM, kBegin, kEnd);
+    const int kLen = kEnd - kBegin;
     const int nk = (kLen + BK - 1) / BK;
 
     const long long offA = CONV ? 0ll : 2 * ((long long)tc.b * p.strideA +

@@ -42,8 +42,9 @@ gemm_bf16_fused_generic_kernel(const GemmParams p)
     const int wm = w >> 1, wn = w & 1;
     const TileCoord tc = map_block(p);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
-    const int kBegin = tc.s * p.kPerSlice;
-    const int kEnd = min(p.K, kBegin + p.kPerSlice);
+    int kBegin = tc.s * p.kPerSlice;
+    int kEnd = min(p.K, kBegin + p.kPerSlice);
+    triangular_k_range(p, m0, BM, kBegin, kEnd);
 
     const uint16_t *A = (const uint16_t *)p.A + (long long)tc.b * p.strideA;
     const uint16_t *B = (const uint16_t *)p.B + (long long)tc.b * p.strideB;

@@ -35,6 +35,8 @@ ge_status_t validate(const ge_fused_args_t &a)
     if (a.R && a.ldr < a.N) return GE_ERR_LD;
     if (a.act != GE_ACT_NONE && a.act != GE_ACT_RELU && a.act != GE_ACT_GELU_TANH) return GE_ERR_ACT;
     if (a.c_type != GE_DTYPE_F32 && a.c_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
+    if (a.a_structure != GE_A_GENERAL && a.a_structure != GE_A_LOWER && a.a_structure != GE_A_UPPER) return GE_ERR_CONFIG;
+    if (a.a_structure != GE_A_GENERAL && a.plan == GE_PLAN_SPLITK) return GE_ERR_CONFIG;
     if (a.R && a.r_type != GE_DTYPE_F32 && a.r_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
     if (!(a.clamp_lo <= a.clamp_hi)) return GE_ERR_EPILOGUE;
     const uintptr_t cMask = a.c_type == GE_DTYPE_F32 ? 3u : 1u, rMask = a.r_type == GE_DTYPE_F32 ? 3u : 1u;
@@ -130,11 +132,13 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     // nothing but scale, bias and activation on row-major operands with fp32 output: the plain
     // operator, whose kernels carry the activation as a compile-time choice
     if (!a.transA && !a.transB && !a.row_scale && !a.R && a.c_type == GE_DTYPE_F32 && std::isinf(a.clamp_lo) &&
-        a.clamp_lo < 0 && std::isinf(a.clamp_hi) && a.clamp_hi > 0)
+        a.clamp_lo < 0 && std::isinf(a.clamp_hi) && a.clamp_hi > 0 && a.a_structure == GE_A_GENERAL)
         return run_bf16(a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb, a.bias, a.alpha, a.act, (float *)a.C, a.ldc, a.batch, a.plan,
                         a.split_k, a.workspace, a.workspace_bytes, stream);
     Plan pl;
-    st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a), a.plan, a.split_k, &pl);
+    // a triangular A: every tile walks its own K range, in one pass (K slices would cut across them)
+    const ge_plan_t plan = a.a_structure != GE_A_GENERAL ? GE_PLAN_DIRECT : a.plan;
+    st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a), plan, a.split_k, &pl);
     if (st != GE_OK) return st;
 
     GemmParams p{};
@@ -171,6 +175,7 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     p.rVec = (a.R && !(((uintptr_t)a.R) & 15u) && ((long long)a.ldr * rElem) % 16 == 0) ? 1 : 0;
     p.transA = a.transA ? 1 : 0;
     p.transB = a.transB ? 1 : 0;
+    p.triA = (int)a.a_structure;
 
     const bool raw = pl.splitK > 1;
     void *ws = nullptr;

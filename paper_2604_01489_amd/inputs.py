@@ -208,10 +208,19 @@ class FusedWorkload:
     beta: float
     clamp: tuple | None
     out: str              # "f32" or "bf16"
+    a_structure: str = "general"   # "lower" / "upper": the other triangle of A (as the operator reads it) is zero
 
     @property
     def flops(self) -> float:
-        return self.base.flops
+        """Multiply-adds with a nonzero A, times two: all of them, or those of the kept triangle."""
+        w = self.base
+        if self.a_structure == "general":
+            return w.flops
+        if self.a_structure == "lower":
+            kept = sum(min(m + 1, w.K) for m in range(w.M))
+        else:
+            kept = sum(max(w.K - m, 0) for m in range(w.M))
+        return 2.0 * w.batch * w.N * kept
 
     @property
     def algorithmic_bytes(self) -> float:
@@ -240,6 +249,11 @@ FUSED_WORKLOADS = {
     "c8_fused_batched_512x512x64_bf16out": _fw(
         "c8_fused_batched_512x512x64_bf16out", 512, 512, 64, 256, 8, "normal", 1.0, 1.0, (-1.0, 1.0),
         "relu", transA=False, transB=False, row_scale=False, residual=None, beta=0.0, clamp=None, out="bf16"),
+    # a lower-triangular A (the caller says so): the multiply skips the zero K ranges of every tile row
+    "c11_fused_lower_8192_bias_relu": _fw(
+        "c11_fused_lower_8192_bias_relu", 8192, 8192, 8192, 1, 11, "normal", 8192 ** -0.5, 0.5, (-0.1, 0.1),
+        "relu", transA=False, transB=False, row_scale=False, residual=None, beta=0.0, clamp=None, out="f32",
+        a_structure="lower"),
 }
 
 
@@ -249,6 +263,10 @@ def make_fused_inputs(fw: FusedWorkload):
     w = fw.base
     A = make_operand(w, "A")
     B = make_operand(w, "B")
+    if fw.a_structure == "lower":
+        A = np.tril(A)                      # the last two axes: A[b, m, k] = 0 for k > m
+    elif fw.a_structure == "upper":
+        A = np.triu(A)
     if fw.transA:
         A = np.ascontiguousarray(A.transpose(0, 2, 1))
     if fw.transB:

@@ -137,12 +137,15 @@ def run_case(oracle, dtype, M, N, K, *, batch=1, alpha=1.0, act="none", with_bia
 
 def run_fused_case(oracle, M, N, K, *, batch=1, transA=False, transB=False, alpha=1.0, with_row_scale=False,
                    with_bias=True, residual=None, beta=1.0, act="none", clamp=None, out="f32",
-                   pad=(0, 0, 0, 0), seed=0, misalign=0, plan="auto", split_k=0, dist="uniform"):
+                   pad=(0, 0, 0, 0), seed=0, misalign=0, plan="auto", split_k=0, dist="uniform",
+                   a_structure="general", hint=True):
     """The widened operator through the C-ABI against its oracle on the same seeded inputs.
 
     ``pad`` = extra elements on (lda, ldb, ldr, ldc).  ``residual`` is None, "f32" or "bf16".
     ``misalign`` shifts the A, B and C pointers by that many elements (guarded kernel).  Padding
     of the inputs holds large finite garbage, padding of C a canary that must survive.
+    ``a_structure`` "lower" / "upper" zeroes the other triangle of A (for the oracle too, which knows
+    nothing of the hint) and, with ``hint``, passes the promise to the library.
     Returns (got, ref, relative Frobenius error, configuration name).
     """
     import torch
@@ -158,6 +161,10 @@ def run_fused_case(oracle, M, N, K, *, batch=1, transA=False, transB=False, alph
         return gen.normal(seed, stream, n, 1.0)
 
     A = gen.to_bf16_bits(draw(gen.STREAM_A, batch * M * K).reshape(batch, M, K))
+    if a_structure == "lower":
+        A = np.tril(A)                  # applied to the last two axes: A[b, m, k] = 0 for k > m
+    elif a_structure == "upper":
+        A = np.triu(A)
     B = gen.to_bf16_bits(draw(gen.STREAM_B, batch * K * N).reshape(batch, K, N))
     bias = gen.uniform(seed, gen.STREAM_BIAS, N, -1.0, 1.0) if with_bias else None
     rs = gen.uniform(seed, 7, M, 0.25, 2.0) if with_row_scale else None
@@ -197,7 +204,8 @@ def run_fused_case(oracle, M, N, K, *, batch=1, transA=False, transB=False, alph
           f"split_k={split_k}", flush=True)
     binding.gemm_epilogue_bf16_fused(M, N, K, dA, lda, dB, ldb, dC, ldc, batch=batch, transA=transA, transB=transB,
                                      alpha=alpha, row_scale=drs, bias=dbias, residual=dR, ldr=ldr, beta=beta,
-                                     act=act, clamp=clamp, plan=plan, split_k=split_k)
+                                     act=act, clamp=clamp, plan=plan, split_k=split_k,
+                                     a_structure=a_structure if hint else "general")
     torch.cuda.synchronize()
     cfg = binding.last_config()
     outv = Cbuf.to(torch.float32).cpu().numpy()

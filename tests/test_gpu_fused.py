@@ -77,6 +77,32 @@ def test_relu_then_clamp(oracle, out, clamp):
     run_fused_case(oracle, 45, 67, 33, act="relu", clamp=clamp, out=out, seed=32)       # guarded kernel
 
 
+@pytest.mark.parametrize("structure", ["lower", "upper"])
+@pytest.mark.parametrize("transA,transB", LAYOUTS)
+def test_triangular_a(oracle, structure, transA, transB):
+    """A promised triangular: the library skips the K ranges in which a whole tile row of A is zero.
+    Same result as the oracle on that A (which is told nothing), and bit for bit the result of the
+    same call without the promise (the skipped terms are exact zeros)."""
+    cases = [(768, 520, 768, "f32", {}),                      # 256 tiles, square A, ragged N
+             (520, 264, 1032, "bf16", {}),                    # K > M, ragged everything
+             (1032, 256, 520, "f32", {}),                     # M > K: tile rows past the last column
+             (392, 136, 392, "bf16", dict(pad=(8, 8, 0, 8))), # 128 tiles (N < 256)
+             (200, 67, 131, "f32", {})]                       # guarded kernel
+    for M, N, K, out, extra in cases:
+        kw = dict(transA=transA, transB=transB, alpha=0.5, act="relu", with_row_scale=True, out=out,
+                  seed=50 + M + K, a_structure=structure, plan="direct", **extra)      # one pass, the same order of sums
+        got, _, _, cfg = run_fused_case(oracle, M, N, K, **kw)
+        plain, _, _, cfg2 = run_fused_case(oracle, M, N, K, hint=False, **kw)
+        assert cfg == cfg2
+        assert np.array_equal(got, plain), f"{cfg}: the promise changed the result"
+    # batched, and the promise is not compatible with K slices
+    run_fused_case(oracle, 512, 256, 512, batch=3, transA=transA, transB=transB, residual="bf16", out="bf16",
+                   seed=60, a_structure=structure)
+    with pytest.raises(Exception):
+        run_fused_case(oracle, 256, 256, 2048, transA=transA, transB=transB, plan="splitk", split_k=4,
+                       a_structure=structure)
+
+
 def test_bf16_output_all_paths(oracle):
     run_fused_case(oracle, 512, 512, 128, out="bf16", act="relu", seed=21)                       # 256 tile, full
     run_fused_case(oracle, 264, 520, 72, out="bf16", act="none", pad=(0, 0, 0, 6), seed=22)      # 256 tile, ragged, ldc even

@@ -91,7 +91,8 @@ def _run_fused_workload(oracle, name, rows_wanted, batches_wanted=4):
     print(f"fused workload {name}", flush=True)
     binding.gemm_epilogue_bf16_fused(w.M, w.N, w.K, dA, A.shape[2], dB, B.shape[2], C, w.N, batch=w.batch,
                                      transA=fw.transA, transB=fw.transB, alpha=w.alpha, row_scale=drs, bias=dbias,
-                                     residual=dR, ldr=w.N, beta=fw.beta, act=w.act, clamp=fw.clamp)
+                                     residual=dR, ldr=w.N, beta=fw.beta, act=w.act, clamp=fw.clamp,
+                                     a_structure=fw.a_structure)
     torch.cuda.synchronize()
     cfg = binding.last_config()
     rows = _sample_rows(w.M, rows_wanted)
@@ -173,3 +174,10 @@ def test_c10_conv_full(oracle):
                              out=cw.out)
     compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"c10_conv3x3_256_bf16out [{cfg}]",
             bf16_out=(cw.out == "bf16"))
+
+
+def test_c11_fused_lower_triangular(oracle):
+    """8192^3 with a lower-triangular A and the caller's promise: sampled rows (first and last tile
+    rows included: the shortest and the longest K range) against the oracle, which is told nothing."""
+    _, cfg = _run_fused_workload(oracle, "c11_fused_lower_8192_bias_relu", 96)
+    assert cfg == "bf16_fused_256x256x32_w8_nn"

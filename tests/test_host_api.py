@@ -79,6 +79,9 @@ def test_fused_argument_errors_return_codes(lib):
     assert call(clamp=(1.0, 0.5)) == 9 and call(clamp=(float("nan"), 1.0)) == 9
     assert call(c_type=2) == 9
     assert call(plan=7) == 8
+    # the promise about A: a known value, and never together with K slices
+    assert call(a_structure=3) == 8 and call(a_structure=-1) == 8
+    assert call(a_structure="lower", plan="splitk") == 8 and call(a_structure="upper", plan="splitk", split_k=4) == 8
     # bf16 output only needs 2-byte alignment of C
     assert call(C_ptr=P + 2, c_type="bf16", plan=7) == 8
     assert binding.load().gemm_epilogue_bf16_fused(None, None) == 1
