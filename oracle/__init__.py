@@ -301,3 +301,19 @@ def conv2d_nhwc(X, Wt, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return Y
+
+
+def gemm_rowsum(A, B, bias=None, alpha=1.0):
+    """Reference for the row sum of a linear layer, ``y[m] = sum_n (alpha * (A @ B)[m, n] + bias[n])``,
+    as an fp64 vector of length M (Level-2 optimisation prompt, "First priority: algebraic
+    simplification": the sum over the output dimension of a linear layer).
+
+    The definition written out: the full product by the pinned GEMM oracle (fp64 sums over k, no
+    activation), then the sum over n of every row in fp64.  The GPU path never forms the product: it
+    uses the collapsed form ``alpha * A @ (B @ 1) + sum(bias)``, which a pin ties to this definition.
+    A: (M, K), B: (K, N) as the operator reads it (a weight matrix stored N x K is passed transposed).
+    """
+    C = gemm_epilogue(A, B, bias, alpha, "none")
+    if C.ndim == 3:
+        C = C[0]
+    return np.sum(C, axis=1, dtype=np.float64)
