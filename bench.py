@@ -47,7 +47,7 @@ BOUND = {
 # WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
 # dropped (reported as null) as soon as the hash of csrc/ changes.
 TRAFFIC = {
-    "source_hash": "e3ec85eecfe1ed95",
+    "source_hash": "fcb4aaa45540dad8",
     # workload -> (kernel configuration the counters were taken on, bytes per launch)
     "bytes_per_launch": {
         "c2_bf16_4096": ("bf16_256x256x32_w8", (98374 * 2.0 + 65544 * 1.0) * 1024),
@@ -61,12 +61,15 @@ TRAFFIC = {
         "c9_diag_bf16_8192": ("diag_rows_vec4", (65732 * 2.0 + 262144 * 1.0) * 1024),
         "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (99466 * 2.0 + 50176 * 1.0) * 1024),
         "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x32_w8_nn", (686048 * 2.0 + 262146 * 1.0) * 1024),
+        # the three kernels of a step: column sums of the weights (two passes), then the pass over the input
+        "c12_rowsum_linear_8192": ("rowsum_rows_vec8", ((65580 + 2080 + 65690) * 2.0 + (4096 + 32 + 32) * 1.0) * 1024),
     },
 }
 
 
-# the device code of the GEMM kernels (host-side dispatch is covered by the kernel name stored with each entry)
-KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h", "gemm_fused.h")
+# the device code of the kernels (host-side dispatch of the GEMMs is covered by the kernel name stored with each entry)
+KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_f32_fast.h", "gemm_generic.h", "gemm_fused.h",
+                  "gemm_diag.hip", "gemm_rowsum.hip")
 
 
 def kernel_source_hash() -> str:
@@ -226,6 +229,85 @@ def bench_diag(args, torch, binding, gen) -> int:
     return 0 if parity is None or parity["ok"] else 1
 
 
+def bench_rowsum(args, torch, binding, gen) -> int:
+    """The row sum of a linear layer by its collapsed form: a step is the parameter reduction plus the
+    reduction over the input (nothing cached); the input-only call and the long way round (the layer
+    through the fused GEMM, then a sum over its output) are timed beside it."""
+    import oracle
+    w = gen.ROWSUM_WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    M, N, K = w.M, w.N, w.K
+    A, Wt, bias = gen.make_rowsum_inputs(w)
+    dA = torch.from_numpy(A.view(np.int16)).to(dev)
+    dW = torch.from_numpy(Wt.view(np.int16)).to(dev)
+    dbias = torch.from_numpy(bias).to(dev)
+    params = torch.empty(K + 1, dtype=torch.float32, device=dev)
+    y = torch.empty(M, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    def step():
+        binding.gemm_rowsum_params_bf16(N, K, dW, K, True, dbias, params, stream=stream)
+        binding.gemm_rowsum_bf16(M, K, dA, K, params, w.alpha, y, stream=stream)
+
+    ms_wall, ms_dev = timed(step, args.warmup, args.steps)
+    _, ms_params = timed(lambda: binding.gemm_rowsum_params_bf16(N, K, dW, K, True, dbias, params, stream=stream),
+                         args.warmup, args.steps)
+    cfg_params = binding.last_config()
+    _, ms_apply = timed(lambda: binding.gemm_rowsum_bf16(M, K, dA, K, params, w.alpha, y, stream=stream),
+                        args.warmup, args.steps)
+    config_name = binding.last_config()
+    nbytes = gen.rowsum_algorithmic_bytes(w)
+    achieved = nbytes / (ms_dev * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(args.workload, config_name),
+                "kernel": config_name, "ms_per_launch": round(ms_dev, 4),
+                "ms_parameter_pass": round(ms_params, 4), "kernel_parameter_pass": cfg_params,
+                "ms_input_pass": round(ms_apply, 4)}
+    # the long way round: the layer's output through the fused GEMM (fp32), then its sum over n
+    dC = torch.empty(M, N, dtype=torch.float32, device=dev)
+    _, ms_long = timed(lambda: (binding.gemm_epilogue_bf16_fused(M, N, K, dA, K, dW, K, dC, N, transB=True, alpha=w.alpha,
+                                                                bias=dbias, stream=stream), dC.sum(dim=1)),
+                       3, 10)
+    long_way = {"ms_per_launch": round(ms_long, 4), "what": "gemm_epilogue_bf16_fused (fp32 out) + torch sum over n",
+                "speedup_of_the_collapse": round(ms_long / ms_dev, 1)}
+    cpu_baseline = parity = None
+    if args.oracle_rows > 0:
+        rows = sample_rows(M, min(args.oracle_rows, 2048))
+        got = y[torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ref = oracle.gemm_rowsum(np.ascontiguousarray(A[rows]), np.ascontiguousarray(Wt.T), bias, w.alpha)
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(len(rows) / M * nbytes / (c1 - c0) / 1e9, 6), "unit": "GB/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"{len(rows)} of {M} rows of y, by the definition (full product, then the sum); "
+                                  f"{c1 - c0:.1f} s"}
+        err = np.abs(got - ref)
+        rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+        parity = {"rows_checked": int(len(rows)), "rel_frobenius": rel, "max_abs_err": float(err.max()),
+                  "ok": bool(rel <= 1e-3 and np.all(err <= 1e-2 * np.maximum(1.0, np.abs(ref))))}
+    out = {"metric": "GB/s of the row sum of a linear layer (collapsed form)", "value": round(nbytes / (ms_wall * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_wall, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "M": M, "N": N, "K": K, "alpha": w.alpha, "bias": True,
+                      "weights": "N x K", "kernel": config_name},
+           "roofline": roofline, "long_way": long_way, "cpu_baseline": cpu_baseline, "parity": parity}
+    print(json.dumps(out))
+    return 0 if parity is None or parity["ok"] else 1
+
+
 def bench_conv(args, torch, binding, gen) -> int:
     """The convolution front-end (implicit GEMM on the main kernel, fused consumer chain)."""
     import oracle
@@ -367,6 +449,8 @@ def main() -> int:
         return bench_diag(args, torch, binding, gen)
     if args.workload in gen.CONV_WORKLOADS:
         return bench_conv(args, torch, binding, gen)
+    if args.workload in gen.ROWSUM_WORKLOADS:
+        return bench_rowsum(args, torch, binding, gen)
     fused = args.workload in gen.FUSED_WORKLOADS
     fw = gen.FUSED_WORKLOADS[args.workload] if fused else None
     w = fw.base if fused else gen.WORKLOADS[args.workload]

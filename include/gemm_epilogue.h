@@ -269,6 +269,42 @@ ge_status_t gemm_epilogue_diag_bf16(int M, int N, const float *d,
                                     const float *bias, float alpha, ge_act_t act,
                                     float *C, int ldc, int batch, void *stream);
 
+/*
+ * Row sum of a linear layer, without the layer's output:
+ *
+ *     y[m] = sum_{n<N} ( alpha * sum_{k<K} A[m,k] * opB(B)[k,n] + bias[n] )
+ *          = alpha * sum_{k<K} A[m,k] * s[k] + t,     s[k] = sum_n opB(B)[k,n],  t = sum_n bias[n]
+ *
+ * The second line is the algebraic simplification the Level-2 optimisation prompt puts before
+ * any tuning ("First priority: algebraic simplification": the sum over the output dimension of a
+ * linear layer becomes x @ sum(weight) + sum(bias)); it is exact in real arithmetic and needs
+ * 2 K (M + N) operations instead of 2 M N K.  s and t depend on the layer's parameters only and
+ * are computed by a call of their own, to be kept for every later input (same prompt,
+ * "Parameter-only reduction rule").  Both calls are bound by HBM: B is read once, then A once.
+ * Sums are fp32, in a fixed order: results are repeatable bit for bit.
+ *
+ * gemm_rowsum_params_bf16:
+ *   N, K >= 1
+ *   B, ldb, transB    device, bf16 bits.  transB = 0: B[k,n] = B[k*ldb + n], ldb >= N;
+ *                     transB != 0 (a weight matrix as frameworks store it): B[k,n] = B[n*ldb + k], ldb >= K
+ *   bias              device, fp32[N], or NULL (t = 0)
+ *   params            device, fp32[K + 1], written: s[0..K), then t
+ * gemm_rowsum_bf16:
+ *   M, K >= 1
+ *   A, lda            device, bf16 bits, A[m,k] = A[m*lda + k], lda >= K
+ *   params            device, fp32[K + 1] as written by gemm_rowsum_params_bf16
+ *   y                 device, fp32[M], written
+ * 16-byte row pieces are used when the pointer and leading dimension allow it, single elements
+ * otherwise.  gemm_rowsum_params_bf16 with transB != 0 uses the library-owned workspace (see
+ * gemm_epilogue_bf16) for partial column sums.
+ * Errors: GE_ERR_NULL, GE_ERR_SHAPE, GE_ERR_LD, GE_ERR_ALIGN (a pointer not aligned to its
+ * element), GE_ERR_WORKSPACE, GE_ERR_LAUNCH.
+ */
+ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, int ldb, int transB,
+                                    const float *bias, float *params, void *stream);
+ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda, const float *params,
+                             float alpha, float *y, void *stream);
+
 /* Bytes of split-K workspace the bf16 call needs for this shape with `plan` and
  * `split_k` as above (0 when the chosen plan is direct).  Host only. */
 size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch,

@@ -22,7 +22,7 @@ SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
            "ge_release_workspace", "ge_status_string", "ge_last_config",
            "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused",
-           "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16")
+           "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16")
 
 DTYPE = {"f32": 0, "bf16": 1}
 STRUCTURE = {"general": 0, "lower": 1, "upper": 2}
@@ -102,6 +102,10 @@ def load():
     lib.gemm_epilogue_diag_bf16.restype = c_int
     lib.gemm_epilogue_diag_bf16.argtypes = [c_int, c_int, c_void, c_void, c_int, c_void, c_float, c_int,
                                             c_void, c_int, c_int, c_void]
+    lib.gemm_rowsum_params_bf16.restype = c_int
+    lib.gemm_rowsum_params_bf16.argtypes = [c_int, c_int, c_void, c_int, c_int, c_void, c_void, c_void]
+    lib.gemm_rowsum_bf16.restype = c_int
+    lib.gemm_rowsum_bf16.argtypes = [c_int, c_int, c_void, c_int, c_void, c_float, c_void, c_void]
     lib.ge_probe_mfma_bf16.restype = c_int
     lib.ge_probe_mfma_bf16.argtypes = [c_void, c_void, c_int, c_int, c_void]
     lib.ge_probe_store_f32.restype = c_int
@@ -270,6 +274,30 @@ def gemm_epilogue_diag_bf16(M, N, d, B, ldb, bias, alpha, act, C, ldc, batch=1, 
 def raw_diag(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch) -> int:
     """The status code of ``gemm_epilogue_diag_bf16`` (for argument-error tests)."""
     return int(load().gemm_epilogue_diag_bf16(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch, None))
+
+
+def gemm_rowsum_params_bf16(N, K, B, ldb, transB, bias, params, stream=None):
+    """``params[k] = sum_n opB(B)[k, n]`` for k < K, ``params[K] = sum(bias)``: the parameter-only part of
+    the row sum of a linear layer, on device tensors."""
+    _require_device(B, bias, params)
+    _check(load().gemm_rowsum_params_bf16(N, K, _ptr(B), ldb, int(bool(transB)), _ptr(bias), _ptr(params),
+                                          _stream_handle(stream)))
+
+
+def gemm_rowsum_bf16(M, K, A, lda, params, alpha, y, stream=None):
+    """``y[m] = alpha * sum_k A[m, k] * params[k] + params[K]``: the row sum of the layer's output."""
+    _require_device(A, params, y)
+    _check(load().gemm_rowsum_bf16(M, K, _ptr(A), lda, _ptr(params), alpha, _ptr(y), _stream_handle(stream)))
+
+
+def raw_rowsum_params(N, K, B_ptr, ldb, transB, bias_ptr, params_ptr) -> int:
+    """Status code of ``gemm_rowsum_params_bf16`` (for argument-error tests)."""
+    return int(load().gemm_rowsum_params_bf16(N, K, B_ptr, ldb, transB, bias_ptr, params_ptr, None))
+
+
+def raw_rowsum(M, K, A_ptr, lda, params_ptr, alpha, y_ptr) -> int:
+    """Status code of ``gemm_rowsum_bf16`` (for argument-error tests)."""
+    return int(load().gemm_rowsum_bf16(M, K, A_ptr, lda, params_ptr, alpha, y_ptr, None))
 
 
 def probe_mfma_bf16(operands, sink, blocks, iters, stream=None):

@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_epilogue.so")
-SOURCES = ["gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip", "gemm_diag.hip", "ge_probes.hip"]
+SOURCES = ["gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip", "gemm_diag.hip", "gemm_rowsum.hip", "ge_probes.hip"]
 # packed fp32 instructions are kept off: some of their forms have misbehaved on this hardware
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -290,6 +290,27 @@ DIAG_WORKLOADS = {
 }
 
 
+# ---------------------------------------------------------------------------------------------
+# row sum of a linear layer: y = sum_n (alpha x W^T + b); W stored N x K as frameworks keep it
+# ---------------------------------------------------------------------------------------------
+ROWSUM_WORKLOADS = {
+    "c12_rowsum_linear_8192": Workload("c12_rowsum_linear_8192", "bf16", 8192, 8192, 8192, 1, 12, "normal",
+                                       8192 ** -0.5, 0.5, (-0.1, 0.1), "none"),
+}
+
+
+def make_rowsum_inputs(w: Workload):
+    """(A bf16 bits [M, K], W bf16 bits [N, K] -- the operator's B is its transpose --, bias fp32[N])."""
+    A = make_operand(w, "A")[0]
+    Wt = np.ascontiguousarray(make_operand(w, "B")[0].T)
+    return A, Wt, make_bias(w)
+
+
+def rowsum_algorithmic_bytes(w: Workload) -> float:
+    """Read A, the weights and the bias once, write y once."""
+    return float((w.M * w.K + w.K * w.N) * 2 + 4 * w.N + 4 * w.M)
+
+
 def make_diag_inputs(w: Workload):
     """(d fp32[M] ~ U(0.5, 1.5), B bf16 bits [batch, M, N], bias)."""
     d = uniform(w.seed, STREAM_ROW_SCALE, w.M, 0.5, 1.5)

@@ -181,3 +181,25 @@ def test_c11_fused_lower_triangular(oracle):
     rows included: the shortest and the longest K range) against the oracle, which is told nothing."""
     _, cfg = _run_fused_workload(oracle, "c11_fused_lower_8192_bias_relu", 96)
     assert cfg == "bf16_fused_256x256x32_w8_nn"
+
+
+def test_c12_rowsum_linear_full(oracle):
+    """The row sum of an 8192 x 8192 linear layer over 8192 inputs by the collapsed form: sampled rows
+    against the definition (full product in fp64, then the sum over the output dimension)."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    w = gen.ROWSUM_WORKLOADS["c12_rowsum_linear_8192"]
+    A, Wt, bias = gen.make_rowsum_inputs(w)
+    dA, dW, dbias = to_device(A), to_device(Wt), to_device(bias)
+    params = torch.empty(w.K + 1, dtype=torch.float32, device="cuda:0")
+    y = torch.empty(w.M, dtype=torch.float32, device="cuda:0")
+    print("workload c12_rowsum_linear_8192", flush=True)
+    binding.gemm_rowsum_params_bf16(w.N, w.K, dW, w.K, True, dbias, params)
+    assert binding.last_config() == "rowsum_params_cols"
+    binding.gemm_rowsum_bf16(w.M, w.K, dA, w.K, params, w.alpha, y)
+    assert binding.last_config() == "rowsum_rows_vec8"
+    torch.cuda.synchronize()
+    rows = _sample_rows(w.M, 128)
+    got = y[torch.from_numpy(rows).cuda()].cpu().numpy()[None, :, None]
+    ref = oracle.gemm_rowsum(np.ascontiguousarray(A[rows]), np.ascontiguousarray(Wt.T), bias, w.alpha)[None, :, None]
+    compare(got, ref, "c12_rowsum_linear_8192 [rowsum_rows_vec8]")

@@ -22,7 +22,7 @@ def test_exports_every_declared_symbol(lib):
     inc = os.path.join(ROOT, "include")
     header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*|conv2d_epilogue\w*)\s*\(", header))
+    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*|conv2d_epilogue\w*|gemm_rowsum\w*)\s*\(", header))
     assert declared == set(binding.SYMBOLS), declared ^ set(binding.SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -101,6 +101,20 @@ def test_diag_argument_errors_return_codes(lib):
     assert call(ldb=47) == 3 and call(ldc=47) == 3
     assert call(act=5) == 4
     assert call(B=P + 1) == 5 and call(C=P + 2) == 5 and call(d=P + 2) == 5 and call(bias=P + 1) == 5
+
+
+def test_rowsum_argument_errors_return_codes(lib):
+    assert binding.raw_rowsum_params(48, 32, None, 48, 0, None, P) == 1 and binding.raw_rowsum_params(48, 32, P, 48, 0, None, None) == 1
+    assert binding.raw_rowsum_params(0, 32, P, 48, 0, None, P) == 2 and binding.raw_rowsum_params(48, 0, P, 48, 0, None, P) == 2
+    assert binding.raw_rowsum_params(48, 32, P, 47, 0, None, P) == 3          # B is K x N: ldb >= N
+    assert binding.raw_rowsum_params(48, 32, P, 31, 1, None, P) == 3          # B stored N x K: ldb >= K
+    assert binding.raw_rowsum_params(48, 32, P + 1, 48, 0, None, P) == 5 and binding.raw_rowsum_params(48, 32, P, 48, 0, P + 2, P) == 5
+    assert binding.raw_rowsum_params(48, 32, P, 48, 0, None, P + 2) == 5
+    assert binding.raw_rowsum_params(65536 * 128, 8, P, 8, 1, None, P) == 2   # more column-sum chunks than the grid carries
+    assert binding.raw_rowsum(64, 32, None, 32, P, 1.0, P) == 1 and binding.raw_rowsum(64, 32, P, 32, None, 1.0, P) == 1
+    assert binding.raw_rowsum(64, 32, P, 32, P, 1.0, None) == 1
+    assert binding.raw_rowsum(0, 32, P, 32, P, 1.0, P) == 2 and binding.raw_rowsum(64, 32, P, 31, P, 1.0, P) == 3
+    assert binding.raw_rowsum(64, 32, P + 1, 32, P, 1.0, P) == 5 and binding.raw_rowsum(64, 32, P, 32, P, 1.0, P + 2) == 5
 
 
 def test_conv_argument_errors_return_codes(lib):
