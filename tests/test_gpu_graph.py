@@ -51,3 +51,56 @@ def test_calls_replay_from_a_captured_graph():
         torch.cuda.synchronize()
         for got, want in zip(out, eager):
             assert torch.equal(got, want), f"replay {replay} differs from the eager result"
+
+
+def test_convolution_rowsum_and_structured_calls_replay_from_a_captured_graph():
+    """The convolution, the row-sum pair (weights stored K x N: no workspace), the diagonal operand and a
+    product with a promised triangular A: kernels only, so their capture replays bit for bit."""
+    import torch
+    from paper_2604_01489_amd import binding, inputs as gen
+    dev = torch.device("cuda:0")
+
+    def bf16(seed, stream, shape, scale=1.0):
+        return torch.from_numpy(gen.to_bf16_bits(gen.normal(seed, stream, int(np.prod(shape)), scale).reshape(shape))
+                                .view(np.int16)).to(dev)
+
+    X, Wt = bf16(80, 0, (2, 20, 20, 64)), bf16(80, 1, (72, 3, 3, 64), 576 ** -0.5)
+    M, N, K = 520, 264, 520
+    A = torch.from_numpy(np.tril(gen.to_bf16_bits(gen.normal(81, 0, M * K, K ** -0.5).reshape(M, K))).view(np.int16)).to(dev)
+    B = bf16(81, 1, (K, N))
+    bias = torch.from_numpy(gen.uniform(81, 2, N, -1.0, 1.0)).to(dev)
+    d = torch.from_numpy(gen.uniform(82, 7, K, 0.5, 1.5)).to(dev)
+
+    def enqueue(Y, C, params, y, D, stream):
+        binding.conv2d_epilogue_bf16(X, Wt, Y, pad=(1, 1), act="relu", stream=stream)
+        binding.gemm_epilogue_bf16_fused(M, N, K, A, K, B, N, C, N, bias=bias, act="relu", a_structure="lower", stream=stream)
+        binding.gemm_rowsum_params_bf16(N, K, B, N, False, bias, params, stream=stream)
+        binding.gemm_rowsum_bf16(M, K, A, K, params, 0.5, y, stream=stream)
+        binding.gemm_epilogue_diag_bf16(K, N, d, B, N, bias, 0.5, "relu", D, N, 1, stream=stream)
+
+    def buffers():
+        return [torch.empty(2, 20, 20, 72, dtype=torch.bfloat16, device=dev), torch.empty(M, N, device=dev),
+                torch.empty(K + 1, device=dev), torch.empty(M, device=dev), torch.empty(K, N, device=dev)]
+
+    eager = buffers()
+    enqueue(*eager, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    out = buffers()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        print("capturing", flush=True)
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(*out, torch.cuda.current_stream())
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in out:
+            t.fill_(-1.0)
+        torch.cuda.synchronize()
+        print(f"replay {replay}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(out, eager):
+            assert torch.equal(got, want), f"replay {replay} differs from the eager result"
