@@ -29,7 +29,7 @@ struct Plan {
 
 extern thread_local const char *g_last_config;
 
-int choose_split(long long tiles, int K);
+int choose_split(long long tiles, int K, int minSlice);
 ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out);
 size_t partial_bytes(int M, int N, int batch, int splitK);
 int choose_group_m(int tilesM, int tilesN);

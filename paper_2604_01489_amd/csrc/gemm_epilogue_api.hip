@@ -37,9 +37,9 @@ bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
 }
 
 // K slices so that a launch with few output tiles still covers the chip.
-int choose_split(long long tiles, int K)
+int choose_split(long long tiles, int K, int minSlice)
 {
-    constexpr int kMinSlice = 512;             // K extent below which a slice is not worth its partial tile
+    const int kMinSlice = minSlice;            // K extent below which a slice is not worth its partial tile
     if (tiles * 2 > kNumCU || K < 2 * kMinSlice) return 1;
     long long s = kNumCU / tiles;
     const long long maxS = K / kMinSlice;
@@ -64,6 +64,12 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
         pl.tile = TILE_GENERIC; pl.bm = 64; pl.bn = 64; pl.bk = 32;
     } else {
         bool big = (M >= 256 && N >= 256);
+        // Few 256 x 256 tiles (half the CUs or fewer) and a K that is not long: four times as many
+        // 128 x 128 tiles, two to a CU, fill the machine with fewer or no K slices.  Found by the
+        // timed search over tile and slice count (tune.py): 2048^3 24.5 us against 38.8 us,
+        // 1024 x 1024 x 8192 28.6 against 36.6; with K = 65536 the 256 tiles' cheaper main loop
+        // wins again (144 against 191 us), hence the bound on K.
+        if (big && (long long)ceil_div(M, 256) * ceil_div(N, 256) * batch * 2 <= kNumCU && K <= 16384) big = false;
         if (force && std::strcmp(force, "256x256") == 0) big = true;
         if (force && std::strcmp(force, "128x128") == 0) big = false;
         if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = ge::BF16_BK; }
@@ -74,11 +80,13 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
     const long long tiles = (long long)pl.tilesM * pl.tilesN * batch;
     if (tiles > 0x7fffffffll / 64) return GE_ERR_SHAPE;
     int want = 1;
+    // slices of at least 512 k; 1024 for the 128 x 128 tiles (timed search)
+    const int minSlice = pl.tile == TILE_128 ? 1024 : 512;
     if (plan == GE_PLAN_SPLITK) {
-        want = split_k > 0 ? split_k : choose_split(tiles, K);
+        want = split_k > 0 ? split_k : choose_split(tiles, K, minSlice);
         if (want < 2) want = 2;
     } else if (plan == GE_PLAN_AUTO) {
-        want = choose_split(tiles, K);
+        want = choose_split(tiles, K, minSlice);
     } else if (plan != GE_PLAN_DIRECT) {
         return GE_ERR_CONFIG;
     }

@@ -50,7 +50,10 @@ def test_conv_3x3_tiles_128(oracle):
     run_conv_case(oracle, (1, 16, 16, 32, 128, 3, 3), pad=(1, 1), seed=2, expect="conv_bf16_128x128x32_w4")   # 256 x 128: full tiles
 
 
-def test_conv_3x3_tiles_256(oracle):
+def test_conv_3x3_tiles_256(oracle, monkeypatch):
+    """The 256 x 256 gathering kernel on shapes the oracle finishes quickly (forced: the planning rule gives so
+    few tiles to the 128 x 128 kernel)."""
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     run_conv_case(oracle, (4, 16, 16, 32, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=3,
                   expect="conv_bf16_256x256x32_w8")                                                      # 1024 x 256: full tiles
     run_conv_case(oracle, (1, 18, 19, 64, 264, 3, 3), pad=(1, 1), act="relu", seed=4, expect="conv_bf16_256x256x32_w8")
@@ -90,15 +93,19 @@ def test_conv_guarded_kernel(oracle):
     run_conv_case(oracle, (1, 8, 8, 32, 12, 1, 1), seed=32, expect="conv_bf16_generic_64x64x32")   # Cout not a multiple of 8
 
 
-def test_conv_split_k_for_few_tiles_and_long_k(oracle):
+def test_conv_split_k_for_few_tiles_and_long_k(oracle, monkeypatch):
     """Late-layer shapes: a handful of output tiles and K = KH*KW*Cin in the thousands -> K slices,
     summed in slice order by the second pass, which also runs the consumer chain."""
     cfg = run_conv_case(oracle, (1, 8, 8, 512, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=40)
     assert cfg == "conv_bf16_128x128x32_w4_splitk"
     cfg = run_conv_case(oracle, (4, 9, 9, 256, 512, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=41)
-    assert cfg == "conv_bf16_256x256x32_w8_splitk"
+    assert cfg == "conv_bf16_128x128x32_w4_splitk"
     cfg = run_conv_case(oracle, (1, 7, 7, 200, 100, 3, 3), pad=(1, 1), stride=(2, 2), act="relu", clamp=(0.0, 1.0), seed=42)
     assert cfg == "conv_bf16_generic_64x64x32_splitk"
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")            # the 256 x 256 kernel's partial tiles
+    cfg = run_conv_case(oracle, (4, 9, 9, 256, 512, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=41)
+    assert cfg == "conv_bf16_256x256x32_w8_splitk"
+    monkeypatch.delenv("GE_FORCE_CONFIG")
     # repeatable bit for bit
     import torch
     from paper_2604_01489_amd import binding, inputs as gen

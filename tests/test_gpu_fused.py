@@ -24,8 +24,10 @@ def stage_k(transA, transB):
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
-def test_layouts_tile_256(oracle, transA, transB):
-    """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded."""
+def test_layouts_tile_256(oracle, transA, transB, monkeypatch):
+    """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded.
+    (The 256 x 256 kernel is forced: by the planning rule so few tiles go to the 128 x 128 kernel.)"""
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     for M, N, K, pad in [(256, 256, 64, (0, 0, 0, 0)), (512, 768, 256, (8, 16, 0, 4)), (520, 776, 328, (24, 8, 0, 0))]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, act="gelu_tanh",
                                       with_row_scale=True, pad=pad, seed=M + K + 2 * transA + transB)
@@ -120,7 +122,12 @@ def test_batched(oracle):
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
-def test_split_k(oracle, transA, transB):
+def test_split_k(oracle, transA, transB, monkeypatch):
+    _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
+                                  with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
+                                  plan="splitk", split_k=0, seed=41)
+    assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB)}_w4_{NAME[transA, transB]}_splitk"
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
                                   with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
                                   plan="splitk", split_k=0, seed=41)
@@ -128,6 +135,7 @@ def test_split_k(oracle, transA, transB):
     _, _, _, cfg = run_fused_case(oracle, 130, 70, 1500, transA=transA, transB=transB, alpha=1.0 / 32,
                                   with_row_scale=True, plan="splitk", split_k=3, seed=42)
     assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}_splitk"
+    monkeypatch.delenv("GE_FORCE_CONFIG")
 
 
 def test_plain_operator_is_the_special_case(oracle):
@@ -139,7 +147,7 @@ def test_plain_operator_is_the_special_case(oracle):
         assert cfg_f == cfg_p and not cfg_f.startswith("bf16_fused")
         assert np.array_equal(got_f, got_p)
     _, _, _, cfg = run_fused_case(oracle, 512, 512, 256, alpha=0.5, act="gelu_tanh", clamp=(-1.0, 1.0), seed=5)
-    assert cfg == f"bf16_fused_256x256x{stage_k(False, False)}_w8_nn"
+    assert cfg == f"bf16_fused_128x128x{stage_k(False, False)}_w4_nn"
 
 
 def test_diagonal_times_dense(oracle):
