@@ -36,7 +36,8 @@ bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
     return true;
 }
 
-// K slices so that a launch with few output tiles still covers the chip.
+// K slices so that a launch with few output tiles still covers the chip (the guarded kernels; the
+// direct-to-LDS kernels choose tile and slices together, see plan_cost_us).
 int choose_split(long long tiles, int K, int minSlice)
 {
     const int kMinSlice = minSlice;            // K extent below which a slice is not worth its partial tile
@@ -56,41 +57,79 @@ void slice_k(int K, int bk, int want, int *splitK, int *kPerSlice)
     *splitK = ceil_div(K, per);
 }
 
+// Estimated time in microseconds of one structure -- block tile (256 or 128) and number of K slices --
+// from a few measured rates: a 256 x 256 block takes 0.80 us per 32-wide K step and about 8 us to fill
+// its pipeline and store its tile, one to a CU; a 128 x 128 block takes 0.30 us per step alone on a CU
+// and 0.54 us when two share it (about 5 and 6 us fixed); K slices add the second pass (a launch and
+// the partial tiles written and read at about 4 TB/s).  Per output element the large tile is the
+// cheaper one (0.20 against 0.27-0.30 us per 128 x 128 x 32 of work); the small one wins where the
+// large one would leave CUs idle or need many slices.  Calibrated on, and checked against, the timed
+// search over both choices (tune.py): the rule is for ranking structures, not for predicting times.
+double plan_cost_us(int M, int N, int K, int batch, int tile, int slices)
+{
+    const long long tiles = (long long)ceil_div(M, tile) * ceil_div(N, tile) * batch;
+    const long long blocks = tiles * slices;
+    const double steps = (double)ceil_div(ceil_div(K, slices), 32);
+    double t;
+    if (tile == 256) t = (double)((blocks + kNumCU - 1) / kNumCU) * (steps * 0.80 + 8.0);
+    else if (blocks <= kNumCU) t = steps * 0.30 + 5.0;
+    else t = (double)((blocks + 2 * kNumCU - 1) / (2 * kNumCU)) * (steps * 0.54 + 6.0);
+    if (slices > 1) t += 3.0 + (double)(slices + 1) * (double)batch * (double)M * (double)N * 4.0 / 4.0e6;
+    return t;
+}
+
+// The slice count of lowest estimated cost for a tile (1 = none); slices keep at least minSlice of K.
+int best_slices(int M, int N, int K, int batch, int tile, int minSlice, double *cost)
+{
+    int best = 1;
+    double bestCost = plan_cost_us(M, N, K, batch, tile, 1);
+    const int maxS = K / minSlice < 64 ? K / minSlice : 64;
+    for (int s2 = 2; s2 <= maxS; ++s2) {
+        const double c = plan_cost_us(M, N, K, batch, tile, s2);
+        if (c < bestCost) { bestCost = c; best = s2; }
+    }
+    if (cost) *cost = bestCost;
+    return best;
+}
+
 ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out)
 {
     Plan pl{};
+    if (plan != GE_PLAN_AUTO && plan != GE_PLAN_DIRECT && plan != GE_PLAN_SPLITK) return GE_ERR_CONFIG;
+    if (split_k < 0) return GE_ERR_CONFIG;
     const char *force = std::getenv("GE_FORCE_CONFIG");
+    int want = 1;
     if (!fast || (force && std::strcmp(force, "generic") == 0)) {
         pl.tile = TILE_GENERIC; pl.bm = 64; pl.bn = 64; pl.bk = 32;
+        const long long tiles = (long long)ceil_div(M, 64) * ceil_div(N, 64) * batch;
+        if (plan == GE_PLAN_SPLITK) want = split_k > 0 ? split_k : choose_split(tiles, K, 512);
+        else if (plan == GE_PLAN_AUTO) want = choose_split(tiles, K, 512);
+        if (plan == GE_PLAN_SPLITK && want < 2) want = 2;
     } else {
-        bool big = (M >= 256 && N >= 256);
-        // Few 256 x 256 tiles (half the CUs or fewer) and a K that is not long: four times as many
-        // 128 x 128 tiles, two to a CU, fill the machine with fewer or no K slices.  Found by the
-        // timed search over tile and slice count (tune.py): 2048^3 24.5 us against 38.8 us,
-        // 1024 x 1024 x 8192 28.6 against 36.6; with K = 65536 the 256 tiles' cheaper main loop
-        // wins again (144 against 191 us), hence the bound on K.
-        if (big && (long long)ceil_div(M, 256) * ceil_div(N, 256) * batch * 2 <= kNumCU && K <= 16384) big = false;
+        // both tiles are candidates when the problem has 256 rows and columns; each with the slice
+        // count the plan asks for (none, the caller's, or its own best), the cheaper structure wins
+        constexpr int kMinSlice = 512;
+        int tileOf[2] = {256, 128}, slicesOf[2] = {1, 1};
+        double costOf[2] = {0.0, 0.0};
+        for (int c = 0; c < 2; ++c) {
+            if (plan == GE_PLAN_DIRECT) slicesOf[c] = 1;
+            else if (plan == GE_PLAN_SPLITK && split_k > 0) slicesOf[c] = split_k < 2 ? 2 : split_k;
+            else {
+                slicesOf[c] = best_slices(M, N, K, batch, tileOf[c], kMinSlice, nullptr);
+                if (plan == GE_PLAN_SPLITK && slicesOf[c] < 2) slicesOf[c] = 2;
+            }
+            costOf[c] = plan_cost_us(M, N, K, batch, tileOf[c], slicesOf[c]);
+        }
+        bool big = (M >= 256 && N >= 256) && costOf[0] <= costOf[1];
         if (force && std::strcmp(force, "256x256") == 0) big = true;
         if (force && std::strcmp(force, "128x128") == 0) big = false;
-        if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = ge::BF16_BK; }
-        else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = ge::BF16_BK; }
+        if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = ge::BF16_BK; want = slicesOf[0]; }
+        else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = ge::BF16_BK; want = slicesOf[1]; }
     }
     pl.tilesM = ceil_div(M, pl.bm);
     pl.tilesN = ceil_div(N, pl.bn);
     const long long tiles = (long long)pl.tilesM * pl.tilesN * batch;
     if (tiles > 0x7fffffffll / 64) return GE_ERR_SHAPE;
-    int want = 1;
-    // slices of at least 512 k; 1024 for the 128 x 128 tiles (timed search)
-    const int minSlice = pl.tile == TILE_128 ? 1024 : 512;
-    if (plan == GE_PLAN_SPLITK) {
-        want = split_k > 0 ? split_k : choose_split(tiles, K, minSlice);
-        if (want < 2) want = 2;
-    } else if (plan == GE_PLAN_AUTO) {
-        want = choose_split(tiles, K, minSlice);
-    } else if (plan != GE_PLAN_DIRECT) {
-        return GE_ERR_CONFIG;
-    }
-    if (split_k < 0) return GE_ERR_CONFIG;
     slice_k(K, pl.bk, want, &pl.splitK, &pl.kPerSlice);
     if (pl.splitK == 1) pl.kPerSlice = ceil_div(K, pl.bk) * pl.bk;
     if (tiles * pl.splitK > 0x7fffffffll) return GE_ERR_SHAPE;
