@@ -159,3 +159,37 @@ def test_split_k_planning(lib):
     # gives 2 slices of 64 with the fast kernels and 4 of 32 with the guarded one; the
     # query does not know the pointers' alignment and reports the larger need
     assert binding.workspace_bytes(256, 256, 128, 1, "splitk", 5) == 4 * 256 * 256 * 4
+
+
+def test_public_headers_compile_as_plain_c(tmp_path):
+    """The boundary is a C ABI: both headers are valid C99 on their own (no C++ in them, every type declared
+    before use)."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "include/gemm_epilogue.h"\n#include "include/ge_probes.h"\n'
+                   "int main(void) { ge_fused_args_t a; ge_conv_args_t c; a.a_structure = GE_A_LOWER; c.N = 1;\n"
+                   "  return (int)(sizeof a + sizeof c) & 0; }\n")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", root, str(src)],
+                   check=True)
+
+
+def test_planner_properties_over_random_shapes(lib):
+    """The plan is a pure function of the shape: slice counts stay in range and keep at least 512 of K each,
+    the workspace request matches the slices, huge grids are refused; 300 seeded shapes, no device needed."""
+    import numpy as np
+    rng = np.random.default_rng(2024)
+    for _ in range(300):
+        M, N = int(rng.integers(1, 9000)), int(rng.integers(1, 9000))
+        K = int(2 ** rng.uniform(0, 17))
+        batch = int(rng.choice([1, 1, 1, 2, 7, 64]))
+        s = binding.auto_split_k(M, N, K, batch)
+        assert 1 <= s <= 64, (M, N, K, batch, s)
+        assert s == 1 or K // s >= 256, (M, N, K, batch, s)              # slices of 512 wanted, rounding may shave
+        assert s == binding.auto_split_k(M, N, K, batch)                 # no hidden state
+        need = binding.workspace_bytes(M, N, K, batch, "auto", 0)
+        assert need in (0, s * batch * M * N * 4) or need >= batch * M * N * 4 * 2, (M, N, K, batch, s, need)
+        assert binding.workspace_bytes(M, N, K, batch, "direct", 0) == 0
+    # many output tiles are never sliced, one tile with a long K always is
+    assert binding.auto_split_k(8192, 8192, 65536) == 1
+    assert binding.auto_split_k(128, 128, 65536) > 8
