@@ -118,27 +118,40 @@ conv_bf16_generic_kernel(const GemmParams p)
     const int kBegin = tc.s * p.kPerSlice;
     const int kEnd = min(p.K, kBegin + p.kPerSlice);
 
-    // the output position of the A row this thread fills (threads walk k fastest: row = e / BK)
+    // A thread fills the same k column (tid % 32) of 8 rows of the A tile, 8 rows apart, in every K
+    // step: the output positions of its rows are decoded once, here, and the filter tap of its k
+    // once per K step, so that an element costs two bounds tests and an address (the divisions by
+    // run-time extents were most of the kernel's time on first-layer shapes).
+    constexpr int ROWS = BM * BK / 256;
+    const int kLane = tid % BK, rowLane = tid / BK;
+    int ihBase[ROWS], iwBase[ROWS];
+    long long imgBase[ROWS];                      // first position of the row's image; -1: row past M
+#pragma unroll
+    for (int i = 0; i < ROWS; ++i) {
+        const int m = m0 + rowLane + i * (256 / BK);
+        const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
+        const int oh = pos / p.convOW, ow = pos % p.convOW;
+        ihBase[i] = oh * p.convSh - p.convPh;
+        iwBase[i] = ow * p.convSw - p.convPw;
+        imgBase[i] = m < p.M ? (long long)img * p.convH * p.convW : -1;
+    }
+
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 
     for (int k0 = kBegin; k0 < kEnd; k0 += BK) {
+        const int kkA = k0 + kLane;
+        const int tap = kkA / p.convCin, c = kkA - tap * p.convCin;
+        const int kh = tap / p.convKW, kw = tap - kh * p.convKW;
+        const int dIh = kh * p.convDh, dIw = kw * p.convDw;
 #pragma unroll
-        for (int i = 0; i < BM * BK / 256; ++i) {
-            const int e = tid + i * 256, row = e / BK, k = e % BK;
-            const int m = m0 + row, kk = k0 + k;
+        for (int i = 0; i < ROWS; ++i) {
+            const int ih = ihBase[i] + dIh, iw = iwBase[i] + dIw;
             uint16_t v = 0;
-            if (m < p.M && kk < kEnd) {
-                const int pos = m % (p.convOH * p.convOW), img = m / (p.convOH * p.convOW);
-                const int oh = pos / p.convOW, ow = pos % p.convOW;
-                const int tap = kk / p.convCin, c = kk % p.convCin;
-                const int ih = oh * p.convSh - p.convPh + (tap / p.convKW) * p.convDh;
-                const int iw = ow * p.convSw - p.convPw + (tap % p.convKW) * p.convDw;
-                if (ih >= 0 && ih < p.convH && iw >= 0 && iw < p.convW)
-                    v = X[(((long long)img * p.convH + ih) * p.convW + iw) * p.convCin + c];
-            }
-            sA[row * LD + k] = v;
+            if (imgBase[i] >= 0 && kkA < kEnd && ih >= 0 && ih < p.convH && iw >= 0 && iw < p.convW)
+                v = X[(imgBase[i] + (long long)ih * p.convW + iw) * p.convCin + c];
+            sA[(rowLane + i * (256 / BK)) * LD + kLane] = v;
         }
 #pragma unroll
         for (int i = 0; i < BK * BN / 256; ++i) {
