@@ -9,6 +9,7 @@
 
 #include "../../include/gemm_epilogue.h"
 #include "gemm_bf16_fast.h"
+#include "gemm_bf16_w4.h"
 #include "gemm_f32_fast.h"
 #include "gemm_generic.h"
 #include "ge_host.h"
@@ -219,6 +220,20 @@ ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void *
     return GE_OK;
 }
 
+hipError_t launch_four_wave(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
+{
+    if (raw) {
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<true, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+    } else if (act == GE_ACT_RELU) {
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_RELU, false, false, false, false>), grid, dim3(256), 0, st, p);
+    } else if (act == GE_ACT_GELU_TANH) {
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_GELU_TANH, false, false, false, false>), grid, dim3(256), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+    }
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN, bool EDGE>
 hipError_t launch_fast_sel(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
 {
@@ -246,6 +261,14 @@ hipError_t launch_reduce(const GemmParams &p, const float *W, float *C, int ldc,
                        W, p.sliceStride, p.splitK, p.M, p.N, p.batch, bias, alpha, act, C, ldc,
                        (long long)p.M * ldc);
     return hipGetLastError();
+}
+
+bool four_wave_ok(const Plan &pl, int K)
+{
+    const char *force = std::getenv("GE_WAVES");
+    if (force && std::strcmp(force, "8") == 0) return false;
+    const int range = pl.splitK > 1 ? pl.kPerSlice : K;
+    return pl.tile == TILE_256 && !pl.edge && K % 128 == 0 && (pl.splitK == 1 || pl.kPerSlice % 128 == 0) && range >= 256;
 }
 
 ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
@@ -281,6 +304,11 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     hipError_t err;
     switch (pl.tile) {
     case TILE_256:
+        if (four_wave_ok(pl, K)) {
+            err = launch_four_wave(p, raw, (int)act, grid, hs);
+            g_last_config = raw ? "bf16_256x256x64_w4_splitk" : "bf16_256x256x64_w4";
+            break;
+        }
         err = pl.edge ? launch_fast_sel<256, 256, 2, 4, true>(p, raw, (int)act, grid, hs)
                       : launch_fast_sel<256, 256, 2, 4, false>(p, raw, (int)act, grid, hs);
         g_last_config = raw ? "bf16_256x256x32_w8_splitk" : "bf16_256x256x32_w8";

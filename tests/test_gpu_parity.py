@@ -26,6 +26,7 @@ def test_bf16_fast_256(oracle, M, N, K, monkeypatch):
     _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K)
     assert cfg == "bf16_128x128x32_w4"
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    monkeypatch.setenv("GE_WAVES", "8")         # the four-wave kernel has its own tests
     _, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act="gelu_tanh", seed=M + N + K)
     assert cfg == "bf16_256x256x32_w8"
 

@@ -50,12 +50,12 @@ def test_c1_f32_256_full(oracle):
 
 def test_c2_bf16_4096(oracle):
     _, cfg, _ = _run_workload(oracle, "c2_bf16_4096", 320)
-    assert cfg == "bf16_256x256x32_w8"
+    assert cfg == "bf16_256x256x64_w4"
 
 
 def test_c3_bf16_8192_bias_gelu(oracle):
     _, cfg, _ = _run_workload(oracle, "c3_bf16_8192_bias_gelu", 320)
-    assert cfg == "bf16_256x256x32_w8"
+    assert cfg == "bf16_256x256x64_w4"
 
 
 def test_c4_bf16_batched(oracle):
@@ -110,7 +110,7 @@ def _run_fused_workload(oracle, name, rows_wanted, batches_wanted=4):
 
 def test_c6_fused_nt_bf16out(oracle):
     _, cfg = _run_fused_workload(oracle, "c6_fused_nt_8192_bias_gelu_bf16out", 96)
-    assert cfg == "bf16_fused_256x256x64_w8_nt"
+    assert cfg == "bf16_fused_256x256x64_w4_nt"
 
 
 def test_c7_fused_tn_chain(oracle):
@@ -180,7 +180,7 @@ def test_c11_fused_lower_triangular(oracle):
     """8192^3 with a lower-triangular A and the caller's promise: sampled rows (first and last tile
     rows included: the shortest and the longest K range) against the oracle, which is told nothing."""
     _, cfg = _run_fused_workload(oracle, "c11_fused_lower_8192_bias_relu", 96)
-    assert cfg == "bf16_fused_256x256x32_w8_nn"
+    assert cfg == "bf16_fused_256x256x64_w4_nn"
 
 
 def test_c12_rowsum_linear_full(oracle):
