@@ -68,3 +68,26 @@ def test_convolution_sweep(oracle, chunk):
                       residual=_pick(rng, [None, "f32", "bf16"]), beta=float(_pick(rng, [1.0, -0.5])),
                       act=_pick(rng, ["none", "relu", "gelu_tanh"]), clamp=_pick(rng, [None, (0.0, 1.5), (-0.5, 0.5)]),
                       out=_pick(rng, ["f32", "bf16"]), seed=6000 + 100 * chunk + i)
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_four_wave_sweep(oracle, chunk, monkeypatch):
+    """Full 256 x 256 tiles over K ranges in multiples of 128, the tile forced: the shapes the four-wave kernel
+    takes, with every storage, consumer chain, output type, padding, batch and K slicing drawn at random."""
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    rng = np.random.default_rng(7000 + chunk)
+    seen = set()
+    for i in range(8):
+        M, N = 256 * int(_pick(rng, [1, 1, 2, 3])), 256 * int(_pick(rng, [1, 2, 3]))
+        K = 128 * int(_pick(rng, [2, 3, 4, 5, 8, 9]))
+        splitk = K >= 1024 and rng.random() < 0.5         # 1024 or 1152 in 2 slices: 512 (four waves) or 576 (eight)
+        pad = tuple(int(8 * rng.integers(0, 3)) for _ in range(4))
+        _, _, _, cfg = run_fused_case(
+            oracle, M, N, K, batch=int(_pick(rng, [1, 1, 2])), transA=bool(rng.integers(2)), transB=bool(rng.integers(2)),
+            alpha=float(_pick(rng, [1.0, 0.5, -0.75])), with_row_scale=bool(rng.integers(2)),
+            with_bias=bool(rng.integers(2)), residual=_pick(rng, [None, "f32", "bf16"]),
+            beta=float(_pick(rng, [1.0, -0.5])), act=_pick(rng, ["none", "relu", "gelu_tanh"]),
+            clamp=_pick(rng, [None, None, (-0.25, 0.5), (0.0, 6.0)]), out=_pick(rng, ["f32", "bf16"]), pad=pad,
+            seed=8000 + 100 * chunk + i, plan="splitk" if splitk else "direct", split_k=2 if splitk else 0)
+        seen.add("w4" if "_w4" in cfg else "w8")
+    assert "w4" in seen, seen
