@@ -21,8 +21,9 @@
 //     MFMAs (measured: the same loads issued back to back at the head of the step cost 9 %);
 //   * the accumulators (256 registers per lane) live in the accumulation registers, which the
 //     compiler does not do by itself for this many: the MFMAs are written as inline assembly.
-// The tile must be full (no edge handling) and every block's K range a multiple of 128 (the
-// loop body is four steps of 32).
+// Every block's K range must be a multiple of 128 (the loop body is four steps of 32).  EDGE: tiles
+// may hang over M or N; the rows and column chunks beyond are never fetched (their lanes carry the
+// out-of-range offset from the start, which costs the loop nothing) and never stored.
 #pragma once
 #include "gemm_bf16_fast.h"
 
@@ -35,8 +36,8 @@ struct W4Tile {
     static constexpr int LDS_BYTES = 2 * OPERAND_BYTES;     // 128 KB
 };
 
-// RAW / ACT / FUSED / OUTBF16 / TA / TB as in gemm_bf16_kernel.
-template <bool RAW, int ACT, bool TA, bool TB, bool FUSED, bool OUTBF16>
+// EDGE as above; RAW / ACT / FUSED / OUTBF16 / TA / TB as in gemm_bf16_kernel.
+template <bool EDGE, bool RAW, int ACT, bool TA, bool TB, bool FUSED, bool OUTBF16>
 __global__ void __launch_bounds__(256)
 gemm_bf16_w4_kernel(const GemmParams p)
 {
@@ -78,9 +79,11 @@ gemm_bf16_w4_kernel(const GemmParams p)
         if (APAIR) {
             const int row = a64_slot_row(j * NW + w, lane), c = a64_slot_chunk(j * NW + w, lane);
             voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
+            if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
         } else {
             const int k = b_slot_k<BM>(j * NW + w, lane), c = b_slot_chunk<BM>(j * NW + w, lane);
             voffA[j] = (unsigned)k * (unsigned)p.lda * 2u + (unsigned)c * 16u;
+            if (EDGE && m0 + c * 8 >= p.M) voffA[j] = OOB_OFFSET;
         }
     }
 #pragma unroll
@@ -88,9 +91,11 @@ gemm_bf16_w4_kernel(const GemmParams p)
         if (BPAIR) {
             const int row = a64_slot_row(j * NW + w, lane), c = a64_slot_chunk(j * NW + w, lane);
             voffB[j] = (unsigned)row * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
+            if (EDGE && n0 + row >= p.N) voffB[j] = OOB_OFFSET;
         } else {
             const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
             voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
+            if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
         }
     }
 
@@ -254,17 +259,19 @@ gemm_bf16_w4_kernel(const GemmParams p)
 #undef GE_W4_READ_STRIDED
 
     // ---- epilogue in registers ----------------------------------------------------
-    const int rowLane = m0 + wm * T::WTM + 4 * (lane >> 4);
-    const int colLane = n0 + wn * T::WTN + (lane & 15);
+    // the lane index as a value born here: nothing of the epilogue's address arithmetic or edge
+    // tests can be hoisted above the main loop, where it would only be carried along
+    int laneE = lane, waveE = (int)(threadIdx.x >> 6);
+    asm volatile("" : "+v"(laneE), "+v"(waveE));
+    const int rowLane = m0 + (waveE / 2) * T::WTM + 4 * (laneE >> 4);
+    const int colLane = n0 + (waveE % 2) * T::WTN + (laneE & 15);
     if constexpr (FUSED) {
         if constexpr (OUTBF16) {
-            int laneE = lane, waveE = (int)(threadIdx.x >> 6);
-            asm volatile("" : "+v"(laneE), "+v"(waveE));
-            fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, false>(
+            fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, EDGE>(
                 p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / 2) * T::WTM + (laneE & 15),
                 (waveE % 2) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
         } else {
-            fused_epilogue_f32_direct<TM, TN, false>(p, tc.b, acc, rowLane, colLane);
+            fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
         }
     } else {
         float *cBase;
@@ -278,17 +285,19 @@ gemm_bf16_w4_kernel(const GemmParams p)
         }
         float bv[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bv[j] = (!RAW && p.bias != nullptr) ? p.bias[colLane + j * 16] : 0.0f;
+        for (int j = 0; j < TN; ++j)
+            bv[j] = (!RAW && p.bias != nullptr && (!EDGE || colLane + j * 16 < p.N)) ? p.bias[colLane + j * 16] : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                float *rowPtr = cBase + (long long)(rowLane + i * 16 + r) * ldc + colLane;
+                const int m = rowLane + i * 16 + r;
+                float *rowPtr = cBase + (long long)m * ldc + colLane;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     float v = acc[i][j][r];
                     if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
-                    rowPtr[j * 16] = v;
+                    if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
                 }
             }
     }

@@ -220,16 +220,17 @@ ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void *
     return GE_OK;
 }
 
+template <bool EDGE>
 hipError_t launch_four_wave(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
 {
     if (raw) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<true, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, true, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else if (act == GE_ACT_RELU) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_RELU, false, false, false, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_RELU, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else if (act == GE_ACT_GELU_TANH) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_GELU_TANH, false, false, false, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_GELU_TANH, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<false, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
     }
     return hipGetLastError();
 }
@@ -268,7 +269,7 @@ bool four_wave_ok(const Plan &pl, int K)
     const char *force = std::getenv("GE_WAVES");
     if (force && std::strcmp(force, "8") == 0) return false;
     const int range = pl.splitK > 1 ? pl.kPerSlice : K;
-    return pl.tile == TILE_256 && !pl.edge && K % 128 == 0 && (pl.splitK == 1 || pl.kPerSlice % 128 == 0) && range >= 256;
+    return pl.tile == TILE_256 && K % 128 == 0 && (pl.splitK == 1 || pl.kPerSlice % 128 == 0) && range >= 256;
 }
 
 ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
@@ -305,7 +306,7 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     switch (pl.tile) {
     case TILE_256:
         if (four_wave_ok(pl, K)) {
-            err = launch_four_wave(p, raw, (int)act, grid, hs);
+            err = pl.edge ? launch_four_wave<true>(p, raw, (int)act, grid, hs) : launch_four_wave<false>(p, raw, (int)act, grid, hs);
             g_last_config = raw ? "bf16_256x256x64_w4_splitk" : "bf16_256x256x64_w4";
             break;
         }

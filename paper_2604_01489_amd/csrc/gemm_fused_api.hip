@@ -122,24 +122,25 @@ bool launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_
     return k64;
 }
 
-// the four-wave kernel, by output mode and operand storage
-template <int MODE>
+// the four-wave kernel, by edge handling, output mode and operand storage
+template <bool EDGE, int MODE>
 void launch_four_wave_layout(const GemmParams &p, dim3 grid, hipStream_t st)
 {
     constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
     if (p.transA) {         // with B along k; the caller keeps the other storage of B on the eight-wave kernel
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<R, ge::ACT_NONE, true, true, F, H>), grid, dim3(256), 0, st, p);
+        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(256), 0, st, p);
     } else {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<R, ge::ACT_NONE, false, true, F, H>), grid, dim3(256), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<R, ge::ACT_NONE, false, false, F, H>), grid, dim3(256), 0, st, p);
+        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(256), 0, st, p);
+        else          hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(256), 0, st, p);
     }
 }
 
+template <bool EDGE>
 void launch_four_wave(const GemmParams &p, bool raw, dim3 grid, hipStream_t st)
 {
-    if (raw) launch_four_wave_layout<0>(p, grid, st);
-    else if (p.cType == ge::DT_BF16) launch_four_wave_layout<2>(p, grid, st);
-    else launch_four_wave_layout<1>(p, grid, st);
+    if (raw) launch_four_wave_layout<EDGE, 0>(p, grid, st);
+    else if (p.cType == ge::DT_BF16) launch_four_wave_layout<EDGE, 2>(p, grid, st);
+    else launch_four_wave_layout<EDGE, 1>(p, grid, st);
 }
 
 }  // namespace
@@ -213,7 +214,8 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
         // both operands k-strided: every request is a whole line already and the four-wave
         // kernel has nothing to gain (measured at 8192^3: 0.812 against 0.806 ms)
         if (four_wave_ok(pl, a.K) && !(a.transA && !a.transB)) {
-            launch_four_wave(pg, raw, grid, hs);
+            if (pl.edge) launch_four_wave<true>(pg, raw, grid, hs);
+            else launch_four_wave<false>(pg, raw, grid, hs);
             set_config("256x256x64_w4", a.transA, a.transB, raw);
         } else if (launch_tile<256, 256, 2, 4>(pg, pl.edge, raw, grid, hs)) set_config("256x256x64_w8", a.transA, a.transB, raw);
         else set_config("256x256x32_w8", a.transA, a.transB, raw);

@@ -1,4 +1,4 @@
-"""GPU parity of the four-wave 256 x 256 kernel (full tiles, K ranges that are multiples of 128)
+"""GPU parity of the four-wave 256 x 256 kernel (full or ragged tiles, K ranges that are multiples of 128)
 against the CPU oracles, through the C-ABI: the plain operator with each activation, the widened
 operator in all four operand storages with fp32 and bf16 output, residual and row scale, padded
 leading dimensions, batches, K slices and a triangular A.  The 256 x 256 tile is forced, since at
@@ -44,12 +44,37 @@ def test_plain_padded_batched_no_bias(oracle, monkeypatch):
     assert cfg == "bf16_256x256x64_w4"
 
 
-def test_not_taken_when_the_shape_does_not_fit(oracle, monkeypatch):
-    """Ragged tiles, a K that is not a multiple of 128 or a short K stay on the eight-wave kernel."""
+def test_not_taken_when_k_does_not_fit(oracle, monkeypatch):
+    """A K that is not a multiple of 128 or a short K stays on the eight-wave kernel."""
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
-    for M, N, K in [(520, 256, 256), (256, 264, 256), (256, 256, 320), (256, 256, 128)]:
+    for M, N, K in [(256, 256, 320), (256, 256, 128), (520, 264, 328)]:
         _, _, _, cfg = run_case(oracle, "bf16", M, N, K, act="relu", seed=M + K, plan="direct")
         assert cfg == "bf16_256x256x32_w8", (M, N, K, cfg)
+
+
+@pytest.mark.parametrize("M,N", [(520, 256), (256, 264), (328, 776), (8, 8), (249, 505)])
+def test_plain_operator_ragged_tiles(oracle, M, N, monkeypatch):
+    """Tiles hanging over M, N or both (rows and column chunks beyond are never fetched, never stored):
+    padded leading dimensions hold garbage and a canary that must survive."""
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    M8, N8 = (M + 7) // 8 * 8, (N + 7) // 8 * 8         # the direct-to-LDS kernels want N a multiple of 8; M is free
+    for act, K in [("gelu_tanh", 256), ("relu", 640)]:
+        _, _, _, cfg = run_case(oracle, "bf16", M, N8, K, alpha=0.5, act=act, seed=M + N + K, lda=K + 8, ldb=N8 + 16,
+                                ldc=N8 + 4, plan="direct")
+        assert cfg == "bf16_256x256x64_w4", (M, N8, K, cfg)
+    _, _, _, cfg = run_case(oracle, "bf16", M, N8, 1024, alpha=0.25, seed=M + N, plan="splitk", split_k=2)
+    assert cfg == "bf16_256x256x64_w4_splitk"
+
+
+@pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, True)])
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+def test_widened_operator_ragged_tiles(oracle, transA, transB, out, monkeypatch):
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    for M, N, K, pad in [(520, 264, 256, (8, 8, 8, 8)), (200, 776, 384, (0, 16, 0, 8)), (264, 8, 256, (0, 0, 0, 0))]:
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, with_row_scale=True,
+                                      residual="bf16" if out == "f32" else "f32", beta=-0.5, act="relu", clamp=(0.0, 2.0),
+                                      out=out, pad=pad, plan="direct", seed=M + N + K + 2 * transA + transB)
+        assert cfg == f"bf16_fused_256x256x64_w4_{NAME[transA, transB]}", (M, N, K, cfg)
 
 
 def test_split_k(oracle, monkeypatch):
