@@ -322,7 +322,7 @@ ge_status_t ge_release_workspace(void);
 const char *ge_status_string(ge_status_t status);
 
 /* Name of the kernel configuration the last successful call on this thread
- * launched ("bf16_256x256x32_w8", "f32_128x128x16", ...); for reports. */
+ * launched ("bf16_256x256x64_w4", "bf16_256x256x32_w8", "f32_128x128x16", ...); for reports. */
 const char *ge_last_config(void);
 
 #ifdef __cplusplus
