@@ -33,9 +33,11 @@ int choose_split(long long tiles, int K, int minSlice);
 ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out);
 size_t partial_bytes(int M, int N, int batch, int splitK);
 int choose_group_m(int tilesM, int tilesN);
-// The four-wave kernel (gemm_bf16_w4.h) takes launches of 256 x 256 tiles (full, or hanging over M or N) whose blocks all
-// walk a K range that is a multiple of 128 and long enough for its deeper pipeline to pay.
-// GE_WAVES=8 in the environment keeps the eight-wave kernel, for timing and for its tests.
+// The four-wave kernel (gemm_bf16_w4.h) takes launches of 256 x 256 tiles whose blocks walk a K range
+// long enough for its deeper pipeline to pay; four_wave_edge names the variant: 0 full tiles, 1 tiles
+// hanging over M or N, 2 also K ranges that are not multiples of 128.  GE_WAVES=8 in the environment keeps the eight-wave
+// kernel, for timing and for its tests.
+int four_wave_edge(const Plan &pl, int K);
 bool four_wave_ok(const Plan &pl, int K);
 ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void **out);
 

@@ -29,6 +29,8 @@
 //     few instructions (measured faster than 16-byte-per-lane stores whose
 //     neighbouring lanes sit in different rows).
 #pragma once
+#include <type_traits>
+
 #include "bf16_layout.h"
 #include "ge_device.h"
 
@@ -553,7 +555,9 @@ gemm_bf16_kernel(const GemmParams p)
                 p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / WN) * T::WTM + (laneE & 15),
                 (waveE % WN) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
         } else {
-            fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
+            // only the tiles that hang over M or N pay for masked stores (a uniform branch)
+            if (!EDGE || (m0 + BM <= p.M && n0 + BN <= p.N)) fused_epilogue_f32_direct<TM, TN, false>(p, tc.b, acc, rowLane, colLane);
+            else fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
         }
     } else {
         float *cBase;
@@ -565,25 +569,31 @@ gemm_bf16_kernel(const GemmParams p)
             ldc = p.ldc;
             cBase = p.C + (long long)tc.b * p.strideC;
         }
-        float bv[TN];
+        auto store_tile = [&](auto masked) {
+            constexpr bool MASK = decltype(masked)::value;
+            float bv[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = colLane + j * 16;
-            bv[j] = (!RAW && p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = rowLane + i * 16 + r;
-                float *rowPtr = cBase + (long long)m * ldc + colLane;
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    float v = acc[i][j][r];
-                    if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
-                    if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
-                }
+            for (int j = 0; j < TN; ++j) {
+                const int n = colLane + j * 16;
+                bv[j] = (!RAW && p.bias != nullptr && (!MASK || n < p.N)) ? p.bias[n] : 0.0f;
             }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = rowLane + i * 16 + r;
+                    float *rowPtr = cBase + (long long)m * ldc + colLane;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        float v = acc[i][j][r];
+                        if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
+                        if (!MASK || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
+                    }
+                }
+        };
+        // only the tiles that hang over M or N pay for masked stores (a uniform branch)
+        if (!EDGE || (m0 + BM <= p.M && n0 + BN <= p.N)) store_tile(std::false_type{});
+        else store_tile(std::true_type{});
     }
 }
 

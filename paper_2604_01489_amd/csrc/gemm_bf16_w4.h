@@ -21,10 +21,15 @@
 //     MFMAs (measured: the same loads issued back to back at the head of the step cost 9 %);
 //   * the accumulators (256 registers per lane) live in the accumulation registers, which the
 //     compiler does not do by itself for this many: the MFMAs are written as inline assembly.
-// Every block's K range must be a multiple of 128 (the loop body is four steps of 32).  EDGE: tiles
-// may hang over M or N; the rows and column chunks beyond are never fetched (their lanes carry the
-// out-of-range offset from the start, which costs the loop nothing) and never stored.
+// Plain variant: full tiles, every block's K range a multiple of 128 (the loop body is four steps of
+// 32).  EDGE: tiles may hang over M or N -- the rows and column chunks beyond are never fetched (their
+// lanes carry the out-of-range offset from the start, which costs the loop nothing) and never
+// stored.  EDGEK: the K range may be any multiple of 8 -- chunks at or beyond its end are masked load
+// by load (two vector instructions each), steps beyond it load nothing, which leaves zeros in their
+// stages, and the loop runs on to the next multiple of four steps over those zeros.
 #pragma once
+#include <type_traits>
+
 #include "gemm_bf16_fast.h"
 
 namespace ge {
@@ -36,12 +41,16 @@ struct W4Tile {
     static constexpr int LDS_BYTES = 2 * OPERAND_BYTES;     // 128 KB
 };
 
-// EDGE as above; RAW / ACT / FUSED / OUTBF16 / TA / TB as in gemm_bf16_kernel.
-template <bool EDGE, bool RAW, int ACT, bool TA, bool TB, bool FUSED, bool OUTBF16>
+// EDGEMODE: 0 none, 1 tiles may hang over M or N (EDGE above), 2 also any K range (EDGEK above; the
+// masks of the K edge are vector instructions among the MFMAs of the one wave a SIMD has, about 10 %
+// of the run at 8192^3, so shapes that only need the first do not pay for the second).
+// RAW / ACT / FUSED / OUTBF16 / TA / TB as in gemm_bf16_kernel.
+template <int EDGEMODE, bool RAW, int ACT, bool TA, bool TB, bool FUSED, bool OUTBF16>
 __global__ void __launch_bounds__(256)
 gemm_bf16_w4_kernel(const GemmParams p)
 {
     using T = W4Tile;
+    constexpr bool EDGE = EDGEMODE >= 1, EDGEK = EDGEMODE == 2;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NW = T::NW, TM = T::TM, TN = T::TN;
     constexpr bool APAIR = !TA, BPAIR = TB;                 // operand staged 64 k at a time
     constexpr int NLA = APAIR ? 8 : 4, NLB = BPAIR ? 8 : 4; // loads per wave and stage
@@ -63,7 +72,8 @@ gemm_bf16_w4_kernel(const GemmParams p)
     int kBegin = tc.s * p.kPerSlice;
     int kEnd = min(p.K, kBegin + p.kPerSlice);
     if constexpr (FUSED) triangular_k_range(p, m0, BM, kBegin, kEnd);
-    const int nk = (kEnd - kBegin) / BK;                    // a multiple of 4 (the host checks)
+    const int kLen = kEnd - kBegin;
+    const int nk = (kLen + BK - 1) / BK;                    // a multiple of 4 unless EDGEK (the host checks)
 
     const long long offA = 2 * ((long long)tc.b * p.strideA +
                                 (TA ? (long long)kBegin * p.lda + m0 : (long long)m0 * p.lda + kBegin));
@@ -74,16 +84,19 @@ gemm_bf16_w4_kernel(const GemmParams p)
 
     // per-lane offsets of the 16-byte chunks this lane fetches (inverse of the LDS layouts)
     unsigned voffA[NLA], voffB[NLB];
+    int kA[EDGEK ? NLA : 1], kB[EDGEK ? NLB : 1];   // first k of the chunk within its stage, for the K-edge mask
 #pragma unroll
     for (int j = 0; j < NLA; ++j) {
         if (APAIR) {
             const int row = a64_slot_row(j * NW + w, lane), c = a64_slot_chunk(j * NW + w, lane);
             voffA[j] = (unsigned)row * (unsigned)p.lda * 2u + (unsigned)c * 16u;
             if (EDGE && m0 + row >= p.M) voffA[j] = OOB_OFFSET;
+            if (EDGEK) kA[j] = c * 8;
         } else {
             const int k = b_slot_k<BM>(j * NW + w, lane), c = b_slot_chunk<BM>(j * NW + w, lane);
             voffA[j] = (unsigned)k * (unsigned)p.lda * 2u + (unsigned)c * 16u;
             if (EDGE && m0 + c * 8 >= p.M) voffA[j] = OOB_OFFSET;
+            if (EDGEK) kA[j] = k;
         }
     }
 #pragma unroll
@@ -92,10 +105,12 @@ gemm_bf16_w4_kernel(const GemmParams p)
             const int row = a64_slot_row(j * NW + w, lane), c = a64_slot_chunk(j * NW + w, lane);
             voffB[j] = (unsigned)row * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
             if (EDGE && n0 + row >= p.N) voffB[j] = OOB_OFFSET;
+            if (EDGEK) kB[j] = c * 8;
         } else {
             const int k = b_slot_k<BN>(j * NW + w, lane), c = b_slot_chunk<BN>(j * NW + w, lane);
             voffB[j] = (unsigned)k * (unsigned)p.ldb * 2u + (unsigned)c * 16u;
             if (EDGE && n0 + c * 8 >= p.N) voffB[j] = OOB_OFFSET;
+            if (EDGEK) kB[j] = k;
         }
     }
 
@@ -104,29 +119,42 @@ gemm_bf16_w4_kernel(const GemmParams p)
     // Resource words of the tile being loaded: the pair of steps kt, kt+1 (kt even) for a pair
     // stage, step kt for a ring stage; zero length past the K range (nothing is read).
     rsrc_words_t rA, rB;
+    int kLeftPair = 0, kLeftRing = 0;               // valid k from the first k of the stage being loaded (EDGEK only)
     auto set_rsrc_pair = [&](int kt) {
         const unsigned rec = kt < nk ? RSRC_RECORDS : 0u;
+        kLeftPair = kLen - kt * BK;
         if (APAIR) rA = make_rsrc(gA + (long long)kt * (BK * 2), rec);
         if (BPAIR) rB = make_rsrc(gB + (long long)kt * (BK * 2), rec);
     };
     auto set_rsrc_ring = [&](int kt) {
         const unsigned rec = kt < nk ? RSRC_RECORDS : 0u;
+        kLeftRing = kLen - kt * BK;
         if (!APAIR) rA = make_rsrc(gA + (long long)kt * BK * p.lda * 2, rec);
         if (!BPAIR) rB = make_rsrc(gB + (long long)kt * BK * p.ldb * 2, rec);
     };
     // load d of the pair loads (A's first) into pair stage pst; load d of the ring loads into ring stage st
     auto dma_pair = [&](int d, int pst) {
-        if (APAIR && d < 8) lds_dma16(rA, ldsA + (unsigned)(pst * 2 * T::STAGE_BYTES + (d * NW + w) * 1024), voffA[d & (NLA - 1)]);
-        else {
+        if (APAIR && d < 8) {
+            unsigned v = voffA[d & (NLA - 1)];
+            if (EDGEK && kA[EDGEK ? (d & (NLA - 1)) : 0] >= kLeftPair) v = OOB_OFFSET;
+            lds_dma16(rA, ldsA + (unsigned)(pst * 2 * T::STAGE_BYTES + (d * NW + w) * 1024), v);
+        } else {
             const int l = APAIR ? d - 8 : d;
-            lds_dma16(rB, ldsB + (unsigned)(pst * 2 * T::STAGE_BYTES + (l * NW + w) * 1024), voffB[l & (NLB - 1)]);
+            unsigned v = voffB[l & (NLB - 1)];
+            if (EDGEK && kB[EDGEK ? (l & (NLB - 1)) : 0] >= kLeftPair) v = OOB_OFFSET;
+            lds_dma16(rB, ldsB + (unsigned)(pst * 2 * T::STAGE_BYTES + (l * NW + w) * 1024), v);
         }
     };
     auto dma_ring = [&](int d, int st) {
-        if (!APAIR && d < 4) lds_dma16(rA, ldsA + (unsigned)(st * T::STAGE_BYTES + (d * NW + w) * 1024), voffA[d & (NLA - 1)]);
-        else {
+        if (!APAIR && d < 4) {
+            unsigned v = voffA[d & (NLA - 1)];
+            if (EDGEK && kA[EDGEK ? (d & (NLA - 1)) : 0] >= kLeftRing) v = OOB_OFFSET;
+            lds_dma16(rA, ldsA + (unsigned)(st * T::STAGE_BYTES + (d * NW + w) * 1024), v);
+        } else {
             const int l = !APAIR ? d - 4 : d;
-            lds_dma16(rB, ldsB + (unsigned)(st * T::STAGE_BYTES + (l * NW + w) * 1024), voffB[l & (NLB - 1)]);
+            unsigned v = voffB[l & (NLB - 1)];
+            if (EDGEK && kB[EDGEK ? (l & (NLB - 1)) : 0] >= kLeftRing) v = OOB_OFFSET;
+            lds_dma16(rB, ldsB + (unsigned)(st * T::STAGE_BYTES + (l * NW + w) * 1024), v);
         }
     };
 
@@ -271,7 +299,10 @@ gemm_bf16_w4_kernel(const GemmParams p)
                 p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / 2) * T::WTM + (laneE & 15),
                 (waveE % 2) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
         } else {
-            fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
+            // only the tiles that hang over M or N pay for masked stores (a uniform branch; masked, the
+            // stores of an 8192^3-sized launch cost 10 % of its run)
+            if (!EDGE || (m0 + BM <= p.M && n0 + BN <= p.N)) fused_epilogue_f32_direct<TM, TN, false>(p, tc.b, acc, rowLane, colLane);
+            else fused_epilogue_f32_direct<TM, TN, EDGE>(p, tc.b, acc, rowLane, colLane);
         }
     } else {
         float *cBase;
@@ -283,23 +314,28 @@ gemm_bf16_w4_kernel(const GemmParams p)
             ldc = p.ldc;
             cBase = p.C + (long long)tc.b * p.strideC;
         }
-        float bv[TN];
+        auto store_tile = [&](auto masked) {
+            constexpr bool MASK = decltype(masked)::value;
+            float bv[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            bv[j] = (!RAW && p.bias != nullptr && (!EDGE || colLane + j * 16 < p.N)) ? p.bias[colLane + j * 16] : 0.0f;
+            for (int j = 0; j < TN; ++j)
+                bv[j] = (!RAW && p.bias != nullptr && (!MASK || colLane + j * 16 < p.N)) ? p.bias[colLane + j * 16] : 0.0f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int m = rowLane + i * 16 + r;
-                float *rowPtr = cBase + (long long)m * ldc + colLane;
+                for (int r = 0; r < 4; ++r) {
+                    const int m = rowLane + i * 16 + r;
+                    float *rowPtr = cBase + (long long)m * ldc + colLane;
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    float v = acc[i][j][r];
-                    if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
-                    if (!EDGE || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
+                    for (int j = 0; j < TN; ++j) {
+                        float v = acc[i][j][r];
+                        if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
+                        if (!MASK || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
+                    }
                 }
-            }
+        };
+        if (!EDGE || (m0 + BM <= p.M && n0 + BN <= p.N)) store_tile(std::false_type{});
+        else store_tile(std::true_type{});
     }
 }
 

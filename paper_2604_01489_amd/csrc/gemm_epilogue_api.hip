@@ -220,7 +220,7 @@ ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void *
     return GE_OK;
 }
 
-template <bool EDGE>
+template <int EDGE>
 hipError_t launch_four_wave(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
 {
     if (raw) {
@@ -269,7 +269,13 @@ bool four_wave_ok(const Plan &pl, int K)
     const char *force = std::getenv("GE_WAVES");
     if (force && std::strcmp(force, "8") == 0) return false;
     const int range = pl.splitK > 1 ? pl.kPerSlice : K;
-    return pl.tile == TILE_256 && K % 128 == 0 && (pl.splitK == 1 || pl.kPerSlice % 128 == 0) && range >= 256;
+    return pl.tile == TILE_256 && range >= 256;
+}
+
+int four_wave_edge(const Plan &pl, int K)
+{
+    if (K % 128 != 0 || (pl.splitK > 1 && pl.kPerSlice % 128 != 0)) return 2;
+    return pl.edge ? 1 : 0;
 }
 
 ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
@@ -306,7 +312,9 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     switch (pl.tile) {
     case TILE_256:
         if (four_wave_ok(pl, K)) {
-            err = pl.edge ? launch_four_wave<true>(p, raw, (int)act, grid, hs) : launch_four_wave<false>(p, raw, (int)act, grid, hs);
+            const int mode = four_wave_edge(pl, K);
+            err = mode == 2 ? launch_four_wave<2>(p, raw, (int)act, grid, hs)
+                : mode == 1 ? launch_four_wave<1>(p, raw, (int)act, grid, hs) : launch_four_wave<0>(p, raw, (int)act, grid, hs);
             g_last_config = raw ? "bf16_256x256x64_w4_splitk" : "bf16_256x256x64_w4";
             break;
         }

@@ -123,7 +123,7 @@ bool launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_
 }
 
 // the four-wave kernel, by edge handling, output mode and operand storage
-template <bool EDGE, int MODE>
+template <int EDGE, int MODE>
 void launch_four_wave_layout(const GemmParams &p, dim3 grid, hipStream_t st)
 {
     constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
@@ -135,7 +135,7 @@ void launch_four_wave_layout(const GemmParams &p, dim3 grid, hipStream_t st)
     }
 }
 
-template <bool EDGE>
+template <int EDGE>
 void launch_four_wave(const GemmParams &p, bool raw, dim3 grid, hipStream_t st)
 {
     if (raw) launch_four_wave_layout<EDGE, 0>(p, grid, st);
@@ -214,8 +214,10 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
         // both operands k-strided: every request is a whole line already and the four-wave
         // kernel has nothing to gain (measured at 8192^3: 0.812 against 0.806 ms)
         if (four_wave_ok(pl, a.K) && !(a.transA && !a.transB)) {
-            if (pl.edge) launch_four_wave<true>(pg, raw, grid, hs);
-            else launch_four_wave<false>(pg, raw, grid, hs);
+            const int mode = four_wave_edge(pl, a.K);
+            if (mode == 2) launch_four_wave<2>(pg, raw, grid, hs);
+            else if (mode == 1) launch_four_wave<1>(pg, raw, grid, hs);
+            else launch_four_wave<0>(pg, raw, grid, hs);
             set_config("256x256x64_w4", a.transA, a.transB, raw);
         } else if (launch_tile<256, 256, 2, 4>(pg, pl.edge, raw, grid, hs)) set_config("256x256x64_w8", a.transA, a.transB, raw);
         else set_config("256x256x32_w8", a.transA, a.transB, raw);

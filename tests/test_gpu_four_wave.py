@@ -1,4 +1,4 @@
-"""GPU parity of the four-wave 256 x 256 kernel (full or ragged tiles, K ranges that are multiples of 128)
+"""GPU parity of the four-wave 256 x 256 kernel (full or ragged tiles, K ranges of 256 or more)
 against the CPU oracles, through the C-ABI: the plain operator with each activation, the widened
 operator in all four operand storages with fp32 and bf16 output, residual and row scale, padded
 leading dimensions, batches, K slices and a triangular A.  The 256 x 256 tile is forced, since at
@@ -44,12 +44,29 @@ def test_plain_padded_batched_no_bias(oracle, monkeypatch):
     assert cfg == "bf16_256x256x64_w4"
 
 
-def test_not_taken_when_k_does_not_fit(oracle, monkeypatch):
-    """A K that is not a multiple of 128 or a short K stays on the eight-wave kernel."""
+def test_not_taken_when_k_is_short(oracle, monkeypatch):
+    """K ranges below 256 stay on the eight-wave kernel (one load phase, or a ring that barely turns)."""
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
-    for M, N, K in [(256, 256, 320), (256, 256, 128), (520, 264, 328)]:
+    for M, N, K in [(256, 256, 128), (520, 264, 248), (256, 256, 64)]:
         _, _, _, cfg = run_case(oracle, "bf16", M, N, K, act="relu", seed=M + K, plan="direct")
         assert cfg == "bf16_256x256x32_w8", (M, N, K, cfg)
+
+
+@pytest.mark.parametrize("K", [264, 320, 328, 392, 1000])
+def test_ragged_k(oracle, K, monkeypatch):
+    """K ranges that are not multiples of 128, of 64, of 32: the chunks beyond the end are masked, the loop
+    runs on over zero-filled stages to the next multiple of four steps."""
+    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    _, _, _, cfg = run_case(oracle, "bf16", 256, 512, K, alpha=0.5, act="gelu_tanh", seed=K, lda=K + 8, plan="direct")
+    assert cfg == "bf16_256x256x64_w4"
+    _, _, _, cfg = run_case(oracle, "bf16", 264, 248, K, alpha=-0.5, seed=K + 1, plan="direct")
+    assert cfg == "bf16_256x256x64_w4"
+    for transA, transB in LAYOUTS:
+        if transA and not transB:
+            continue
+        _, _, _, cfg = run_fused_case(oracle, 256, 264, K, transA=transA, transB=transB, with_row_scale=True, act="relu",
+                                      out="bf16", pad=(8, 0, 0, 8), plan="direct", seed=K + 2 * transA + transB)
+        assert cfg == f"bf16_fused_256x256x64_w4_{NAME[transA, transB]}"
 
 
 @pytest.mark.parametrize("M,N", [(520, 256), (256, 264), (328, 776), (8, 8), (249, 505)])
@@ -79,13 +96,17 @@ def test_widened_operator_ragged_tiles(oracle, transA, transB, out, monkeypatch)
 
 def test_split_k(oracle, monkeypatch):
     """Partial tiles from the four-wave kernel, reduced in slice order: matches the oracle, repeats
-    bit for bit, and a slice length that is not a multiple of 128 falls back to eight waves."""
+    bit for bit; slice lengths that are not multiples of 128 take the edge variant, short ones eight waves."""
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     got1, _, _, cfg = run_case(oracle, "bf16", 256, 512, 2048, alpha=0.125, act="gelu_tanh", seed=41, plan="splitk", split_k=4)
     assert cfg == "bf16_256x256x64_w4_splitk"
     got2, _, _, _ = run_case(oracle, "bf16", 256, 512, 2048, alpha=0.125, act="gelu_tanh", seed=41, plan="splitk", split_k=4)
     assert np.array_equal(got1, got2)
     _, _, _, cfg = run_case(oracle, "bf16", 256, 256, 1152, alpha=0.125, seed=42, plan="splitk", split_k=4)  # slices of 288
+    assert cfg == "bf16_256x256x64_w4_splitk"
+    _, _, _, cfg = run_case(oracle, "bf16", 256, 256, 1096, alpha=0.125, seed=43, plan="splitk", split_k=3)  # 384, 384, 328
+    assert cfg == "bf16_256x256x64_w4_splitk"
+    _, _, _, cfg = run_case(oracle, "bf16", 256, 256, 800, alpha=0.125, seed=44, plan="splitk", split_k=4)   # slices of 224: too short
     assert cfg == "bf16_256x256x32_w8_splitk"
 
 

@@ -72,14 +72,16 @@ def test_convolution_sweep(oracle, chunk):
 
 @pytest.mark.parametrize("chunk", range(4))
 def test_four_wave_sweep(oracle, chunk, monkeypatch):
-    """Full 256 x 256 tiles over K ranges in multiples of 128, the tile forced: the shapes the four-wave kernel
-    takes, with every storage, consumer chain, output type, padding, batch and K slicing drawn at random."""
+    """256 x 256 tiles, full or ragged, over K ranges of 256 and more, the tile forced: the shapes the four-wave
+    kernel takes, with every storage, consumer chain, output type, padding, batch and K slicing drawn at random."""
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     rng = np.random.default_rng(7000 + chunk)
     seen = set()
     for i in range(8):
         M, N = 256 * int(_pick(rng, [1, 1, 2, 3])), 256 * int(_pick(rng, [1, 2, 3]))
         K = 128 * int(_pick(rng, [2, 3, 4, 5, 8, 9]))
+        if rng.random() < 0.4:                            # ragged in every direction: the edge variant
+            M, N, K = M - 8 * int(rng.integers(0, 20)), N - 8 * int(rng.integers(0, 20)), K + 8 * int(rng.integers(0, 16))
         splitk = K >= 1024 and rng.random() < 0.5         # 1024 or 1152 in 2 slices: 512 (four waves) or 576 (eight)
         pad = tuple(int(8 * rng.integers(0, 3)) for _ in range(4))
         _, _, _, cfg = run_fused_case(
