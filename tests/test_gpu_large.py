@@ -58,6 +58,37 @@ def test_plain_a_of_five_gigabytes(oracle):
     _check(C[idx].cpu().numpy().astype(np.float64), ref, f"plain {M}x{N}x{K} [{binding.last_config()}]")
 
 
+def test_four_wave_kernel_a_of_five_gigabytes(oracle):
+    """The same A against 256 columns, both storages of B: 4688 tile rows of the four-wave kernel (the last one
+    ragged), tile bases up to 4.9e9 bytes into A, fp32 and bf16 output."""
+    import torch
+    from paper_2604_01489_amd import binding
+    M, N, K = 1_200_000, 256, 2048
+    A = _big_bf16(M, K, 111, K ** -0.5)
+    B = _big_bf16(K, N, 112, 1.0)
+    bias = torch.linspace(-0.5, 0.5, N, device="cuda:0")
+    C = torch.empty(M, N, dtype=torch.float32, device="cuda:0")
+    print(f"large four-wave case M={M} N={N} K={K}", flush=True)
+    binding.gemm_epilogue_bf16(M, N, K, A, K, B, N, bias, 0.5, "relu", C, N, 1)
+    torch.cuda.synchronize()
+    assert binding.last_config() == "bf16_256x256x64_w4"
+    rows = _rows(M)
+    idx = torch.from_numpy(rows).cuda()
+    ref = oracle.gemm_epilogue(_bits(A[idx]), _bits(B), bias.cpu().numpy(), 0.5, "relu")
+    _check(C[idx].cpu().numpy().astype(np.float64), ref, f"plain {M}x{N}x{K} [{binding.last_config()}]")
+    del C
+    Bt = B.t().contiguous()
+    C16 = torch.empty(M, N, dtype=torch.bfloat16, device="cuda:0")
+    binding.gemm_epilogue_bf16_fused(M, N, K, A, K, Bt, K, C16, N, transB=True, alpha=0.5, bias=bias, act="relu")
+    torch.cuda.synchronize()
+    assert binding.last_config() == "bf16_fused_256x256x64_w4_nt"
+    got = C16[idx].to(torch.float32).cpu().numpy().astype(np.float64)
+    # the oracle's fp32-output result rounded as the kernel rounds: compare within the bar plus half a bf16 step
+    err = np.abs(got - ref)
+    assert np.all(err <= ELEM_TOL * np.maximum(1.0, np.abs(ref)) + np.abs(ref) * 2.0 ** -8), "bf16 output"
+    assert float(np.linalg.norm(got - ref) / np.linalg.norm(ref)) <= 4e-3
+
+
 @pytest.mark.parametrize("transA", [False, True])
 def test_fused_batch_stride_past_two_to_the_31(oracle, transA):
     """Two batches of a 70000 x 32768 A (2.29e9 elements each, 9.2 GB together), stored either way round,
