@@ -7,9 +7,14 @@ import pytest
 pytestmark = pytest.mark.gpu
 
 
-def test_calls_replay_from_a_captured_graph():
+@pytest.mark.parametrize("force", [None, "256x256"])
+def test_calls_replay_from_a_captured_graph(force, monkeypatch):
+    """As the planner routes them (128 x 128 tiles at these sizes) and with the 256 x 256 tile forced, which
+    puts all three calls on the four-wave kernel (plain, partial tiles, bf16 output through LDS)."""
     import torch
     from paper_2604_01489_amd import binding, inputs as gen
+    if force:
+        monkeypatch.setenv("GE_FORCE_CONFIG", force)
     dev = torch.device("cuda:0")
     M, N, K = 512, 512, 256
     A = torch.from_numpy(gen.to_bf16_bits(gen.normal(70, 0, M * K, K ** -0.5).reshape(M, K)).view(np.int16)).to(dev)
@@ -31,6 +36,8 @@ def test_calls_replay_from_a_captured_graph():
     eager = [torch.empty(M, N, device=dev), torch.empty(256, 256, device=dev), torch.empty(M, N, dtype=torch.bfloat16, device=dev)]
     enqueue(*eager, torch.cuda.current_stream())
     torch.cuda.synchronize()
+    if force:
+        assert binding.last_config() == "bf16_fused_256x256x64_w4_nn", binding.last_config()
 
     out = [torch.zeros_like(t) for t in eager]
     graph = torch.cuda.CUDAGraph()
