@@ -231,7 +231,12 @@ gemm_bf16_kernel(const GemmParams p)
         tapH = tap / p.convKW;
         tapW = tap % p.convKW;
     }
-    auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
+    // issue_prep(kt) sets up tile kt (resource words, K-edge limit, tap offsets); issue_one(l, ...) then
+    // issues its load l (A's first, then B's); issue() is both for all loads.
+    rsrc_words_t rA, rB;
+    int kLeft = 0, dIh = 0, dIw = 0;                 // valid k in the tile (EDGE only); tap displacement (CONV only)
+    unsigned tapOff = 0u;
+    auto issue_prep = [&](int kt) {
         const long long stepA = CONV ? 0ll : TA ? (long long)kt * BK * p.lda * 2 : (long long)kt * (BK * 2);
         const long long stepB = TB ? (long long)kt * (BK * 2) : (long long)kt * BK * p.ldb * 2;
         // Full tiles: every offset lies inside the operand by construction, and the exact extent
@@ -241,34 +246,39 @@ gemm_bf16_kernel(const GemmParams p)
         // unconditionally, then selected: a conditional around it would be a scalar branch.
         const unsigned leftA = (EDGE || CONV) ? records_left(p.bytesA, offA + stepA) : RSRC_RECORDS;
         const unsigned leftB = EDGE ? records_left(p.bytesB, offB + stepB) : RSRC_RECORDS;
-        const unsigned recA = kt < nk ? leftA : 0u;
-        const unsigned recB = kt < nk ? leftB : 0u;
-        const rsrc_words_t rA = make_rsrc(gA + stepA, recA);
-        const rsrc_words_t rB = make_rsrc(gB + stepB, recB);
-        const int kLeft = kLen - kt * BK;            // valid k in this tile (EDGE only)
-        const int dIh = tapH * p.convDh, dIw = tapW * p.convDw;
-        const unsigned tapOff = (unsigned)(((dIh * p.convW + dIw) * p.convCin + tapC) * 2);
-#pragma unroll
-        for (int j = 0; j < T::A_LOADS; ++j) {
-            unsigned v = voffA[j];
-            if (CONV) {
-                const bool inside = (unsigned)(ih0[j] + dIh) < (unsigned)p.convH && (unsigned)(iw0[j] + dIw) < (unsigned)p.convW;
-                v = inside ? v + tapOff : OOB_OFFSET;
-            }
-            if (EDGE && kA[j] >= kLeft) v = OOB_OFFSET;
-            lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
-        }
+        rA = make_rsrc(gA + stepA, kt < nk ? leftA : 0u);
+        rB = make_rsrc(gB + stepB, kt < nk ? leftB : 0u);
+        kLeft = kLen - kt * BK;
         if (CONV) {
+            dIh = tapH * p.convDh;
+            dIw = tapW * p.convDw;
+            tapOff = (unsigned)(((dIh * p.convW + dIw) * p.convCin + tapC) * 2);
             tapC += BK;
             if (tapC >= p.convCin) { tapC = 0; ++tapW; }
             if (tapW >= p.convKW) { tapW = 0; ++tapH; }
         }
-#pragma unroll
-        for (int j = 0; j < T::B_LOADS; ++j) {
+    };
+    auto issue_one = [&](int l, GE_LDS char *dA, GE_LDS char *dB) {
+        if (l < T::A_LOADS) {
+            const int j = l < T::A_LOADS ? l : 0;
+            unsigned v = voffA[j];
+            if (CONV) {
+                const bool inside = (unsigned)(ih0[CONV ? j : 0] + dIh) < (unsigned)p.convH && (unsigned)(iw0[CONV ? j : 0] + dIw) < (unsigned)p.convW;
+                v = inside ? v + tapOff : OOB_OFFSET;
+            }
+            if (EDGE && kA[j] >= kLeft) v = OOB_OFFSET;
+            lds_dma16(rA, (unsigned)(size_t)(dA + (j * NW + w) * 1024), v);
+        } else {
+            const int j = l < T::A_LOADS ? 0 : l - T::A_LOADS;
             unsigned v = voffB[j];
             if (EDGE && kB[j] >= kLeft) v = OOB_OFFSET;
             lds_dma16(rB, (unsigned)(size_t)(dB + (j * NW + w) * 1024), v);
         }
+    };
+    auto issue = [&](int kt, GE_LDS char *dA, GE_LDS char *dB) {
+        issue_prep(kt);
+#pragma unroll
+        for (int l = 0; l < LOADS; ++l) issue_one(l, dA, dB);
     };
 
     // K64: tile t64 (64 k from kBegin + 64 t64) into stage `stage` of two.  A k-strided operand
@@ -406,6 +416,24 @@ gemm_bf16_kernel(const GemmParams p)
             }
     };
 
+    // The same with the loads of the tile set up by issue_prep issued between the MFMAs, one every
+    // fourth (four-wave blocks: issued back to back at the head of the step they cost 4-7 % on the
+    // mid-size shapes these blocks serve, 2048^3 25.7 -> 24.2 us).
+    auto mma_with_loads = [&](GE_LDS char *dA, GE_LDS char *dB) {
+        constexpr int SPREAD = (TM * TN) / LOADS >= 4 ? 4 : (TM * TN) / LOADS >= 2 ? 2 : 1;
+        static_assert(LOADS <= TM * TN, "a load slot per MFMA at most");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (OUTBF16) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                const int q = i * TN + j;
+                if (q % SPREAD == 0 && q / SPREAD < LOADS) issue_one(q / SPREAD, dA, dB);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    };
+
     GE_LDS char *const ldsBase = (GE_LDS char *)smem;
     GE_LDS char *lA[4], *lB[4];
 #pragma unroll
@@ -421,7 +449,7 @@ gemm_bf16_kernel(const GemmParams p)
     //  8 waves: [LDS reads t, loads t+3, wait own part of t+1] barrier [MFMAs t] barrier (the LDS
     //           reads go first: their latency, not the load issue, is what the phase waits for),
     //           the two groups half a step apart (one extra barrier for group 1 up front);
-    //  4 waves: [wait own part of t] barrier [loads t+3, LDS reads t, MFMAs t].
+    //  4 waves: [wait own part of t] barrier [LDS reads t, MFMAs t with the loads of t+3 between them].
 #define GE_BF16_STEP(S, t)                                                                          \
     if (PINGPONG) {                                                                                 \
         read_frags(S);                                                                              \
@@ -438,9 +466,10 @@ gemm_bf16_kernel(const GemmParams p)
     } else {                                                                                        \
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * LOADS) : "memory");    \
         __builtin_amdgcn_sched_barrier(0);                                                          \
-        issue((t) + 3, lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
+        issue_prep((t) + 3);                                                                        \
         read_frags(S);                                                                              \
-        mma();                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                          \
+        mma_with_loads(lA[((S) + 3) & 3], lB[((S) + 3) & 3]);                                       \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 
