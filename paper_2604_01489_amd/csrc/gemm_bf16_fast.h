@@ -340,6 +340,32 @@ gemm_bf16_kernel(const GemmParams p)
         }
     };
 
+    // The same tile in two parts, for the four-wave blocks, which issue its loads between their MFMAs:
+    // issue64_prep sets up tile t64, issue64_one issues load l of it (both operands in 128-byte rows).
+    rsrc_words_t rA64, rB64;
+    int kLeft64 = 0;
+    auto issue64_prep = [&](int t64) {
+        const long long step = (long long)t64 * 128;
+        const unsigned leftA = EDGE ? records_left(p.bytesA, offA + step) : RSRC_RECORDS;
+        const unsigned leftB = EDGE ? records_left(p.bytesB, offB + step) : RSRC_RECORDS;
+        rA64 = make_rsrc(gA + step, t64 < nk64 ? leftA : 0u);
+        rB64 = make_rsrc(gB + step, t64 < nk64 ? leftB : 0u);
+        kLeft64 = kLen - t64 * 64;
+    };
+    auto issue64_one = [&](int l, int stage) {
+        if (l < NLA) {
+            const int j = l < NLA ? l : 0;
+            unsigned v = voffA[j];
+            if (EDGE && kA[j] >= kLeft64) v = OOB_OFFSET;
+            lds_dma16(rA64, (unsigned)(size_t)((GE_LDS char *)smem + stage * 2 * T::A_BYTES + (j * NW + w) * 1024), v);
+        } else {
+            const int j = l < NLA ? 0 : l - NLA;
+            unsigned v = voffB[j];
+            if (EDGE && kB[j] >= kLeft64) v = OOB_OFFSET;
+            lds_dma16(rB64, (unsigned)(size_t)((GE_LDS char *)smem + 4 * T::A_BYTES + stage * 2 * T::B_BYTES + (j * NW + w) * 1024), v);
+        }
+    };
+
     // ---- per-lane LDS read addresses ---------------------------------------------
     // k-contiguous stage, fragment i: rows base + 16 i + lane%16, k chunk lane/16
     // (k = 8*(lane/16) + e): one ds_read_b128, stepping i adds 1 KB.
@@ -434,6 +460,21 @@ gemm_bf16_kernel(const GemmParams p)
             }
     };
 
+    auto mma_with_loads64 = [&](int stage) {
+        constexpr int N64 = NLA + NLB, SPREAD = (TM * TN) / N64 >= 2 ? 2 : 1;
+        static_assert(!K64 || N64 <= TM * TN, "a load slot per MFMA at most");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if (OUTBF16) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+                else acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                const int q = i * TN + j;
+                if (q % SPREAD == 0 && q / SPREAD < N64) issue64_one(q / SPREAD, stage);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    };
+
     GE_LDS char *const ldsBase = (GE_LDS char *)smem;
     GE_LDS char *lA[4], *lB[4];
 #pragma unroll
@@ -477,7 +518,7 @@ gemm_bf16_kernel(const GemmParams p)
     // are issued in the even piece, into the stage whose second half every wave finished reading
     // before the last barrier, and awaited in the odd piece.
     //  8 waves: [LDS reads, (loads | wait)] barrier [MFMAs] barrier, the two groups half a piece apart;
-    //  4 waves: even piece [wait own part of this tile] barrier [loads t64+1, LDS reads, MFMAs],
+    //  4 waves: even piece [wait own part of this tile] barrier [LDS reads, MFMAs with the loads of t64+1 between them],
     //           odd piece [LDS reads, MFMAs].
 #define GE_BF16_STEP64(Q, t64)                                                                      \
     if (PINGPONG) {                                                                                 \
@@ -500,10 +541,20 @@ gemm_bf16_kernel(const GemmParams p)
         if (((Q) & 1) == 0) {                                                                       \
             asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");                \
             __builtin_amdgcn_sched_barrier(0);                                                      \
-            issue64((t64) + 1, (((Q) >> 1) ^ 1));                                                   \
+            if (A64 && B64) {                                                                       \
+                issue64_prep((t64) + 1);                                                            \
+                read_frags(Q);                                                                      \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+                mma_with_loads64(((Q) >> 1) ^ 1);                                                   \
+            } else {                                                                                \
+                issue64((t64) + 1, (((Q) >> 1) ^ 1));                                               \
+                read_frags(Q);                                                                      \
+                mma();                                                                              \
+            }                                                                                       \
+        } else {                                                                                    \
+            read_frags(Q);                                                                          \
+            mma();                                                                                  \
         }                                                                                           \
-        read_frags(Q);                                                                              \
-        mma();                                                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                          \
     }
 

@@ -116,7 +116,10 @@ void launch_tile_k(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStrea
 template <int BM, int BN, int WM, int WN>
 bool launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
 {
-    const bool k64 = stage_k64(p.transA != 0, p.transB != 0);
+    // 128 x 128 blocks: only where more than one block shares a CU (measured with both operands along
+    // k, bf16 out: 4096x2048x2048, 512 blocks, 33 us with 64 k per load phase against 44 us with 32;
+    // 2048^3, 256 blocks, 27 against 22 us; 2048x2048x8192 81 against 66 us)
+    const bool k64 = stage_k64(p.transA != 0, p.transB != 0) && (BM == 256 || grid.x > (unsigned)kNumCU);
     if (k64) launch_tile_k<BM, BN, WM, WN, true>(p, edge || (p.K % 64) || (p.kPerSlice % 64), raw, grid, st);
     else     launch_tile_k<BM, BN, WM, WN, false>(p, edge, raw, grid, st);
     return k64;

@@ -15,12 +15,13 @@ LAYOUTS = list(itertools.product([False, True], repeat=2))
 NAME = {(False, False): "nn", (False, True): "nt", (True, False): "tn", (True, True): "tt"}
 
 
-def stage_k(transA, transB):
-    """k per load phase the library picks for a layout (64 where both operands' rows run along k);
+def stage_k(transA, transB, shared_cu=True):
+    """k per load phase the library picks for a layout (64 where both operands' rows run along k; with
+    128 x 128 blocks only when more than 256 blocks are launched, so that blocks share a CU);
     GE_STAGE_K=32 switches that off for timing runs."""
     if os.environ.get("GE_STAGE_K") == "32":
         return 32
-    return 64 if (not transA and transB) else 32
+    return 64 if (not transA and transB and shared_cu) else 32
 
 
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
@@ -40,6 +41,11 @@ def test_layouts_tile_128(oracle, transA, transB):
     for M, N, K in [(128, 128, 192), (136, 248, 200), (8, 8, 8), (64, 384, 40)]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", with_row_scale=True,
                                       seed=3 * M + K)
+        assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB, shared_cu=False)}_w4_{NAME[transA, transB]}"
+    # more blocks than CUs (17 x 17 full and ragged tiles): 64 k per load phase where both operands run along k
+    for M, N, K in [(2176, 2176, 192), (2184, 2168, 200)]:
+        _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, act="relu", with_row_scale=True,
+                                      out="bf16", seed=3 * M + K, plan="direct")
         assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB)}_w4_{NAME[transA, transB]}"
 
 
@@ -127,7 +133,7 @@ def test_split_k(oracle, transA, transB, monkeypatch):
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
                                   with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
                                   plan="splitk", split_k=0, seed=41)
-    assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB)}_w4_{NAME[transA, transB]}_splitk"
+    assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB, shared_cu=False)}_w4_{NAME[transA, transB]}_splitk"
     monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
     monkeypatch.setenv("GE_WAVES", "8")         # the four-wave kernel has its own tests
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
