@@ -9,7 +9,10 @@ one synthetic batch already resident in HBM.  The default workload is the
 8192^3 bf16 GEMM + bias + tanh-GELU the headline metric is quoted on.  Prints one
 JSON line with the whole-job rate, the roofline fraction of the dominant kernel
 (algorithmic FLOP or bytes per launch over the launch time measured with HIP
-events on the launch stream) and the CPU oracle timed on a bounded sample.
+events on the launch stream) and the CPU oracle timed on a sample of the same
+workload (`--oracle-rows`; the default is every row of C at 8192^3, about 15 s on the 16
+host cores of a GPU machine; the widened operator's oracle takes 512 rows).
+fp32 workloads (c1_f32_256, c13_f32_8192x8192x2048) are measured against the fp32 matrix peak.
 """
 from __future__ import annotations
 
@@ -26,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 matrix peak (datasheet)
+PEAK_F32_TFLOPS = 157.3     # MI355X fp32 matrix peak (datasheet)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E bandwidth (datasheet)
 DEFAULT_WORKLOAD = "c3_bf16_8192_bias_gelu"
 # which roofline bounds the dominant kernel of each workload
@@ -38,6 +42,16 @@ BOUND = {
     "c7_fused_tn_8192_chain": "mfma",
     "c8_fused_batched_512x512x64_bf16out": "hbm",
     "c11_fused_lower_8192_bias_relu": "mfma",
+    "c1_f32_256": "mfma",
+    "c13_f32_8192x8192x2048": "mfma",
+}
+# 16-byte pieces read : written by the HBM-bound workloads, for the stream probe of the same mix
+# (c4: 33.5 MB in, 268 MB out; c8: 33.5 in, 134 out; c9: 134 in, 268 out; c12: reads only)
+STREAM_MIX = {
+    "c4_bf16_batched_512x512x64": (1, 8),
+    "c8_fused_batched_512x512x64_bf16out": (1, 4),
+    "c9_diag_bf16_8192": (1, 2),
+    "c12_rowsum_linear_8192": (1, 0),
 }
 
 
@@ -81,10 +95,12 @@ def kernel_source_hash() -> str:
     return h.hexdigest()[:16]
 
 
-def measured_ceilings(torch, binding, dA, stream):
+def measured_ceilings(torch, binding, dA, stream, mix=None, mfma=True):
     """What the device itself sustains, measured in this run with HIP events: a register-resident
     bf16 MFMA loop fed with the workload's own operand values (the clock is power-managed and
-    depends on them), and a streaming fp32 store of 256 MiB."""
+    depends on them), a streaming fp32 store of 256 MiB, and -- for an HBM-bound workload -- a
+    stream with the workload's own ratio of bytes read to bytes written (`mix` = 16-byte pieces
+    read, written per step; about 256 MiB moved per launch)."""
     def timed(fn, reps):
         fn()
         torch.cuda.synchronize()
@@ -97,17 +113,29 @@ def measured_ceilings(torch, binding, dA, stream):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / reps
 
-    blocks, iters = 512, 40000
-    sink = torch.empty(blocks * 512, dtype=torch.float32, device=dA.device)
-    operands = dA.reshape(-1)[:32768]
-    t = timed(lambda: binding.probe_mfma_bf16(operands, sink, blocks, iters, stream=stream), 3)
-    mfma = blocks * 8 * iters * 16 * (2.0 * 16 * 16 * 32) / t / 1e12
+    out, how = {}, []
+    if mfma:
+        blocks, iters = 512, 40000
+        sink = torch.empty(blocks * 512, dtype=torch.float32, device=dA.device)
+        operands = dA.reshape(-1).view(torch.int16)[:32768]
+        t = timed(lambda: binding.probe_mfma_bf16(operands, sink, blocks, iters, stream=stream), 3)
+        out["mfma_bf16_tflops"] = round(blocks * 8 * iters * 16 * (2.0 * 16 * 16 * 32) / t / 1e12, 1)
+        how.append("v_mfma_f32_16x16x32_bf16 loop, 512 blocks x 8 waves, operands = first 64 KiB of A")
     buf = torch.empty(64 << 20, dtype=torch.float32, device=dA.device)
     t = timed(lambda: binding.probe_store_f32(buf, 1.0, stream=stream), 20)
-    store = buf.numel() * 4 / t / 1e9
-    return {"mfma_bf16_tflops": round(mfma, 1), "store_gbs": round(store, 1),
-            "how": "v_mfma_f32_16x16x32_bf16 loop, 512 blocks x 8 waves, operands = first 64 KiB of A; "
-                   "fp32 store of 256 MiB, 16 B per lane"}
+    out["store_gbs"] = round(buf.numel() * 4 / t / 1e9, 1)
+    how.append("fp32 store of 256 MiB, 16 B per lane")
+    if mix is not None:
+        reads, writes = mix
+        trips = (256 << 20) // (16 * (reads + writes))
+        src = torch.ones(trips * reads * 4, dtype=torch.int32, device=dA.device)
+        dst = torch.empty(max(trips * writes * 4, 4), dtype=torch.int32, device=dA.device)
+        t = timed(lambda: binding.probe_stream_mix(src, dst, trips, reads, writes, stream=stream), 20)
+        out["stream_mix_gbs"] = round(trips * 16.0 * (reads + writes) / t / 1e9, 1)
+        out["stream_mix"] = {"reads": reads, "writes": writes}
+        how.append(f"stream of {reads} read : {writes} written 16-byte pieces, 256 MiB per launch")
+    out["how"] = "; ".join(how)
+    return out
 
 
 def blas_yardstick(torch, dA, dB, transA: bool, transB: bool, flops: float, warmup: int, steps: int):
@@ -190,6 +218,10 @@ def bench_diag(args, torch, binding, gen) -> int:
                 "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(args.workload, config_name),
                 "kernel": config_name,
                 "ms_per_launch": round(ms_dev, 4)}
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measured_ceilings(torch, binding, dB, stream, mix=STREAM_MIX.get(args.workload), mfma=False)
+        roofline["frac_of_measured"] = round(achieved / ceilings["stream_mix_gbs"], 4)
     # the same product as a dense GEMM: A = diag(d) rounded to bf16 (context only; d is fp32 in the entry point)
     dense = None
     if batch == 1:
@@ -224,7 +256,7 @@ def bench_diag(args, torch, binding, gen) -> int:
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": args.workload, "M": M, "N": N, "batch": batch, "alpha": w.alpha, "act": w.act,
                       "bias": True, "out_dtype": "f32", "kernel": config_name},
-           "roofline": roofline, "dense_gemm": dense, "cpu_baseline": cpu_baseline, "parity": parity}
+           "roofline": roofline, "ceilings": ceilings, "dense_gemm": dense, "cpu_baseline": cpu_baseline, "parity": parity}
     print(json.dumps(out))
     return 0 if parity is None or parity["ok"] else 1
 
@@ -276,6 +308,10 @@ def bench_rowsum(args, torch, binding, gen) -> int:
                 "kernel": config_name, "ms_per_launch": round(ms_dev, 4),
                 "ms_parameter_pass": round(ms_params, 4), "kernel_parameter_pass": cfg_params,
                 "ms_input_pass": round(ms_apply, 4)}
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measured_ceilings(torch, binding, dA, stream, mix=STREAM_MIX.get(args.workload), mfma=False)
+        roofline["frac_of_measured"] = round(achieved / ceilings["stream_mix_gbs"], 4)
     # the long way round: the layer's output through the fused GEMM (fp32), then its sum over n
     dC = torch.empty(M, N, dtype=torch.float32, device=dev)
     _, ms_long = timed(lambda: (binding.gemm_epilogue_bf16_fused(M, N, K, dA, K, dW, K, dC, N, transB=True, alpha=w.alpha,
@@ -303,7 +339,7 @@ def bench_rowsum(args, torch, binding, gen) -> int:
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": args.workload, "M": M, "N": N, "K": K, "alpha": w.alpha, "bias": True,
                       "weights": "N x K", "kernel": config_name},
-           "roofline": roofline, "long_way": long_way, "cpu_baseline": cpu_baseline, "parity": parity}
+           "roofline": roofline, "ceilings": ceilings, "long_way": long_way, "cpu_baseline": cpu_baseline, "parity": parity}
     print(json.dumps(out))
     return 0 if parity is None or parity["ok"] else 1
 
@@ -455,9 +491,8 @@ def main() -> int:
     fw = gen.FUSED_WORKLOADS[args.workload] if fused else None
     w = fw.base if fused else gen.WORKLOADS[args.workload]
     job = fw if fused else w                       # flops and algorithmic bytes
-    if w.dtype != "bf16":
-        print("bench.py times the bf16 workloads", file=sys.stderr)
-        return 2
+    f32 = w.dtype == "f32"
+    peak_mfma = PEAK_F32_TFLOPS if f32 else PEAK_BF16_TFLOPS
     dev = torch.device("cuda:0")
     M, N, K, batch = w.M, w.N, w.K, w.batch
     stream = torch.cuda.current_stream()
@@ -499,6 +534,8 @@ def main() -> int:
                                              transB=fw.transB, alpha=w.alpha, row_scale=drs, bias=dbias,
                                              residual=dR, ldr=N, beta=fw.beta, act=w.act, clamp=fw.clamp,
                                              stream=stream, a_structure=structure[0])
+        elif f32:
+            binding.gemm_epilogue_f32(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
         else:
             binding.gemm_epilogue_bf16(M, N, K, a, K, b, N, dbias, w.alpha, w.act, c, N, batch, stream=stream)
 
@@ -531,8 +568,8 @@ def main() -> int:
     bound = BOUND[args.workload]
     if bound == "mfma":
         achieved = job.flops / (ms_dev * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None}
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak_mfma,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak_mfma, 4), "traffic": None}
     else:
         achieved = job.algorithmic_bytes / (ms_dev * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
@@ -543,9 +580,12 @@ def main() -> int:
     roofline["ms_single_launch"] = {"median": round(singles[len(singles) // 2], 4), "min": round(singles[0], 4)}
     ceilings = None
     if not args.no_ceilings:
-        ceilings = measured_ceilings(torch, binding, dA, stream)
-        top = ceilings["mfma_bf16_tflops"] if bound == "mfma" else ceilings["store_gbs"]
-        roofline["frac_of_measured"] = round(achieved / top, 4)
+        # fp32 operands: no probe of the fp32 matrix pipe exists, the datasheet fraction stands alone
+        ceilings = measured_ceilings(torch, binding, dA, stream, mix=STREAM_MIX.get(args.workload), mfma=not f32)
+        if bound == "hbm":
+            roofline["frac_of_measured"] = round(achieved / ceilings["stream_mix_gbs"], 4)
+        elif not f32:
+            roofline["frac_of_measured"] = round(achieved / ceilings["mfma_bf16_tflops"], 4)
 
     # a structured A: the same call without the promise (every multiply-add of the full product), for scale
     general = None
@@ -566,7 +606,7 @@ def main() -> int:
         step()                                                  # leave the promised call's result in C
         torch.cuda.synchronize()
     blas = None
-    if not args.no_blas:
+    if not args.no_blas and not f32:
         try:
             blas = blas_yardstick(torch, dA, dB, bool(fused and fw.transA), bool(fused and fw.transB), job.flops,
                                   args.warmup, args.steps)
@@ -612,7 +652,8 @@ def main() -> int:
                   "max_abs_err": float(err.max()), "ok": ok}
 
     out = {
-        "metric": "TFLOP/s and % of MI355X bf16 MFMA peak, GEMM+bias+GELU at 8192^3",
+        "metric": ("TFLOP/s and % of MI355X fp32 MFMA peak, fp32 GEMM" if f32 else
+                   "TFLOP/s and % of MI355X bf16 MFMA peak, GEMM+bias+GELU at 8192^3"),
         "value": round(tflops, 2),
         "unit": "TFLOP/s",
         "n_gpus": 1,
@@ -622,7 +663,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "f32" if f32 else "bf16",
         "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "batch": batch,
                    "alpha": w.alpha, "act": w.act, "bias": w.bias is not None,
@@ -631,7 +672,7 @@ def main() -> int:
                    "row_scale": bool(fused and fw.row_scale), "residual": fw.residual if fused else None,
                    "clamp": fw.clamp if fused else None, "a_structure": fw.a_structure if fused else "general",
                    "kernel": config_name},
-        "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        ("pct_of_f32_mfma_peak" if f32 else "pct_of_bf16_mfma_peak"): round(100.0 * tflops / peak_mfma, 2),
         "roofline": roofline,
         "ceilings": ceilings,
         "general_call": general,

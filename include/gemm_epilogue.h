@@ -27,6 +27,19 @@
  * or bias.  bf16 values are passed as their 16-bit patterns so this header
  * needs no HIP types.
  *
+ * Partial results.  Plans that slice K (and the column-sum pass of
+ * gemm_rowsum_params_bf16) park fp32 partial results in a workspace.  A call
+ * that takes a `workspace` argument and is given one allocates nothing.
+ * Otherwise the library keeps one buffer per (device, stream): the first call
+ * on a stream that needs a larger one than that stream has had calls hipMalloc
+ * (which may take time but does not wait for the device); a buffer that was
+ * handed out is never freed or moved before ge_release_workspace, so work
+ * already enqueued, and graphs already captured, keep a valid address.  A
+ * stream that is being captured is refused such a first allocation
+ * (GE_ERR_WORKSPACE): run the call once on that stream before capturing, or
+ * pass a workspace.  Calls on different streams use different buffers; calls
+ * on one stream are ordered by it.
+ *
  * Errors.  Every call validates its arguments first and returns a status; on
  * any status other than GE_OK nothing was enqueued and C is untouched.
  *
@@ -85,11 +98,10 @@ typedef enum {
  *   stream            hipStream_t
  * Fast kernels (direct-to-LDS loads) need A and B 16-byte aligned, lda, ldb, N
  * and K multiples of 8; any other legal argument list takes a guarded generic
- * kernel with the same result contract (Debugging guide, "gate by alignment ...
- * correct fallback").  Large-K small-MN shapes use split-K with a workspace the
- * library owns (grown with hipMalloc when a larger one is first needed, freed
- * by ge_release_workspace or at process exit); calls that use it must be
- * ordered on one stream at a time.
+ * kernel with the same result contract (the coding and debugging guide's rule
+ * for vectorised copies: gated by alignment, with a correct fallback).  Large-K
+ * small-MN shapes use split-K with the library's workspace of the stream (see
+ * "Partial results" above).
  */
 ge_status_t gemm_epilogue_bf16(int M, int N, int K,
                                const uint16_t *A, int lda,
@@ -222,10 +234,11 @@ ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
  * Wt 16-byte aligned, Cin a multiple of 32, Cout a multiple of 8, an input smaller than
  * 2 GiB and (for bf16 output) Y 16-byte aligned; any other legal argument list takes a guarded
  * kernel with the same result contract.  Shapes with few output tiles and a long K are split
- * over K into the library-owned workspace (as gemm_epilogue_bf16 does) and summed in slice order:
- * bitwise repeatable; such calls must be ordered on one stream at a time.
+ * over K and summed in slice order (bitwise repeatable); the partial results go to `workspace`
+ * (256-byte aligned, at least conv2d_epilogue_workspace_bytes(args) bytes) or, when it is NULL,
+ * to the library's buffer of the stream (see "Partial results" above).
  * Errors: GE_ERR_NULL, GE_ERR_SHAPE (a size < 1, an empty output, index ranges), GE_ERR_ACT,
- * GE_ERR_EPILOGUE, GE_ERR_ALIGN, GE_ERR_LAUNCH.
+ * GE_ERR_EPILOGUE, GE_ERR_ALIGN, GE_ERR_WORKSPACE, GE_ERR_LAUNCH.
  */
 typedef struct ge_conv_args {
     int N, H, W, Cin, Cout, KH, KW;
@@ -238,9 +251,14 @@ typedef struct ge_conv_args {
     ge_act_t act;
     float clamp_lo, clamp_hi;
     void *Y; ge_dtype_t y_type;
+    void *workspace; size_t workspace_bytes;
 } ge_conv_args_t;
 
 ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *stream);
+
+/* Bytes of workspace the convolution needs for these sizes (0 when it runs in one pass, or
+ * when the sizes are not valid).  Host only; reads the sizes and pointers' alignment only. */
+size_t conv2d_epilogue_workspace_bytes(const ge_conv_args_t *args);
 
 /*
  * Structured operand: A = diag(d), an M x M matrix given by its diagonal.
@@ -295,8 +313,8 @@ ge_status_t gemm_epilogue_diag_bf16(int M, int N, const float *d,
  *   params            device, fp32[K + 1] as written by gemm_rowsum_params_bf16
  *   y                 device, fp32[M], written
  * 16-byte row pieces are used when the pointer and leading dimension allow it, single elements
- * otherwise.  gemm_rowsum_params_bf16 with transB != 0 uses the library-owned workspace (see
- * gemm_epilogue_bf16) for partial column sums.
+ * otherwise.  gemm_rowsum_params_bf16 with transB != 0 parks partial column sums in the library's
+ * workspace of the stream (see "Partial results" at the top).
  * Errors: GE_ERR_NULL, GE_ERR_SHAPE, GE_ERR_LD, GE_ERR_ALIGN (a pointer not aligned to its
  * element), GE_ERR_WORKSPACE, GE_ERR_LAUNCH.
  */
@@ -306,7 +324,9 @@ ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda, const flo
                              float alpha, float *y, void *stream);
 
 /* Bytes of split-K workspace the bf16 call needs for this shape with `plan` and
- * `split_k` as above (0 when the chosen plan is direct).  Host only. */
+ * `split_k` as above (0 when the chosen plan is direct): the size depends on the
+ * plan the caller is going to ask for, so the query takes the same two arguments
+ * as the call.  Host only. */
 size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch,
                                      ge_plan_t plan, int split_k);
 
@@ -314,9 +334,24 @@ size_t gemm_epilogue_workspace_bytes(int M, int N, int K, int batch,
  * Host only; needs no device. */
 int gemm_epilogue_auto_split_k(int M, int N, int K, int batch);
 
-/* Frees the library-owned split-K workspace of the current device (after the
- * caller has synchronised the streams that used it). */
+/* Frees every library-owned workspace of the current device, outgrown ones included.
+ * The caller has synchronised the streams that used them and replays no graph that
+ * was captured over them.  Calls hipFree (which waits for the device). */
 ge_status_t ge_release_workspace(void);
+
+/*
+ * Switches for timing runs and tests; none changes a result contract.
+ *   "force_config"  "256x256" | "128x128" | "generic": block tile of the bf16 kernels
+ *                   ("generic" also for fp32), whatever the planner would pick
+ *   "waves"         "8": full 256 x 256 tiles stay on the eight-wave kernel ("4": default)
+ *   "stage_k"       "32": no 64-k load phases in the eight-wave kernel ("64": default)
+ * value == NULL restores the default.  Process-wide, effective from the next call.  The
+ * initial values come from the environment variables GE_FORCE_CONFIG, GE_WAVES and
+ * GE_STAGE_K, read once when the library is loaded; no entry point reads the
+ * environment afterwards.
+ * Errors: GE_ERR_NULL (name), GE_ERR_CONFIG (unknown name or value).
+ */
+ge_status_t ge_set_option(const char *name, const char *value);
 
 /* Static, never NULL. */
 const char *ge_status_string(ge_status_t status);

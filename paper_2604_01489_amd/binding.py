@@ -13,16 +13,19 @@ import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgemm_epilogue.so")
+PROBES_LIB_PATH = os.path.join(_HERE, "libge_probes.so")
 
 ACT = {"none": 0, "relu": 1, "gelu_tanh": 2}
 PLAN = {"auto": 0, "direct": 1, "splitk": 2}
 GE_OK = 0
 
+# what each header declares and the library that exports it
 SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
-           "ge_release_workspace", "ge_status_string", "ge_last_config",
-           "ge_probe_mfma_bf16", "ge_probe_store_f32", "gemm_epilogue_bf16_fused",
-           "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16")
+           "ge_release_workspace", "ge_status_string", "ge_last_config", "ge_set_option",
+           "gemm_epilogue_bf16_fused", "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16",
+           "conv2d_epilogue_workspace_bytes", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16")
+PROBE_SYMBOLS = ("ge_probe_mfma_bf16", "ge_probe_store_f32", "ge_probe_stream_mix")
 
 DTYPE = {"f32": 0, "bf16": 1}
 STRUCTURE = {"general": 0, "lower": 1, "upper": 2}
@@ -54,10 +57,12 @@ class ConvArgs(ctypes.Structure):
         ("X", ctypes.c_void_p), ("Wt", ctypes.c_void_p), ("alpha", ctypes.c_float), ("bias", ctypes.c_void_p),
         ("R", ctypes.c_void_p), ("r_type", ctypes.c_int), ("beta", ctypes.c_float),
         ("act", ctypes.c_int), ("clamp_lo", ctypes.c_float), ("clamp_hi", ctypes.c_float),
-        ("Y", ctypes.c_void_p), ("y_type", ctypes.c_int)]
+        ("Y", ctypes.c_void_p), ("y_type", ctypes.c_int),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 _lib = None
+_probes = None
 
 
 class GemmEpilogueError(RuntimeError):
@@ -106,12 +111,38 @@ def load():
     lib.gemm_rowsum_params_bf16.argtypes = [c_int, c_int, c_void, c_int, c_int, c_void, c_void, c_void]
     lib.gemm_rowsum_bf16.restype = c_int
     lib.gemm_rowsum_bf16.argtypes = [c_int, c_int, c_void, c_int, c_void, c_float, c_void, c_void]
+    lib.conv2d_epilogue_workspace_bytes.restype = c_size
+    lib.conv2d_epilogue_workspace_bytes.argtypes = [ctypes.POINTER(ConvArgs)]
+    lib.ge_set_option.restype = c_int
+    lib.ge_set_option.argtypes = [ctypes.c_char_p, ctypes.c_char_p]
+    _lib = lib
+    return lib
+
+
+def load_probes():
+    """Load the measurement probes (``include/ge_probes.h``), a library of their own."""
+    global _probes
+    if _probes is not None:
+        return _probes
+    if not os.path.exists(PROBES_LIB_PATH):
+        raise FileNotFoundError(
+            f"{PROBES_LIB_PATH} is missing: run `python -m paper_2604_01489_amd.build` first")
+    lib = ctypes.CDLL(PROBES_LIB_PATH)
+    c_int, c_void, c_float, c_size = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
     lib.ge_probe_mfma_bf16.restype = c_int
     lib.ge_probe_mfma_bf16.argtypes = [c_void, c_void, c_int, c_int, c_void]
     lib.ge_probe_store_f32.restype = c_int
     lib.ge_probe_store_f32.argtypes = [c_void, c_size, c_float, c_void]
-    _lib = lib
+    lib.ge_probe_stream_mix.restype = c_int
+    lib.ge_probe_stream_mix.argtypes = [c_void, c_void, c_size, c_int, c_int, c_void]
+    _probes = lib
     return lib
+
+
+def set_option(name: str, value=None):
+    """``ge_set_option``: a switch for timing runs and tests ("force_config", "waves", "stage_k");
+    ``None`` restores the default."""
+    _check(load().ge_set_option(name.encode(), None if value is None else str(value).encode()))
 
 
 def status_string(status: int) -> str:
@@ -151,10 +182,21 @@ def raw_call(name, M, N, K, A_ptr, lda, B_ptr, ldb, bias_ptr, alpha, act, C_ptr,
                   *extra, stream_ptr))
 
 
+def _require_extent(t, rows, cols, ld, batch=1, what="operand"):
+    """The tensor must hold what the sizes describe: batch*rows rows of `ld` elements, the last one
+    `cols` long.  A wrong size here would otherwise become an out-of-bounds access on the device."""
+    if t is None:
+        return
+    need = (int(batch) * int(rows) - 1) * int(ld) + int(cols)
+    if rows >= 1 and cols >= 1 and batch >= 1 and ld >= cols and t.numel() < need:
+        raise ValueError(f"{what}: tensor holds {t.numel()} elements, the sizes describe {need}")
+
+
 def gemm_epilogue_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=1, stream=None):
     """C = act(alpha*A@B + bias); A, B: device tensors of bf16 bit patterns
     (torch.bfloat16, int16 or uint16), bias/C: float32 device tensors."""
     _require_device(A, B, C, bias)
+    _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch)
     _check(load().gemm_epilogue_bf16(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), alpha,
                                      ACT[act], _ptr(C), ldc, batch, _stream_handle(stream)))
 
@@ -162,6 +204,7 @@ def gemm_epilogue_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=
 def gemm_epilogue_f32(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=1, stream=None):
     """fp32 operands, fp32 matrix instructions."""
     _require_device(A, B, C, bias)
+    _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch)
     _check(load().gemm_epilogue_f32(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), alpha,
                                     ACT[act], _ptr(C), ldc, batch, _stream_handle(stream)))
 
@@ -169,10 +212,19 @@ def gemm_epilogue_f32(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=1
 def gemm_epilogue_bf16_ex(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=1,
                           plan="auto", split_k=0, workspace=None, stream=None):
     _require_device(A, B, C, bias, workspace)
+    _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load().gemm_epilogue_bf16_ex(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), alpha,
                                         ACT[act], _ptr(C), ldc, batch, PLAN[plan], split_k,
                                         _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+def _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch, transA=False, transB=False, R=None, ldr=0):
+    _require_extent(A, K if transA else M, M if transA else K, lda, batch, "A")
+    _require_extent(B, N if transB else K, K if transB else N, ldb, batch, "B")
+    _require_extent(C, M, N, ldc, batch, "C")
+    _require_extent(R, M, N, ldr, batch, "R")
+    _require_extent(bias, 1, N, N, 1, "bias")
 
 
 def workspace_bytes(M, N, K, batch=1, plan="auto", split_k=0) -> int:
@@ -217,6 +269,8 @@ def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA
     "general", or the caller's promise that opA(A) is "lower" / "upper" triangular."""
     import torch
     _require_device(A, B, C, row_scale, bias, residual, workspace)
+    _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch, transA, transB, residual, ldr)
+    _require_extent(row_scale, 1, M, M, 1, "row_scale")
 
     def kind(t):
         return "f32" if t.dtype == torch.float32 else "bf16"
@@ -232,12 +286,17 @@ def gemm_epilogue_bf16_fused(M, N, K, A, lda, B, ldb, C, ldc, *, batch=1, transA
 
 
 def conv_args(shape, X_ptr, Wt_ptr, Y_ptr, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias_ptr=None,
-              R_ptr=None, r_type="f32", beta=1.0, act="none", clamp=None, y_type="f32") -> ConvArgs:
+              R_ptr=None, r_type="f32", beta=1.0, act="none", clamp=None, y_type="f32", workspace_ptr=None,
+              workspace_bytes=0) -> ConvArgs:
     """Fill a ``ge_conv_args_t`` from raw addresses; ``shape`` = (N, H, W, Cin, Cout, KH, KW)."""
     lo, hi = (-float("inf"), float("inf")) if clamp is None else clamp
     return ConvArgs(*shape, stride[0], stride[1], pad[0], pad[1], dil[0], dil[1], X_ptr, Wt_ptr, alpha, bias_ptr,
                     R_ptr, DTYPE[r_type], beta, ACT[act] if isinstance(act, str) else int(act), lo, hi, Y_ptr,
-                    DTYPE[y_type] if isinstance(y_type, str) else int(y_type))
+                    DTYPE[y_type] if isinstance(y_type, str) else int(y_type), workspace_ptr, workspace_bytes)
+
+
+def conv_workspace_bytes(args: ConvArgs) -> int:
+    return int(load().conv2d_epilogue_workspace_bytes(ctypes.byref(args)))
 
 
 def raw_conv(args: ConvArgs) -> int:
@@ -246,11 +305,11 @@ def raw_conv(args: ConvArgs) -> int:
 
 
 def conv2d_epilogue_bf16(X, Wt, Y, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, bias=None, residual=None,
-                         beta=1.0, act="none", clamp=None, stream=None):
+                         beta=1.0, act="none", clamp=None, workspace=None, stream=None):
     """Channels-last convolution with the fused consumer chain on device tensors: ``X`` [N,H,W,Cin] and
     ``Wt`` [Cout,KH,KW,Cin] hold bf16 (bits), ``Y`` [N,OH,OW,Cout] is float32 or bfloat16."""
     import torch
-    _require_device(X, Wt, Y, bias, residual)
+    _require_device(X, Wt, Y, bias, residual, workspace)
 
     def kind(t):
         return "f32" if t.dtype == torch.float32 else "bf16"
@@ -260,7 +319,8 @@ def conv2d_epilogue_bf16(X, Wt, Y, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alp
     args = conv_args((Nb, H, W, Cin, Cout, KH, KW), _addr(X), _addr(Wt), _addr(Y), stride=stride, pad=pad, dil=dil,
                      alpha=alpha, bias_ptr=_addr(bias), R_ptr=_addr(residual),
                      r_type=kind(residual) if residual is not None else "f32", beta=beta, act=act, clamp=clamp,
-                     y_type=kind(Y))
+                     y_type=kind(Y), workspace_ptr=_addr(workspace),
+                     workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
     _check(load().conv2d_epilogue_bf16(ctypes.byref(args), _stream_handle(stream)))
 
 
@@ -303,13 +363,23 @@ def raw_rowsum(M, K, A_ptr, lda, params_ptr, alpha, y_ptr) -> int:
 def probe_mfma_bf16(operands, sink, blocks, iters, stream=None):
     """Measured ceiling: register-resident bf16 MFMA loop (include/ge_probes.h)."""
     _require_device(operands, sink)
-    _check(load().ge_probe_mfma_bf16(_ptr(operands), _ptr(sink), blocks, iters, _stream_handle(stream)))
+    _check(load_probes().ge_probe_mfma_bf16(_ptr(operands), _ptr(sink), blocks, iters, _stream_handle(stream)))
 
 
 def probe_store_f32(dst, value=1.0, stream=None):
     """Measured ceiling: streaming fp32 store over all of ``dst`` (include/ge_probes.h)."""
     _require_device(dst)
-    _check(load().ge_probe_store_f32(_ptr(dst), dst.numel(), value, _stream_handle(stream)))
+    _check(load_probes().ge_probe_store_f32(_ptr(dst), dst.numel(), value, _stream_handle(stream)))
+
+
+def probe_stream_mix(src, dst, trips, reads, writes, stream=None):
+    """Measured ceiling: a stream of ``trips`` steps that each read ``reads`` and write ``writes``
+    16-byte pieces (include/ge_probes.h)."""
+    _require_device(src, dst)
+    nbytes = lambda t: 0 if t is None else t.numel() * t.element_size()
+    if nbytes(src) < trips * reads * 16 or nbytes(dst) < max(trips * writes * 16, 16):
+        raise ValueError("probe buffer too small for the trips asked for")
+    _check(load_probes().ge_probe_stream_mix(_ptr(src), _ptr(dst), trips, reads, writes, _stream_handle(stream)))
 
 
 def _require_device(*tensors):

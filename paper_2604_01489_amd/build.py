@@ -1,4 +1,5 @@
-"""Build step: compile the HIP sources into ``libgemm_epilogue.so`` for gfx950.
+"""Build step: compile the HIP sources into ``libgemm_epilogue.so`` (the operator) and
+``libge_probes.so`` (the measurement probes) for gfx950.
 
 ``python -m paper_2604_01489_amd.build`` or ``build_library()``.  hipcc cross
 compiles without a GPU.  The library is kept in-tree, next to this file.
@@ -12,15 +13,30 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_epilogue.so")
-SOURCES = ["gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip", "gemm_diag.hip", "gemm_rowsum.hip", "ge_probes.hip"]
+PROBES_LIB = os.path.join(HERE, "libge_probes.so")
+LIB_SOURCES = ["gemm_epilogue_api.hip", "gemm_fused_api.hip", "conv_api.hip", "gemm_diag.hip", "gemm_rowsum.hip"]
+PROBE_SOURCES = ["ge_probes.hip"]
+SOURCES = LIB_SOURCES + PROBE_SOURCES
 # packed fp32 instructions are kept off: some of their forms have misbehaved on this hardware
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose: bool = False, extra_flags=()) -> str:
+def _includes(path, seen):
+    """Files a source pulls in through #include "..." (transitively)."""
+    import re
+    if path in seen or not os.path.exists(path):
+        return seen
+    seen.add(path)
+    for inc in re.findall(r'^\s*#include\s+"([^"]+)"', open(path).read(), flags=re.M):
+        _includes(os.path.normpath(os.path.join(os.path.dirname(path), inc)), seen)
+    return seen
+
+
+def build_library(verbose: bool = False, extra_flags=(), incremental: bool = False) -> str:
     """Compile every source to an object (in parallel: the kernel templates dominate the build
-    time), then link ``libgemm_epilogue.so``."""
+    time), then link the two libraries.  ``incremental`` keeps the objects that are newer than
+    the source and every header it includes (for work on one file; the default compiles all)."""
     from concurrent.futures import ThreadPoolExecutor
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
@@ -28,6 +44,10 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
+        if incremental and not extra_flags and os.path.exists(obj):
+            deps = _includes(os.path.join(CSRC, src), set())
+            if all(os.path.getmtime(d) <= os.path.getmtime(obj) for d in deps):
+                return obj
         cmd = ["hipcc", *compile_flags, *extra_flags, "-c", "-o", obj, os.path.join(CSRC, src)]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -37,22 +57,24 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
             raise RuntimeError(f"hipcc failed on {src}")
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(6, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("link failed")
+    n = len(LIB_SOURCES)
+    for out, group in ((LIB, objs[:n]), (PROBES_LIB, objs[n:])):
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *group]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout + res.stderr)
+            raise RuntimeError("link failed")
     return LIB
 
 
 def library_is_current() -> bool:
-    if not os.path.exists(LIB):
+    if not os.path.exists(LIB) or not os.path.exists(PROBES_LIB):
         return False
-    t = os.path.getmtime(LIB)
+    t = min(os.path.getmtime(LIB), os.path.getmtime(PROBES_LIB))
     deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
     inc = os.path.join(os.path.dirname(HERE), "include")
     deps += [os.path.join(inc, f) for f in os.listdir(inc)]
@@ -60,4 +82,4 @@ def library_is_current() -> bool:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=True, incremental="--incremental" in sys.argv[1:]))

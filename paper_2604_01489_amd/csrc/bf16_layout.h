@@ -7,7 +7,7 @@
 // pick their global chunk, and fragment reads use the inverse.
 #pragma once
 
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 #define GE_HD __host__ __device__
 #else
 #define GE_HD

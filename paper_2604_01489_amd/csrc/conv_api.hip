@@ -29,23 +29,27 @@ void launch_conv(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_
     constexpr int threads = WM * WN * 64;
     const bool h = p.cType == ge::DT_BF16;
     if (raw) {
-        if (edge) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
-        else      hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
+        if (edge) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
+        else      GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, true, ge::ACT_NONE, false, true, false, false, true>), grid, dim3(threads), 0, st, p);
     } else if (edge) {
-        if (h) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
-        else   hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
+        if (h) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
+        else   GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, true, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
     } else {
-        if (h) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
-        else   hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
+        if (h) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, true, true>), grid, dim3(threads), 0, st, p);
+        else   GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, false, false, ge::ACT_NONE, false, true, true, false, true>), grid, dim3(threads), 0, st, p);
     }
 }
 
-}  // namespace
+// Validation and plan of one call: everything that depends on the sizes and on the alignment of the
+// pointers only, shared by the call itself and by the workspace query.
+struct ConvPlan {
+    int OH, OW;
+    long long M, K, xElems;
+    Plan pl;
+};
 
-extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *stream)
+ge_status_t plan_conv(const ge_conv_args_t &a, ConvPlan *out)
 {
-    if (!args) return GE_ERR_NULL;
-    const ge_conv_args_t &a = *args;
     if (!a.X || !a.Wt || !a.Y) return GE_ERR_NULL;
     if (a.N < 1 || a.H < 1 || a.W < 1 || a.Cin < 1 || a.Cout < 1 || a.KH < 1 || a.KW < 1) return GE_ERR_SHAPE;
     if (a.stride_h < 1 || a.stride_w < 1 || a.pad_h < 0 || a.pad_w < 0 || a.dil_h < 1 || a.dil_w < 1) return GE_ERR_SHAPE;
@@ -71,9 +75,29 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
     bool fast = !((((uintptr_t)a.X) | ((uintptr_t)a.Wt)) & 15u) && (a.Cin % 32 == 0) && (a.Cout % 8 == 0) &&
                 xElems * 2 < (1ll << 31) - (1 << 20) && K * 2 * 256 + 1024 < (1ll << 31);
     if (a.y_type == GE_DTYPE_BF16 && (((uintptr_t)a.Y) & 15u)) fast = false;
-    Plan pl;
-    ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &pl);
+    out->OH = OH; out->OW = OW; out->M = M; out->K = K; out->xElems = xElems;
+    return make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &out->pl);
+}
+
+}  // namespace
+
+extern "C" size_t conv2d_epilogue_workspace_bytes(const ge_conv_args_t *args)
+{
+    ConvPlan cp;
+    if (!args || plan_conv(*args, &cp) != GE_OK) return 0;
+    return partial_bytes((int)cp.M, args->Cout, 1, cp.pl.splitK);
+}
+
+extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *stream)
+{
+    if (!args) return GE_ERR_NULL;
+    const ge_conv_args_t &a = *args;
+    ConvPlan cp;
+    ge_status_t st = plan_conv(a, &cp);
     if (st != GE_OK) return st;
+    const int OH = cp.OH, OW = cp.OW;
+    const long long M = cp.M, K = cp.K, xElems = cp.xElems;
+    const Plan &pl = cp.pl;
 
     GemmParams p{};
     p.A = a.X; p.B = a.Wt; p.bias = a.bias; p.C = (float *)a.Y;
@@ -114,7 +138,7 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
     void *ws = nullptr;
     GemmParams pg = p;
     if (raw) {
-        st = acquire_workspace(partial_bytes((int)M, a.Cout, 1, pl.splitK), nullptr, 0, &ws);
+        st = acquire_workspace(partial_bytes((int)M, a.Cout, 1, pl.splitK), a.workspace, a.workspace_bytes, (hipStream_t)stream, &ws);
         if (st != GE_OK) return st;
         pg.C = (float *)ws;
     }
@@ -130,18 +154,18 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
         g_last_config = raw ? "conv_bf16_128x128x32_w4_splitk" : "conv_bf16_128x128x32_w4";
         break;
     default:
-        if (raw) hipLaunchKernelGGL(ge::conv_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
-        else     hipLaunchKernelGGL(ge::conv_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
+        if (raw) GE_LAUNCH(ge::conv_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
+        else     GE_LAUNCH(ge::conv_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
         g_last_config = raw ? "conv_bf16_generic_64x64x32_splitk" : "conv_bf16_generic_64x64x32";
         break;
     }
-    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
     if (raw) {
         const long long total = M * a.Cout;
         long long blocks = (total + 255) / 256;
         if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
-        hipLaunchKernelGGL(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
-        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+        GE_LAUNCH(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
+        if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
     }
     return GE_OK;
 }

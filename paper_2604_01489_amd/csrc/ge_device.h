@@ -210,24 +210,47 @@ __device__ inline float bf16_bits_as_f32(unsigned bits16) { return __uint_as_flo
 // [max(lo, 0), hi], or the constant hi where that interval is empty (hi < 0), so the bounds are
 // adjusted once, on the scalar unit, and each value costs one median-of-three either way (on a
 // store-bound shape the epilogue's vector instructions are time nothing else overlaps).
+//
+// Non-finite values follow the compare-and-select chain of fused_value (and of the CPU reference):
+// relu maps NaN to 0, which is then clamped; without relu a NaN stays a NaN through the clamp.  The
+// median-of-three instruction returns the smaller bound for a NaN, which is the right answer after
+// relu and the wrong one otherwise: there the clamp is skipped altogether when both sides are off
+// (a uniform branch), and a NaN is put back by one compare and select per value when they are not.
+__device__ __forceinline__ float clamp_keep_nan(float v, float lo, float hi)
+{
+    const float c = __builtin_amdgcn_fmed3f(v, lo, hi);
+    return v != v ? v : c;
+}
+
 template <int TN>
 __device__ __forceinline__ void act_clamp_row_block(const GemmParams &p, f32x4_t (&v)[TN])
 {
+    const bool clampOn = p.clampLo != -__builtin_inff() || p.clampHi != __builtin_inff();
     if (p.act == ACT_GELU_TANH) {
+        if (clampOn) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
-    } else {
-        float lo = p.clampLo, hi = p.clampHi;
-        if (p.act == ACT_RELU) {
-            lo = lo > 0.0f ? lo : 0.0f;
-            lo = hi < lo ? hi : lo;
+                for (int r = 0; r < 4; ++r) v[j][r] = clamp_keep_nan(gelu_tanh_f32(v[j][r]), p.clampLo, p.clampHi);
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[j][r] = gelu_tanh_f32(v[j][r]);
         }
+    } else if (p.act == ACT_RELU) {
+        float lo = p.clampLo, hi = p.clampHi;
+        lo = lo > 0.0f ? lo : 0.0f;
+        lo = hi < lo ? hi : lo;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[j][r] = __builtin_amdgcn_fmed3f(v[j][r], lo, hi);
+    } else if (clampOn) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = clamp_keep_nan(v[j][r], p.clampLo, p.clampHi);
     }
 }
 

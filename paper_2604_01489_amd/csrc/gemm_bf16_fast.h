@@ -51,7 +51,7 @@ typedef __attribute__((ext_vector_type(4))) int rsrc_words_t;
 __device__ inline void lds_dma16(rsrc_words_t rs, unsigned ldsAddr, unsigned voff)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(ldsAddr), "v"(voff), "s"(rs) : "memory");
+                 :: "s"(ldsAddr), "v"(voff), "s"(rs) : "memory", "m0");
 }
 
 // num_records for a resource that starts `consumed` bytes into an allocation of `total` bytes:

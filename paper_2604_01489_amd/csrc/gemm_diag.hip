@@ -79,15 +79,15 @@ extern "C" ge_status_t gemm_epilogue_diag_bf16(int M, int N, const float *d, con
     const dim3 grid((unsigned)blocks), block(256);
     if (vec) {
         if (act == GE_ACT_RELU)
-            hipLaunchKernelGGL(diag_rows_vec4_kernel<ge::ACT_RELU>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
+            GE_LAUNCH(diag_rows_vec4_kernel<ge::ACT_RELU>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
         else if (act == GE_ACT_GELU_TANH)
-            hipLaunchKernelGGL(diag_rows_vec4_kernel<ge::ACT_GELU_TANH>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
+            GE_LAUNCH(diag_rows_vec4_kernel<ge::ACT_GELU_TANH>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
         else
-            hipLaunchKernelGGL(diag_rows_vec4_kernel<ge::ACT_NONE>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
+            GE_LAUNCH(diag_rows_vec4_kernel<ge::ACT_NONE>, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, C, ldc);
         ge_host::g_last_config = "diag_rows_vec4";
     } else {
-        hipLaunchKernelGGL(diag_rows_kernel, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, (int)act, C, ldc);
+        GE_LAUNCH(diag_rows_kernel, grid, block, 0, hs, M, N, batch, d, B, ldb, bias, alpha, (int)act, C, ldc);
         ge_host::g_last_config = "diag_rows_generic";
     }
-    return hipGetLastError() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
+    return ge_host::take_launch_error() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
 }

@@ -3,9 +3,11 @@
 // include/gemm_epilogue.h for the contract of every entry point.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "../../include/gemm_epilogue.h"
 #include "gemm_bf16_fast.h"
@@ -18,14 +20,45 @@ namespace ge_host {
 
 thread_local const char *g_last_config = "none";
 
-constexpr int kMaxDevices = 64;
+thread_local hipError_t g_launch_error = hipSuccess;
 
+// Library-owned buffers for partial results, one per (device, stream) that has needed one: calls on
+// different streams never share a buffer, calls on one stream are ordered by it.
 struct Workspace {
-    void *ptr = nullptr;
-    size_t bytes = 0;
+    int dev;
+    hipStream_t stream;
+    void *ptr;
+    size_t bytes;
 };
-Workspace g_ws[kMaxDevices];
+std::vector<Workspace> g_ws, g_ws_retired;
 std::mutex g_ws_mutex;
+
+// Switches for timing runs and tests: set by ge_set_option, initial values from the environment,
+// read once when the library is loaded.
+std::atomic<int> g_opt_force{FORCE_NONE};
+std::atomic<int> g_opt_waves8{0}, g_opt_stage32{0};
+
+int parse_force(const char *v)
+{
+    if (!v) return FORCE_NONE;
+    if (std::strcmp(v, "256x256") == 0) return FORCE_256;
+    if (std::strcmp(v, "128x128") == 0) return FORCE_128;
+    if (std::strcmp(v, "generic") == 0) return FORCE_GENERIC;
+    return -1;
+}
+
+const bool g_env_read = [] {
+    const int f = parse_force(std::getenv("GE_FORCE_CONFIG"));
+    g_opt_force = f < 0 ? FORCE_NONE : f;
+    const char *w = std::getenv("GE_WAVES"), *k = std::getenv("GE_STAGE_K");
+    g_opt_waves8 = (w && std::strcmp(w, "8") == 0) ? 1 : 0;
+    g_opt_stage32 = (k && std::strcmp(k, "32") == 0) ? 1 : 0;
+    return true;
+}();
+
+int opt_force_config() { return g_opt_force.load(std::memory_order_relaxed); }
+bool opt_eight_waves() { return g_opt_waves8.load(std::memory_order_relaxed) != 0; }
+bool opt_stage_k32() { return g_opt_stage32.load(std::memory_order_relaxed) != 0; }
 
 bool fast_path_ok(int N, int K, const void *A, int lda, const void *B, int ldb)
 {
@@ -98,9 +131,9 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
     Plan pl{};
     if (plan != GE_PLAN_AUTO && plan != GE_PLAN_DIRECT && plan != GE_PLAN_SPLITK) return GE_ERR_CONFIG;
     if (split_k < 0) return GE_ERR_CONFIG;
-    const char *force = std::getenv("GE_FORCE_CONFIG");
+    const int force = opt_force_config();
     int want = 1;
-    if (!fast || (force && std::strcmp(force, "generic") == 0)) {
+    if (!fast || force == FORCE_GENERIC) {
         pl.tile = TILE_GENERIC; pl.bm = 64; pl.bn = 64; pl.bk = 32;
         const long long tiles = (long long)ceil_div(M, 64) * ceil_div(N, 64) * batch;
         if (plan == GE_PLAN_SPLITK) want = split_k > 0 ? split_k : choose_split(tiles, K, 512);
@@ -122,8 +155,8 @@ ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t 
             costOf[c] = plan_cost_us(M, N, K, batch, tileOf[c], slicesOf[c]);
         }
         bool big = (M >= 256 && N >= 256) && costOf[0] <= costOf[1];
-        if (force && std::strcmp(force, "256x256") == 0) big = true;
-        if (force && std::strcmp(force, "128x128") == 0) big = false;
+        if (force == FORCE_256) big = true;
+        if (force == FORCE_128) big = false;
         if (big) { pl.tile = TILE_256; pl.bm = 256; pl.bn = 256; pl.bk = ge::BF16_BK; want = slicesOf[0]; }
         else     { pl.tile = TILE_128; pl.bm = 128; pl.bn = 128; pl.bk = ge::BF16_BK; want = slicesOf[1]; }
     }
@@ -191,7 +224,7 @@ int choose_group_m(int tilesM, int tilesN)
     return g < 1 ? 1 : g;
 }
 
-ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void **out)
+ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, hipStream_t stream, void **out)
 {
     if (user) {
         if (user_bytes < need || ((uintptr_t)user & 255u)) return GE_ERR_WORKSPACE;
@@ -199,24 +232,30 @@ ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, void *
         return GE_OK;
     }
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GE_ERR_WORKSPACE;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return GE_ERR_WORKSPACE;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    Workspace &ws = g_ws[dev];
-    if (ws.bytes < need) {
-        if (ws.ptr) {
-            (void)hipFree(ws.ptr);   // waits for work that may still read it
-            ws.ptr = nullptr;
-            ws.bytes = 0;
-        }
-        void *ptr = nullptr;
-        if (hipMalloc(&ptr, need) != hipSuccess) {
-            (void)hipGetLastError();
-            return GE_ERR_WORKSPACE;
-        }
-        ws.ptr = ptr;
-        ws.bytes = need;
+    Workspace *ws = nullptr;
+    for (Workspace &w : g_ws)
+        if (w.dev == dev && w.stream == stream) { ws = &w; break; }
+    if (ws && ws->bytes >= need) {
+        *out = ws->ptr;
+        return GE_OK;
     }
-    *out = ws.ptr;
+    // A larger buffer is needed.  hipMalloc is not a capturable operation, and a graph captured
+    // now would keep replaying into whatever address it recorded: refuse instead.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return GE_ERR_WORKSPACE;
+    void *ptr = nullptr;
+    if (hipMalloc(&ptr, need) != hipSuccess) return GE_ERR_WORKSPACE;
+    if (ws) {
+        // work enqueued earlier (or a graph captured earlier) may still use the outgrown buffer
+        g_ws_retired.push_back(Workspace{dev, nullptr, ws->ptr, 0});
+        ws->ptr = ptr;
+        ws->bytes = need;
+    } else {
+        g_ws.push_back(Workspace{dev, stream, ptr, need});
+    }
+    *out = ptr;
     return GE_OK;
 }
 
@@ -224,15 +263,15 @@ template <int EDGE>
 hipError_t launch_four_wave(const GemmParams &p, bool raw, int act, dim3 grid, hipStream_t st)
 {
     if (raw) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, true, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, true, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else if (act == GE_ACT_RELU) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_RELU, false, false, false, false>), grid, dim3(256), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_RELU, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else if (act == GE_ACT_GELU_TANH) {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_GELU_TANH, false, false, false, false>), grid, dim3(256), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_GELU_TANH, false, false, false, false>), grid, dim3(256), 0, st, p);
     } else {
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, false, ge::ACT_NONE, false, false, false, false>), grid, dim3(256), 0, st, p);
     }
-    return hipGetLastError();
+    return ge_host::take_launch_error();
 }
 
 template <int BM, int BN, int WM, int WN, bool EDGE>
@@ -240,15 +279,15 @@ hipError_t launch_fast_sel(const GemmParams &p, bool raw, int act, dim3 grid, hi
 {
     constexpr int threads = WM * WN * 64;
     if (raw) {
-        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, true, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, true, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
     } else if (act == GE_ACT_RELU) {
-        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_RELU>), grid, dim3(threads), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_RELU>), grid, dim3(threads), 0, st, p);
     } else if (act == GE_ACT_GELU_TANH) {
-        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_GELU_TANH>), grid, dim3(threads), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_GELU_TANH>), grid, dim3(threads), 0, st, p);
     } else {
-        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, false, ge::ACT_NONE>), grid, dim3(threads), 0, st, p);
     }
-    return hipGetLastError();
+    return ge_host::take_launch_error();
 }
 
 hipError_t launch_reduce(const GemmParams &p, const float *W, float *C, int ldc, int act,
@@ -258,16 +297,15 @@ hipError_t launch_reduce(const GemmParams &p, const float *W, float *C, int ldc,
     long long blocks = (total / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
-    hipLaunchKernelGGL(ge::splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+    GE_LAUNCH(ge::splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
                        W, p.sliceStride, p.splitK, p.M, p.N, p.batch, bias, alpha, act, C, ldc,
                        (long long)p.M * ldc);
-    return hipGetLastError();
+    return ge_host::take_launch_error();
 }
 
 bool four_wave_ok(const Plan &pl, int K)
 {
-    const char *force = std::getenv("GE_WAVES");
-    if (force && std::strcmp(force, "8") == 0) return false;
+    if (opt_eight_waves()) return false;
     const int range = pl.splitK > 1 ? pl.kPerSlice : K;
     return pl.tile == TILE_256 && range >= 256;
 }
@@ -302,7 +340,7 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     const bool raw = pl.splitK > 1;
     void *ws = nullptr;
     if (raw) {
-        st = acquire_workspace(partial_bytes(M, N, batch, pl.splitK), workspace, workspace_bytes, &ws);
+        st = acquire_workspace(partial_bytes(M, N, batch, pl.splitK), workspace, workspace_bytes, (hipStream_t)stream, &ws);
         if (st != GE_OK) return st;
         p.C = (float *)ws;
     }
@@ -328,9 +366,9 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
         g_last_config = raw ? "bf16_128x128x32_w4_splitk" : "bf16_128x128x32_w4";
         break;
     default:
-        if (raw) hipLaunchKernelGGL(ge::gemm_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, p);
-        else     hipLaunchKernelGGL(ge::gemm_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, p);
-        err = hipGetLastError();
+        if (raw) GE_LAUNCH(ge::gemm_bf16_generic_kernel<true>, grid, dim3(256), 0, hs, p);
+        else     GE_LAUNCH(ge::gemm_bf16_generic_kernel<false>, grid, dim3(256), 0, hs, p);
+        err = ge_host::take_launch_error();
         g_last_config = raw ? "bf16_generic_64x64x32_splitk" : "bf16_generic_64x64x32";
         break;
     }
@@ -376,11 +414,10 @@ ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, cons
     p.splitK = 1;
     p.kPerSlice = ceil_div(K, 16) * 16;
     hipStream_t hs = (hipStream_t)stream;
-    const char *force = std::getenv("GE_FORCE_CONFIG");
     // direct-to-LDS kernel: 16-byte chunks of 4 floats must not straddle rows or the K / N edge
     const bool fast = !((((uintptr_t)A) | ((uintptr_t)B)) & 15u) && !((lda | ldb | N | K) & 3) &&
                       (long long)lda * 4 * 128 + 256 < (1ll << 31) && (long long)ldb * 4 * 16 + 1024 < (1ll << 31) &&
-                      !(force && std::strcmp(force, "generic") == 0);
+                      opt_force_config() != FORCE_GENERIC;
     if (fast) {
         // 128x128 tiles once they give every other CU a block, else 64x64 (more blocks, less padding)
         const long long t128 = (long long)ceil_div(M, 128) * ceil_div(N, 128) * batch;
@@ -394,15 +431,15 @@ ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, cons
         const bool edge = (M % bm) || (N % bm) || (K % 16);
         const dim3 grid((unsigned)blocks), block(256);
         if (big) {
-            if (edge) hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<128, 128, true>), grid, block, 0, hs, p);
-            else      hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<128, 128, false>), grid, block, 0, hs, p);
+            if (edge) GE_LAUNCH((ge::gemm_f32_fast_kernel<128, 128, true>), grid, block, 0, hs, p);
+            else      GE_LAUNCH((ge::gemm_f32_fast_kernel<128, 128, false>), grid, block, 0, hs, p);
             g_last_config = "f32_128x128x16_w4";
         } else {
-            if (edge) hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<64, 64, true>), grid, block, 0, hs, p);
-            else      hipLaunchKernelGGL((ge::gemm_f32_fast_kernel<64, 64, false>), grid, block, 0, hs, p);
+            if (edge) GE_LAUNCH((ge::gemm_f32_fast_kernel<64, 64, true>), grid, block, 0, hs, p);
+            else      GE_LAUNCH((ge::gemm_f32_fast_kernel<64, 64, false>), grid, block, 0, hs, p);
             g_last_config = "f32_64x64x16_w4";
         }
-        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+        if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
         return GE_OK;
     }
     p.tilesM = ceil_div(M, 128);
@@ -410,8 +447,8 @@ ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, cons
     p.groupM = choose_group_m(p.tilesM, p.tilesN);
     const long long blocks = (long long)p.tilesM * p.tilesN * batch;
     if (blocks > 0x7fffffffll) return GE_ERR_SHAPE;
-    hipLaunchKernelGGL(ge::gemm_f32_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, hs, p);
-    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    GE_LAUNCH(ge::gemm_f32_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, hs, p);
+    if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
     g_last_config = "f32_generic_128x128x16";
     return GE_OK;
 }
@@ -442,11 +479,35 @@ int gemm_epilogue_auto_split_k(int M, int N, int K, int batch)
 ge_status_t ge_release_workspace(void)
 {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GE_ERR_WORKSPACE;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return GE_ERR_WORKSPACE;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (g_ws[dev].ptr) (void)hipFree(g_ws[dev].ptr);
-    g_ws[dev].ptr = nullptr;
-    g_ws[dev].bytes = 0;
+    for (std::vector<Workspace> *list : {&g_ws, &g_ws_retired}) {
+        size_t kept = 0;
+        for (Workspace &w : *list) {
+            if (w.dev == dev) (void)hipFree(w.ptr);
+            else (*list)[kept++] = w;
+        }
+        list->resize(kept);
+    }
+    return GE_OK;
+}
+
+ge_status_t ge_set_option(const char *name, const char *value)
+{
+    if (!name) return GE_ERR_NULL;
+    if (std::strcmp(name, "force_config") == 0) {
+        const int f = parse_force(value);
+        if (f < 0) return GE_ERR_CONFIG;
+        g_opt_force = f;
+    } else if (std::strcmp(name, "waves") == 0) {
+        if (value && std::strcmp(value, "8") != 0 && std::strcmp(value, "4") != 0) return GE_ERR_CONFIG;
+        g_opt_waves8 = (value && std::strcmp(value, "8") == 0) ? 1 : 0;
+    } else if (std::strcmp(name, "stage_k") == 0) {
+        if (value && std::strcmp(value, "32") != 0 && std::strcmp(value, "64") != 0) return GE_ERR_CONFIG;
+        g_opt_stage32 = (value && std::strcmp(value, "32") == 0) ? 1 : 0;
+    } else {
+        return GE_ERR_CONFIG;
+    }
     return GE_OK;
 }
 

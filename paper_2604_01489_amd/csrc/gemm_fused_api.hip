@@ -73,11 +73,10 @@ bool fast_ok(const ge_fused_args_t &a)
 // 64 k per load phase (see the kernel) where both operands' rows run along k: measured at 8192^3
 // with bf16 output, 0.85 -> 0.81 ms for that layout and 0.75 -> 0.81 ms for each of the other three,
 // whose k-strided operands are fetched in whole lines anyway and only lose the deeper ring.
-// GE_STAGE_K=32 switches it off, for timing.
+// The option "stage_k" = "32" switches it off, for timing.
 bool stage_k64(bool transA, bool transB)
 {
-    const char *force = std::getenv("GE_STAGE_K");
-    if (force && std::strcmp(force, "32") == 0) return false;
+    if (opt_stage_k32()) return false;
     return !transA && transB;
 }
 
@@ -87,13 +86,13 @@ void launch_layout(const GemmParams &p, dim3 grid, hipStream_t st)
     constexpr int threads = WM * WN * 64;
     constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
     if constexpr (K64) {        // only the layout stage_k64 names
-        hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H, false, true>), grid, dim3(threads), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H, false, true>), grid, dim3(threads), 0, st, p);
     } else if (p.transA) {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(threads), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, false, F, H>), grid, dim3(threads), 0, st, p);
+        if (p.transB) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(threads), 0, st, p);
+        else          GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, false, F, H>), grid, dim3(threads), 0, st, p);
     } else {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(threads), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(threads), 0, st, p);
+        if (p.transB) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(threads), 0, st, p);
+        else          GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(threads), 0, st, p);
     }
 }
 
@@ -131,10 +130,10 @@ void launch_four_wave_layout(const GemmParams &p, dim3 grid, hipStream_t st)
 {
     constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
     if (p.transA) {         // with B along k; the caller keeps the other storage of B on the eight-wave kernel
-        hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(256), 0, st, p);
+        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(256), 0, st, p);
     } else {
-        if (p.transB) hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(256), 0, st, p);
-        else          hipLaunchKernelGGL((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(256), 0, st, p);
+        if (p.transB) GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(256), 0, st, p);
+        else          GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(256), 0, st, p);
     }
 }
 
@@ -206,7 +205,7 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     void *ws = nullptr;
     GemmParams pg = p;                      // the GEMM pass: partial tiles go to the workspace
     if (raw) {
-        st = acquire_workspace(partial_bytes(a.M, a.N, a.batch, pl.splitK), a.workspace, a.workspace_bytes, &ws);
+        st = acquire_workspace(partial_bytes(a.M, a.N, a.batch, pl.splitK), a.workspace, a.workspace_bytes, (hipStream_t)stream, &ws);
         if (st != GE_OK) return st;
         pg.C = (float *)ws;
     }
@@ -230,18 +229,18 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
         else set_config("128x128x32_w4", a.transA, a.transB, raw);
         break;
     default:
-        if (raw) hipLaunchKernelGGL(ge::gemm_bf16_fused_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
-        else     hipLaunchKernelGGL(ge::gemm_bf16_fused_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
+        if (raw) GE_LAUNCH(ge::gemm_bf16_fused_generic_kernel<true>, grid, dim3(256), 0, hs, pg);
+        else     GE_LAUNCH(ge::gemm_bf16_fused_generic_kernel<false>, grid, dim3(256), 0, hs, pg);
         set_config("generic_64x64x32", a.transA, a.transB, raw);
         break;
     }
-    if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+    if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
     if (raw) {
         const long long total = (long long)a.batch * a.M * a.N;
         long long blocks = (total + 255) / 256;
         if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
-        hipLaunchKernelGGL(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
-        if (hipGetLastError() != hipSuccess) return GE_ERR_LAUNCH;
+        GE_LAUNCH(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
+        if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
     }
     return GE_OK;
 }

@@ -159,8 +159,8 @@ void launch_rows_dot(int R, int C, const uint16_t *X, long long ldx, const float
     const long long cap = 2ll * kNumCU;             // two blocks of 16 waves per CU; many rows per staging of v
     if (blocks > cap) blocks = cap;
     const dim3 threads(kRowWaves * 64);
-    if (vec_ok(X, ldx)) hipLaunchKernelGGL(rows_dot_kernel<true>, dim3((unsigned)blocks), threads, lds, st, R, C, X, ldx, v, scale, add, out, stage);
-    else                hipLaunchKernelGGL(rows_dot_kernel<false>, dim3((unsigned)blocks), threads, lds, st, R, C, X, ldx, v, scale, add, out, stage);
+    if (vec_ok(X, ldx)) GE_LAUNCH(rows_dot_kernel<true>, dim3((unsigned)blocks), threads, lds, st, R, C, X, ldx, v, scale, add, out, stage);
+    else                GE_LAUNCH(rows_dot_kernel<false>, dim3((unsigned)blocks), threads, lds, st, R, C, X, ldx, v, scale, add, out, stage);
 }
 
 }  // namespace
@@ -177,23 +177,23 @@ extern "C" ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, 
     if (!transB) {
         // B is K x N: s[k] is the sum of row k
         launch_rows_dot(K, N, B, ldb, nullptr, 1.0f, nullptr, params, st);
-        hipLaunchKernelGGL(vector_sum_kernel, dim3(1), dim3(256), 0, st, N, bias, params + K);
+        GE_LAUNCH(vector_sum_kernel, dim3(1), dim3(256), 0, st, N, bias, params + K);
         g_last_config = "rowsum_params_rows";
     } else {
         // B is stored N x K: s[k] is the sum of column k, in two passes through the workspace
         const int chunks = ceil_div(N, kColChunkRows);
         void *ws = nullptr;
-        const ge_status_t rc = acquire_workspace((size_t)chunks * (size_t)K * sizeof(float), nullptr, 0, &ws);
+        const ge_status_t rc = acquire_workspace((size_t)chunks * (size_t)K * sizeof(float), nullptr, 0, st, &ws);
         if (rc != GE_OK) return rc;
         const bool vec = vec_ok(B, ldb);
         const dim3 grid((unsigned)ceil_div(K, 256 * (vec ? 8 : 1)), (unsigned)chunks);
-        if (vec) hipLaunchKernelGGL(cols_partial_kernel<true>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
-        else     hipLaunchKernelGGL(cols_partial_kernel<false>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
-        hipLaunchKernelGGL(cols_finish_kernel, dim3((unsigned)ceil_div(K, 256) + 1), dim3(256), 0, st, K, chunks, (const float *)ws,
+        if (vec) GE_LAUNCH(cols_partial_kernel<true>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
+        else     GE_LAUNCH(cols_partial_kernel<false>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
+        GE_LAUNCH(cols_finish_kernel, dim3((unsigned)ceil_div(K, 256) + 1), dim3(256), 0, st, K, chunks, (const float *)ws,
                            params, N, bias);
         g_last_config = "rowsum_params_cols";
     }
-    return hipGetLastError() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
+    return ge_host::take_launch_error() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
 }
 
 extern "C" ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda, const float *params,
@@ -205,5 +205,5 @@ extern "C" ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda
     if ((((uintptr_t)A) & 1u) || (((uintptr_t)params) & 3u) || (((uintptr_t)y) & 3u)) return GE_ERR_ALIGN;
     launch_rows_dot(M, K, A, lda, params, alpha, params + K, y, (hipStream_t)stream);
     g_last_config = vec_ok(A, lda) ? "rowsum_rows_vec8" : "rowsum_rows_generic";
-    return hipGetLastError() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
+    return ge_host::take_launch_error() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
 }

@@ -147,6 +147,10 @@ WORKLOADS = {
                                            "normal", 1.0, 1.0, (-1.0, 1.0), "relu"),
     "c5_bf16_splitk_1024x1024x65536": Workload("c5_bf16_splitk_1024x1024x65536", "bf16", 1024, 1024,
                                                65536, 1, 4, "uniform", 1.0, 1.0 / 256.0, "zero", "none"),
+    # a large fp32 product: c1's recipe (U(-1,1), no bias, no activation) at a size that fills the chip,
+    # for the fp32 matrix-instruction roofline (c1 itself is bound by launch latency)
+    "c13_f32_8192x8192x2048": Workload("c13_f32_8192x8192x2048", "f32", 8192, 8192, 2048, 1, 13, "uniform", 1.0, 1.0,
+                                       None, "none"),
 }
 
 

@@ -56,10 +56,8 @@ def sweep_split_k(M: int, N: int, K: int, batch: int = 1, warmup: int = 5, reps:
 
 def sweep_structure(M: int, N: int, K: int, batch: int = 1, warmup: int = 5, reps: int = 20):
     """The two structural choices together: block tile (256 x 256 or 128 x 128, forced through the
-    library's GE_FORCE_CONFIG switch for the duration of a timing) and the number of K slices.
+    library's "force_config" option for the duration of a timing) and the number of K slices.
     Returns (fastest (tile, split, us), the library's own (kernel name, us), [(tile, split, us), ...])."""
-    import os
-
     import torch
     dev = torch.device("cuda:0")
     A = torch.randn(batch * M, K, device=dev).to(torch.bfloat16).view(torch.int16)
@@ -80,19 +78,17 @@ def sweep_structure(M: int, N: int, K: int, batch: int = 1, warmup: int = 5, rep
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps * 1e3
 
-    saved = os.environ.pop("GE_FORCE_CONFIG", None)
+    binding.set_option("force_config", None)
     try:
         own_us = timed("auto", 0)
         own = (binding.last_config(), own_us)
         table = []
         for tile in ("256x256", "128x128"):
-            os.environ["GE_FORCE_CONFIG"] = tile
+            binding.set_option("force_config", tile)
             for s in candidate_splits(K):
                 table.append((tile, s, timed("direct" if s == 1 else "splitk", s)))
     finally:
-        os.environ.pop("GE_FORCE_CONFIG", None)
-        if saved is not None:
-            os.environ["GE_FORCE_CONFIG"] = saved
+        binding.set_option("force_config", None)
     return min(table, key=lambda t: t[2]), own, table
 
 

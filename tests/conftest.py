@@ -17,3 +17,13 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+@pytest.fixture(autouse=True)
+def _library_options_back_to_default(request):
+    """Tests switch kernels through ge_set_option; whatever a GPU test set is undone after it."""
+    yield
+    if request.node.get_closest_marker("gpu") is not None:
+        from paper_2604_01489_amd import binding
+        for name in ("force_config", "waves", "stage_k"):
+            binding.set_option(name, None)

@@ -4,6 +4,8 @@ paddings, dilations, the consumer chain with fp32 and bf16 output, and the guard
 import numpy as np
 import pytest
 
+from paper_2604_01489_amd import binding
+
 from gpu_util import compare, to_device, torch_device
 
 pytestmark = pytest.mark.gpu
@@ -53,7 +55,7 @@ def test_conv_3x3_tiles_128(oracle):
 def test_conv_3x3_tiles_256(oracle, monkeypatch):
     """The 256 x 256 gathering kernel on shapes the oracle finishes quickly (forced: the planning rule gives so
     few tiles to the 128 x 128 kernel)."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     run_conv_case(oracle, (4, 16, 16, 32, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=3,
                   expect="conv_bf16_256x256x32_w8")                                                      # 1024 x 256: full tiles
     run_conv_case(oracle, (1, 18, 19, 64, 264, 3, 3), pad=(1, 1), act="relu", seed=4, expect="conv_bf16_256x256x32_w8")
@@ -102,10 +104,10 @@ def test_conv_split_k_for_few_tiles_and_long_k(oracle, monkeypatch):
     assert cfg == "conv_bf16_128x128x32_w4_splitk"
     cfg = run_conv_case(oracle, (1, 7, 7, 200, 100, 3, 3), pad=(1, 1), stride=(2, 2), act="relu", clamp=(0.0, 1.0), seed=42)
     assert cfg == "conv_bf16_generic_64x64x32_splitk"
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")            # the 256 x 256 kernel's partial tiles
+    binding.set_option("force_config", "256x256")            # the 256 x 256 kernel's partial tiles
     cfg = run_conv_case(oracle, (4, 9, 9, 256, 512, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=41)
     assert cfg == "conv_bf16_256x256x32_w8_splitk"
-    monkeypatch.delenv("GE_FORCE_CONFIG")
+    binding.set_option("force_config", None)
     # repeatable bit for bit
     import torch
     from paper_2604_01489_amd import binding, inputs as gen

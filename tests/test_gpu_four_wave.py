@@ -9,6 +9,8 @@ import itertools
 import numpy as np
 import pytest
 
+from paper_2604_01489_amd import binding
+
 from gpu_util import run_case, run_fused_case
 
 pytestmark = pytest.mark.gpu
@@ -24,10 +26,10 @@ NAME = {(False, False): "nn", (False, True): "nt", (True, False): "tn", (True, T
 ])
 @pytest.mark.parametrize("act", ["none", "relu", "gelu_tanh"])
 def test_plain_operator(oracle, M, N, K, act, monkeypatch):
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     got4, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act=act, seed=M + N + K, plan="direct")
     assert cfg == "bf16_256x256x64_w4"
-    monkeypatch.setenv("GE_WAVES", "8")
+    binding.set_option("waves", "8")
     got8, _, _, cfg = run_case(oracle, "bf16", M, N, K, alpha=0.5, act=act, seed=M + N + K, plan="direct")
     assert cfg == "bf16_256x256x32_w8"
     # same products, same order of the k steps within an accumulator: the two kernels agree closely
@@ -35,7 +37,7 @@ def test_plain_operator(oracle, M, N, K, act, monkeypatch):
 
 
 def test_plain_padded_batched_no_bias(oracle, monkeypatch):
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     _, _, _, cfg = run_case(oracle, "bf16", 256, 512, 256, batch=3, lda=264, ldb=520, ldc=516, act="relu", seed=31,
                             plan="direct")
     assert cfg == "bf16_256x256x64_w4"
@@ -46,7 +48,7 @@ def test_plain_padded_batched_no_bias(oracle, monkeypatch):
 
 def test_not_taken_when_k_is_short(oracle, monkeypatch):
     """K ranges below 256 stay on the eight-wave kernel (one load phase, or a ring that barely turns)."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     for M, N, K in [(256, 256, 128), (520, 264, 248), (256, 256, 64)]:
         _, _, _, cfg = run_case(oracle, "bf16", M, N, K, act="relu", seed=M + K, plan="direct")
         assert cfg == "bf16_256x256x32_w8", (M, N, K, cfg)
@@ -56,7 +58,7 @@ def test_not_taken_when_k_is_short(oracle, monkeypatch):
 def test_ragged_k(oracle, K, monkeypatch):
     """K ranges that are not multiples of 128, of 64, of 32: the chunks beyond the end are masked, the loop
     runs on over zero-filled stages to the next multiple of four steps."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     _, _, _, cfg = run_case(oracle, "bf16", 256, 512, K, alpha=0.5, act="gelu_tanh", seed=K, lda=K + 8, plan="direct")
     assert cfg == "bf16_256x256x64_w4"
     _, _, _, cfg = run_case(oracle, "bf16", 264, 248, K, alpha=-0.5, seed=K + 1, plan="direct")
@@ -73,7 +75,7 @@ def test_ragged_k(oracle, K, monkeypatch):
 def test_plain_operator_ragged_tiles(oracle, M, N, monkeypatch):
     """Tiles hanging over M, N or both (rows and column chunks beyond are never fetched, never stored):
     padded leading dimensions hold garbage and a canary that must survive."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     M8, N8 = (M + 7) // 8 * 8, (N + 7) // 8 * 8         # the direct-to-LDS kernels want N a multiple of 8; M is free
     for act, K in [("gelu_tanh", 256), ("relu", 640)]:
         _, _, _, cfg = run_case(oracle, "bf16", M, N8, K, alpha=0.5, act=act, seed=M + N + K, lda=K + 8, ldb=N8 + 16,
@@ -86,7 +88,7 @@ def test_plain_operator_ragged_tiles(oracle, M, N, monkeypatch):
 @pytest.mark.parametrize("transA,transB", [(False, False), (False, True), (True, True)])
 @pytest.mark.parametrize("out", ["f32", "bf16"])
 def test_widened_operator_ragged_tiles(oracle, transA, transB, out, monkeypatch):
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     for M, N, K, pad in [(520, 264, 256, (8, 8, 8, 8)), (200, 776, 384, (0, 16, 0, 8)), (264, 8, 256, (0, 0, 0, 0))]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, with_row_scale=True,
                                       residual="bf16" if out == "f32" else "f32", beta=-0.5, act="relu", clamp=(0.0, 2.0),
@@ -97,7 +99,7 @@ def test_widened_operator_ragged_tiles(oracle, transA, transB, out, monkeypatch)
 def test_split_k(oracle, monkeypatch):
     """Partial tiles from the four-wave kernel, reduced in slice order: matches the oracle, repeats
     bit for bit; slice lengths that are not multiples of 128 take the edge variant, short ones eight waves."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     got1, _, _, cfg = run_case(oracle, "bf16", 256, 512, 2048, alpha=0.125, act="gelu_tanh", seed=41, plan="splitk", split_k=4)
     assert cfg == "bf16_256x256x64_w4_splitk"
     got2, _, _, _ = run_case(oracle, "bf16", 256, 512, 2048, alpha=0.125, act="gelu_tanh", seed=41, plan="splitk", split_k=4)
@@ -113,7 +115,7 @@ def test_split_k(oracle, monkeypatch):
 @pytest.mark.parametrize("transA,transB", LAYOUTS)
 @pytest.mark.parametrize("out", ["f32", "bf16"])
 def test_widened_operator_layouts(oracle, transA, transB, out, monkeypatch):
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     name = f"bf16_fused_256x256x64_w4_{NAME[transA, transB]}"
     if transA and not transB:       # both operands in whole lines already: stays on eight waves
         name = "bf16_fused_256x256x32_w8_tn"
@@ -127,7 +129,7 @@ def test_widened_operator_layouts(oracle, transA, transB, out, monkeypatch):
 @pytest.mark.parametrize("residual,out", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32"), ("f32", "bf16")])
 def test_widened_operator_chain(oracle, residual, out, monkeypatch):
     """Row scale, bias, residual (aligned and, with a padded ldr, unaligned rows), relu, clamp."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     for pad in [(0, 0, 0, 0), (0, 8, 3 if out == "f32" else 8, 0)]:
         _, _, _, cfg = run_fused_case(oracle, 256, 512, 640, transB=True, alpha=0.25, with_row_scale=True,
                                       residual=residual, beta=-0.5, act="relu", clamp=(0.0, 1.5), out=out, pad=pad,
@@ -136,7 +138,7 @@ def test_widened_operator_chain(oracle, residual, out, monkeypatch):
 
 
 def test_widened_operator_batched_and_split(oracle, monkeypatch):
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 384, batch=3, transA=True, transB=True, act="relu", out="bf16",
                                   plan="direct", seed=51)
     assert cfg == "bf16_fused_256x256x64_w4_tt"
@@ -148,7 +150,7 @@ def test_widened_operator_batched_and_split(oracle, monkeypatch):
 @pytest.mark.parametrize("structure", ["lower", "upper"])
 def test_triangular_a(oracle, structure, monkeypatch):
     """Per-tile-row K ranges (multiples of 256): the shortest is one pass of the loop body."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     got_h, _, _, cfg = run_fused_case(oracle, 768, 256, 768, act="relu", a_structure=structure, hint=True, plan="direct", seed=61)
     assert cfg == "bf16_fused_256x256x64_w4_nn"
     got_g, _, _, _ = run_fused_case(oracle, 768, 256, 768, act="relu", a_structure=structure, hint=False, plan="direct", seed=61)

@@ -7,6 +7,8 @@ import os
 import numpy as np
 import pytest
 
+from paper_2604_01489_amd import binding
+
 from gpu_util import run_case, run_fused_case
 
 pytestmark = pytest.mark.gpu
@@ -28,8 +30,8 @@ def stage_k(transA, transB, shared_cu=True):
 def test_layouts_tile_256(oracle, transA, transB, monkeypatch):
     """Full and ragged tiles, several K tiles (ring) and few (one load phase); leading dimensions padded.
     (The 256 x 256 kernel is forced: by the planning rule so few tiles go to the 128 x 128 kernel.)"""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
-    monkeypatch.setenv("GE_WAVES", "8")         # the four-wave kernel has its own tests
+    binding.set_option("force_config", "256x256")
+    binding.set_option("waves", "8")         # the four-wave kernel has its own tests
     for M, N, K, pad in [(256, 256, 64, (0, 0, 0, 0)), (512, 768, 256, (8, 16, 0, 4)), (520, 776, 328, (24, 8, 0, 0))]:
         _, _, _, cfg = run_fused_case(oracle, M, N, K, transA=transA, transB=transB, alpha=0.5, act="gelu_tanh",
                                       with_row_scale=True, pad=pad, seed=M + K + 2 * transA + transB)
@@ -134,17 +136,17 @@ def test_split_k(oracle, transA, transB, monkeypatch):
                                   with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
                                   plan="splitk", split_k=0, seed=41)
     assert cfg == f"bf16_fused_128x128x{stage_k(transA, transB, shared_cu=False)}_w4_{NAME[transA, transB]}_splitk"
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
-    monkeypatch.setenv("GE_WAVES", "8")         # the four-wave kernel has its own tests
+    binding.set_option("force_config", "256x256")
+    binding.set_option("waves", "8")         # the four-wave kernel has its own tests
     _, _, _, cfg = run_fused_case(oracle, 256, 256, 4096, transA=transA, transB=transB, alpha=1.0 / 64, act="gelu_tanh",
                                   with_row_scale=True, residual="f32", clamp=(-1.0, 1.0), out="bf16",
                                   plan="splitk", split_k=0, seed=41)
     assert cfg == f"bf16_fused_256x256x{stage_k(transA, transB)}_w8_{NAME[transA, transB]}_splitk"
-    monkeypatch.delenv("GE_WAVES")
+    binding.set_option("waves", None)
     _, _, _, cfg = run_fused_case(oracle, 130, 70, 1500, transA=transA, transB=transB, alpha=1.0 / 32,
                                   with_row_scale=True, plan="splitk", split_k=3, seed=42)
     assert cfg == f"bf16_fused_generic_64x64x32_{NAME[transA, transB]}_splitk"
-    monkeypatch.delenv("GE_FORCE_CONFIG")
+    binding.set_option("force_config", None)
 
 
 def test_plain_operator_is_the_special_case(oracle):

@@ -4,6 +4,8 @@ replay is checked against the eager result, with eager work and synchronisations
 import numpy as np
 import pytest
 
+from paper_2604_01489_amd import binding
+
 pytestmark = pytest.mark.gpu
 
 
@@ -14,7 +16,7 @@ def test_calls_replay_from_a_captured_graph(force, monkeypatch):
     import torch
     from paper_2604_01489_amd import binding, inputs as gen
     if force:
-        monkeypatch.setenv("GE_FORCE_CONFIG", force)
+        binding.set_option("force_config", force)
     dev = torch.device("cuda:0")
     M, N, K = 512, 512, 256
     A = torch.from_numpy(gen.to_bf16_bits(gen.normal(70, 0, M * K, K ** -0.5).reshape(M, K)).view(np.int16)).to(dev)

@@ -5,6 +5,8 @@ a failure names a reproducible case (each case prints its arguments before it ru
 import numpy as np
 import pytest
 
+from paper_2604_01489_amd import binding
+
 from gpu_util import run_case, run_fused_case
 from test_gpu_conv import run_conv_case
 
@@ -74,7 +76,7 @@ def test_convolution_sweep(oracle, chunk):
 def test_four_wave_sweep(oracle, chunk, monkeypatch):
     """256 x 256 tiles, full or ragged, over K ranges of 256 and more, the tile forced: the shapes the four-wave
     kernel takes, with every storage, consumer chain, output type, padding, batch and K slicing drawn at random."""
-    monkeypatch.setenv("GE_FORCE_CONFIG", "256x256")
+    binding.set_option("force_config", "256x256")
     rng = np.random.default_rng(7000 + chunk)
     seen = set()
     for i in range(8):

@@ -18,14 +18,65 @@ def lib():
     return binding.load()
 
 
+def declared_in(header_file):
+    text = open(os.path.join(ROOT, "include", header_file)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return set(re.findall(r"\b(ge_\w+|gemm_epilogue\w*|conv2d_epilogue\w*|gemm_rowsum\w*)\s*\(", text))
+
+
 def test_exports_every_declared_symbol(lib):
-    inc = os.path.join(ROOT, "include")
-    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(ge\w*|gemm_epilogue\w*|conv2d_epilogue\w*|gemm_rowsum\w*)\s*\(", header))
+    """Each header against the library that implements it: the operator, and the measurement probes."""
+    assert sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")) == ["ge_probes.h", "gemm_epilogue.h"]
+    declared = declared_in("gemm_epilogue.h")
     assert declared == set(binding.SYMBOLS), declared ^ set(binding.SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
+    probes = binding.load_probes()
+    declared = declared_in("ge_probes.h")
+    assert declared == set(binding.PROBE_SYMBOLS), declared ^ set(binding.PROBE_SYMBOLS)
+    for name in declared:
+        assert getattr(probes, name) is not None
+        assert not hasattr(lib, name), f"{name} belongs to the probes library, not to the operator's"
+
+
+def test_options_are_validated_and_restorable(lib):
+    """ge_set_option: known names and values only; NULL restores the default."""
+    assert lib.ge_set_option(None, b"8") == 1
+    assert lib.ge_set_option(b"no_such_switch", b"1") == 8
+    assert lib.ge_set_option(b"force_config", b"512x512") == 8
+    assert lib.ge_set_option(b"waves", b"16") == 8 and lib.ge_set_option(b"stage_k", b"48") == 8
+    try:
+        # the switch changes the plan the host-side queries report
+        assert binding.auto_split_k(2048, 2048, 2048) == 1
+        binding.set_option("force_config", "256x256")
+        forced = binding.auto_split_k(2048, 2048, 2048)
+        binding.set_option("force_config", None)
+        assert binding.auto_split_k(2048, 2048, 2048) == 1
+        assert forced >= 1
+        for name, value in (("force_config", "128x128"), ("force_config", "generic"), ("waves", "8"), ("waves", "4"),
+                            ("stage_k", "32"), ("stage_k", "64")):
+            binding.set_option(name, value)
+    finally:
+        for name in ("force_config", "waves", "stage_k"):
+            binding.set_option(name, None)
+
+
+def test_conv_workspace_query(lib):
+    """Host only: a late layer (few output tiles, long K) is split over K and says how many bytes its
+    partial results take; an early layer runs in one pass; invalid sizes report 0."""
+    late = binding.conv_args((32, 7, 7, 512, 512, 3, 3), P, P, P, pad=(1, 1), y_type="bf16")
+    early = binding.conv_args((32, 56, 56, 256, 256, 3, 3), P, P, P, pad=(1, 1), y_type="bf16")
+    bad = binding.conv_args((32, 7, 7, 0, 512, 3, 3), P, P, P)
+    n = binding.conv_workspace_bytes(late)
+    assert n > 0 and n % (32 * 7 * 7 * 512 * 4) == 0
+    assert binding.conv_workspace_bytes(early) == 0 and binding.conv_workspace_bytes(bad) == 0
+    # a workspace that is too small or misaligned is refused before anything is enqueued
+    small = binding.conv_args((32, 7, 7, 512, 512, 3, 3), P, P, P, pad=(1, 1), y_type="bf16", workspace_ptr=P,
+                              workspace_bytes=n - 1)
+    assert binding.raw_conv(small) == 6
+    odd = binding.conv_args((32, 7, 7, 512, 512, 3, 3), P, P, P, pad=(1, 1), y_type="bf16", workspace_ptr=P + 16,
+                            workspace_bytes=n)
+    assert binding.raw_conv(odd) == 6
 
 
 def test_status_strings(lib):
