@@ -135,6 +135,30 @@ ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K,
                                   void *stream);
 
 /*
+ * gemm_epilogue_bf16_ex for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same operator, same kernels and the same bits as gemm_epilogue_bf16_ex; split-K
+ * partials go to a fixed array of gemm_epilogue_static_scratch_bytes() = 64 MiB of device
+ * memory that is part of the library's code object (every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates and frees nothing, on the host
+ * side of the HIP runtime or on the device; the first call on a device only asks the
+ * runtime for the array's address.
+ *   A plan whose partial tiles (split_k * batch * M * N * 4 bytes) exceed the array
+ *   returns GE_ERR_WORKSPACE and enqueues nothing.
+ *   Every partial tile is written before it is read, so nothing has to be cleared between
+ *   calls; but all calls on one GPU share the one array: calls that overlap in time on
+ *   the same GPU (different streams, or replays of graphs in flight together) race.
+ * Errors: as gemm_epilogue_bf16_ex.
+ */
+ge_status_t gemm_epilogue_bf16_static(int M, int N, int K,
+                                      const uint16_t *A, int lda,
+                                      const uint16_t *B, int ldb,
+                                      const float *bias, float alpha, ge_act_t act,
+                                      float *C, int ldc, int batch,
+                                      ge_plan_t plan, int split_k, void *stream);
+size_t gemm_epilogue_static_scratch_bytes(void);
+
+/*
  * The widened operator (bf16 operands, fp32 accumulation):
  *
  *     P[b][m,n] = sum_{k<K} opA(A[b])[m,k] * opB(B[b])[k,n]

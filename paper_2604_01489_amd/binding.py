@@ -23,6 +23,7 @@ GE_OK = 0
 SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "gemm_epilogue_workspace_bytes", "gemm_epilogue_auto_split_k",
            "ge_release_workspace", "ge_status_string", "ge_last_config", "ge_set_option",
+           "gemm_epilogue_bf16_static", "gemm_epilogue_static_scratch_bytes",
            "gemm_epilogue_bf16_fused", "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16",
            "conv2d_epilogue_workspace_bytes", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16")
 PROBE_SYMBOLS = ("ge_probe_mfma_bf16", "ge_probe_store_f32", "ge_probe_stream_mix")
@@ -90,6 +91,10 @@ def load():
     lib.gemm_epilogue_f32.argtypes = common + [c_void]
     lib.gemm_epilogue_bf16_ex.restype = c_int
     lib.gemm_epilogue_bf16_ex.argtypes = common + [c_int, c_int, c_void, c_size, c_void]
+    lib.gemm_epilogue_bf16_static.restype = c_int
+    lib.gemm_epilogue_bf16_static.argtypes = common + [c_int, c_int, c_void]
+    lib.gemm_epilogue_static_scratch_bytes.restype = c_size
+    lib.gemm_epilogue_static_scratch_bytes.argtypes = []
     lib.gemm_epilogue_workspace_bytes.restype = c_size
     lib.gemm_epilogue_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int]
     lib.gemm_epilogue_auto_split_k.restype = c_int
@@ -225,6 +230,21 @@ def _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch, transA=False
     _require_extent(C, M, N, ldc, batch, "C")
     _require_extent(R, M, N, ldr, batch, "R")
     _require_extent(bias, 1, N, N, 1, "bias")
+
+
+def gemm_epilogue_bf16_static(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch=1,
+                              plan="auto", split_k=0, stream=None):
+    """``gemm_epilogue_bf16_ex`` for callers that cannot allocate: split-K partials go to the
+    library's fixed array of device memory (``static_scratch_bytes()``)."""
+    _require_device(A, B, C, bias)
+    _require_operands(M, N, K, A, lda, B, ldb, bias, C, ldc, batch)
+    _check(load().gemm_epilogue_bf16_static(M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(bias), alpha,
+                                            ACT[act], _ptr(C), ldc, batch, PLAN[plan], split_k,
+                                            _stream_handle(stream)))
+
+
+def static_scratch_bytes() -> int:
+    return int(load().gemm_epilogue_static_scratch_bytes())
 
 
 def workspace_bytes(M, N, K, batch=1, plan="auto", split_k=0) -> int:

@@ -380,6 +380,35 @@ ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint
     return GE_OK;
 }
 
+// ---- scratch for the entry point that allocates nothing -----------------------------------------
+// Partial tiles of gemm_epilogue_bf16_static live in this array, which every GPU the library runs
+// on holds, at its own address, until the process ends.  In host code the array's name is not a
+// device address: the address is asked for once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+void *g_static_scratch_ptr[kMaxDevices] = {};
+std::mutex g_static_scratch_mutex;
+
+}  // namespace ge_host
+
+static __device__ __align__(256) unsigned char scratch[ge_host::kStaticScratchBytes];
+
+namespace ge_host {
+
+ge_status_t static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GE_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (!g_static_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return GE_ERR_WORKSPACE;
+        g_static_scratch_ptr[dev] = ptr;
+    }
+    *out = g_static_scratch_ptr[dev];
+    return GE_OK;
+}
+
 }  // namespace ge_host
 
 using namespace ge_host;
@@ -401,6 +430,29 @@ ge_status_t gemm_epilogue_bf16_ex(int M, int N, int K, const uint16_t *A, int ld
     return run_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch, plan, split_k, workspace,
                     workspace_bytes, stream);
 }
+
+ge_status_t gemm_epilogue_bf16_static(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
+                                      const float *bias, float alpha, ge_act_t act, float *C, int ldc,
+                                      int batch, ge_plan_t plan, int split_k, void *stream)
+{
+    ge_status_t st = validate(M, N, K, A, lda, B, ldb, bias, (int)act, C, ldc, batch, 2);
+    if (st != GE_OK) return st;
+    Plan pl;
+    st = make_plan_bf16(M, N, K, batch, fast_path_ok(N, K, A, lda, B, ldb), plan, split_k, &pl);
+    if (st != GE_OK) return st;
+    void *ws = nullptr;
+    if (pl.splitK > 1) {
+        if (partial_bytes(M, N, batch, pl.splitK) > kStaticScratchBytes) return GE_ERR_WORKSPACE;
+        st = static_scratch(&ws);
+        if (st != GE_OK) return st;
+    }
+    // with a workspace in hand the common path neither allocates nor frees; every partial tile is
+    // written before the second pass reads it, so what an earlier call left in the array is never seen
+    return run_bf16(M, N, K, A, lda, B, ldb, bias, alpha, act, C, ldc, batch, plan, split_k, ws,
+                    ws ? kStaticScratchBytes : 0, stream);
+}
+
+size_t gemm_epilogue_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 ge_status_t gemm_epilogue_f32(int M, int N, int K, const float *A, int lda, const float *B, int ldb,
                               const float *bias, float alpha, ge_act_t act, float *C, int ldc,
