@@ -384,7 +384,10 @@ __device__ __forceinline__ void chain_and_park_t(const GemmParams &p, int b, f32
 // `lds` must hold BM*BN*2 bytes nobody reads any more; all NW waves of the block call this.
 // (tileRow, tileCol): row of this lane and first of its 4 columns in block (0, 0) of the wave
 // tile, relative to the block tile.
-template <int BM, int BN, int NW, int LDS_BYTES, int TM, int TN, bool EDGE>
+// NT: the row pieces leave with the non-temporal hint (C is not read back).  Measured at 8192^3 on the
+// four-wave kernel: 0.826 -> 0.811 ms; on the eight-wave kernel no gain (short-K batched shape, 8192^3
+// with A stored K x M) or a loss (3 x 3 convolution, 0.132 -> 0.135 ms), so only the former asks for it.
+template <int BM, int BN, int NW, int LDS_BYTES, int TM, int TN, bool EDGE, bool NT = false>
 __device__ __forceinline__ void fused_epilogue_bf16_through_lds(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], GE_LDS char *lds,
                                                        int m0, int n0, int tileRow, int tileCol, int w, int lane)
 {
@@ -412,7 +415,10 @@ __device__ __forceinline__ void fused_epilogue_bf16_through_lds(const GemmParams
         const int row = (it * NW + w) * ROWS_PER_INSTR + rowInGroup;
         const i32x4_t v = *(const GE_LDS i32x4_t *)(lds + row * PITCH + ((chunk ^ (row & (CHUNKS - 1))) << 4));
         const int m = m0 + row, n = n0 + chunk * 8;
-        if (!EDGE || (m < p.M && n < p.N)) *(i32x4_t *)(cBase + (long long)m * p.ldc + n) = v;
+        if (!EDGE || (m < p.M && n < p.N)) {
+            if (NT) __builtin_nontemporal_store(v, (i32x4_t *)(cBase + (long long)m * p.ldc + n));
+            else *(i32x4_t *)(cBase + (long long)m * p.ldc + n) = v;
+        }
     }
 }
 

@@ -295,7 +295,7 @@ gemm_bf16_w4_kernel(const GemmParams p)
     const int colLane = n0 + (waveE % 2) * T::WTN + (laneE & 15);
     if constexpr (FUSED) {
         if constexpr (OUTBF16) {
-            fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, EDGE>(
+            fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, EDGE, true>(
                 p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / 2) * T::WTM + (laneE & 15),
                 (waveE % 2) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
         } else {

@@ -14,6 +14,13 @@ using namespace ge_host;
 
 constexpr int kColChunkRows = 64;       // rows of the matrix one block of the column-sum pass adds up
 constexpr int kRowWaves = 16;           // waves of a block of the row pass (one staging of v per block)
+constexpr int kBlockRows = 8;           // rows a block of the wide row pass takes, all in flight at once
+constexpr int kBlockCols = kRowWaves * 64 * 8;   // columns its 1024 threads cover in one sweep
+
+// A streamed operand is read once and never again: the non-temporal hint keeps it from displacing
+// anything in the caches, and on this part a read-only stream measured 7.1 TB/s with it against
+// 6.3 TB/s without (sizes beyond the memory-side cache).
+__device__ inline ge::i32x4_t load_stream16(const void *p) { return __builtin_nontemporal_load((const ge::i32x4_t *)p); }
 
 __device__ inline float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -76,30 +83,98 @@ rows_dot_kernel(int R, int C, const uint16_t *__restrict__ X, long long ldx, con
     }
 }
 
+// The same for matrices whose rows can be read in 16-byte pieces (C a multiple of 8) and are at least
+// 512 columns wide: a block of 1024 threads is G groups of 16/G waves, each group takes kBlockRows
+// consecutive rows; a thread owns 8 consecutive columns per sweep of 8192/G columns, holds their v in
+// registers and has one 16-byte load per row in flight, all issued before the first is used.  Many
+// short-lived blocks that each ask for everything up front keep more of the memory system busy than few
+// long-lived waves that walk their own rows: measured on an 8192 x 8192 matrix beyond the
+// memory-side cache, 23 us against 33-37 us for the kernel above.  Per row: a fixed butterfly inside
+// each wave, then the wave sums of its group added in wave order.
+template <int G>
+__global__ void __launch_bounds__(kRowWaves * 64)
+rows_dot_wide_kernel(int R, int C, const uint16_t *__restrict__ X, long long ldx, const float *__restrict__ v,
+                     float scale, const float *__restrict__ add, float *__restrict__ out)
+{
+    constexpr int WG = kRowWaves / G;               // waves of a group
+    constexpr int SWEEP = WG * 64 * 8;              // columns a group covers in one sweep
+    __shared__ float part[G * kBlockRows][WG];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int g = w / WG, wg = w % WG;
+    const long long r0 = ((long long)blockIdx.x * G + g) * kBlockRows;
+    float acc[kBlockRows];
+#pragma unroll
+    for (int u = 0; u < kBlockRows; ++u) acc[u] = 0.0f;
+    for (int c0 = (wg * 64 + lane) * 8; c0 < C; c0 += SWEEP) {
+        ge::i32x4_t x[kBlockRows];
+#pragma unroll
+        for (int u = 0; u < kBlockRows; ++u) {
+            x[u] = ge::i32x4_t{0, 0, 0, 0};
+            if (r0 + u < R) x[u] = load_stream16(X + (r0 + u) * ldx + c0);
+        }
+        float vv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vv[e] = v != nullptr ? v[c0 + e] : 1.0f;
+#pragma unroll
+        for (int u = 0; u < kBlockRows; ++u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[u] = __builtin_fmaf(bf16_lo((unsigned)x[u][e]), vv[2 * e], acc[u]);
+                acc[u] = __builtin_fmaf(bf16_hi((unsigned)x[u][e]), vv[2 * e + 1], acc[u]);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kBlockRows; ++u) {
+        const float t = wave_sum(acc[u]);
+        if (lane == 0) part[g * kBlockRows + u][wg] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x < G * kBlockRows) {
+        const long long r = (long long)blockIdx.x * G * kBlockRows + threadIdx.x;      // rows of a block are consecutive
+        if (r < R) {
+            float t = 0.0f;
+#pragma unroll
+            for (int k = 0; k < WG; ++k) t += part[threadIdx.x][k];
+            out[r] = __builtin_fmaf(scale, t, add != nullptr ? add[0] : 0.0f);
+        }
+    }
+}
+
 // partial[chunk][c] = sum over the rows of chunk `chunk` (kColChunkRows rows, in row order) of X[r,c].
-// A thread owns 8 consecutive columns (16 bytes per row) when VEC, one column otherwise.
+// A thread owns 8 consecutive columns (16 bytes per row) when VEC, one column otherwise.  The loads of
+// 8 rows are issued together, ahead of their additions (left to the compiler's unrolling they went out
+// one by one behind a bounds test: 50 us for 8192 x 8192 against 23 us).
 template <bool VEC>
 __global__ void __launch_bounds__(256)
 cols_partial_kernel(int R, int C, const uint16_t *__restrict__ X, long long ldx, float *__restrict__ partial)
 {
-    constexpr int W = VEC ? 8 : 1;
+    constexpr int W = VEC ? 8 : 1, U = 8;
     const int c0 = (blockIdx.x * 256 + threadIdx.x) * W;
     if (c0 >= C) return;
     const int r0 = blockIdx.y * kColChunkRows, r1 = min(R, r0 + kColChunkRows);
     float acc[W];
 #pragma unroll
     for (int e = 0; e < W; ++e) acc[e] = 0.0f;
-#pragma unroll 8
-    for (int r = r0; r < r1; ++r) {
-        const uint16_t *row = X + (long long)r * ldx;
-        if (VEC && c0 + 8 <= C) {
-            const ge::i32x4_t x = *(const ge::i32x4_t *)(row + c0);
+    if (VEC && c0 + 8 <= C) {
+        for (int r = r0; r < r1; r += U) {
+            ge::i32x4_t x[U];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc[2 * e] += bf16_lo((unsigned)x[e]);
-                acc[2 * e + 1] += bf16_hi((unsigned)x[e]);
+            for (int u = 0; u < U; ++u) {
+                x[u] = ge::i32x4_t{0, 0, 0, 0};
+                if (r + u < r1) x[u] = load_stream16(X + (long long)(r + u) * ldx + c0);
             }
-        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[2 * e] += bf16_lo((unsigned)x[u][e]);
+                    acc[2 * e + 1] += bf16_hi((unsigned)x[u][e]);
+                }
+        }
+    } else {
+        for (int r = r0; r < r1; ++r) {
+            const uint16_t *row = X + (long long)r * ldx;
 #pragma unroll
             for (int e = 0; e < W; ++e)
                 if (c0 + e < C) acc[e] += bf16_lo((unsigned)row[c0 + e]);
@@ -123,8 +198,11 @@ __device__ inline void block_vector_sum(int n, const float *__restrict__ x, floa
     if (threadIdx.x == 0) out[0] = (part[0] + part[1]) + (part[2] + part[3]);
 }
 
-// s[c] = sum of the chunks' partial sums, in chunk order; the block past the last column block adds up
-// the bias into s[C]
+// s[c] = sum of the chunks' partial sums; the block past the last column block adds up the bias into
+// s[C].  A block covers 32 columns with 8 threads each: thread g of a column adds chunks g, g + 8, ...
+// in ascending order, then the 8 sums are added in the order of g (one thread per column over all
+// chunks left the pass at the latency of a chain of dependent loads: 10 us for 2 MB).
+constexpr int kFinishCols = 32, kFinishWays = 8;
 __global__ void __launch_bounds__(256)
 cols_finish_kernel(int C, int chunks, const float *__restrict__ partial, float *__restrict__ s, int nBias,
                    const float *__restrict__ bias)
@@ -133,12 +211,20 @@ cols_finish_kernel(int C, int chunks, const float *__restrict__ partial, float *
         block_vector_sum(nBias, bias, s + C);
         return;
     }
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
+    __shared__ float part[kFinishWays][kFinishCols];
+    const int g = threadIdx.x / kFinishCols, cl = threadIdx.x % kFinishCols;
+    const int c = blockIdx.x * kFinishCols + cl;
     float acc = 0.0f;
-#pragma unroll 8
-    for (int q = 0; q < chunks; ++q) acc += partial[(long long)q * C + c];
-    s[c] = acc;
+    if (c < C)
+        for (int q = g; q < chunks; q += kFinishWays) acc += partial[(long long)q * C + c];
+    part[g][cl] = acc;
+    __syncthreads();
+    if (g == 0 && c < C) {
+        float t = part[0][cl];
+#pragma unroll
+        for (int k = 1; k < kFinishWays; ++k) t += part[k][cl];
+        s[c] = t;
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -149,10 +235,28 @@ vector_sum_kernel(int n, const float *__restrict__ x, float *__restrict__ out)
 
 bool vec_ok(const void *base, long long ld) { return (((uintptr_t)base) & 15u) == 0 && ld % 8 == 0; }
 
+// The wide kernel needs rows in 16-byte pieces and enough columns to give most lanes of a wave one
+// (its narrowest sweep is 512 columns); the grid's block count must fit 31 bits.
+bool rows_wide(int R, int C, const void *X, long long ldx)
+{
+    return vec_ok(X, ldx) && C % 8 == 0 && C >= 384;
+}
+
 // rows of X times v (or ones), on `st`
 void launch_rows_dot(int R, int C, const uint16_t *X, long long ldx, const float *v, float scale, const float *add,
                      float *out, hipStream_t st)
 {
+    if (rows_wide(R, C, X, ldx)) {
+        // the narrowest sweep that covers a row, or the whole block per row
+        const dim3 threads(kRowWaves * 64);
+        auto blocks = [&](int G) { return dim3((unsigned)ceil_div(R, G * kBlockRows)); };
+        if (C <= kBlockCols / 16)     GE_LAUNCH(rows_dot_wide_kernel<16>, blocks(16), threads, 0, st, R, C, X, ldx, v, scale, add, out);
+        else if (C <= kBlockCols / 8) GE_LAUNCH(rows_dot_wide_kernel<8>, blocks(8), threads, 0, st, R, C, X, ldx, v, scale, add, out);
+        else if (C <= kBlockCols / 4) GE_LAUNCH(rows_dot_wide_kernel<4>, blocks(4), threads, 0, st, R, C, X, ldx, v, scale, add, out);
+        else if (C <= kBlockCols / 2) GE_LAUNCH(rows_dot_wide_kernel<2>, blocks(2), threads, 0, st, R, C, X, ldx, v, scale, add, out);
+        else                          GE_LAUNCH(rows_dot_wide_kernel<1>, blocks(1), threads, 0, st, R, C, X, ldx, v, scale, add, out);
+        return;
+    }
     const int stage = (v != nullptr && (size_t)C * sizeof(float) <= 48 * 1024) ? 1 : 0;
     const size_t lds = stage ? (size_t)C * sizeof(float) : 0;
     long long blocks = ((long long)R + kRowWaves - 1) / kRowWaves;
@@ -189,7 +293,7 @@ extern "C" ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, 
         const dim3 grid((unsigned)ceil_div(K, 256 * (vec ? 8 : 1)), (unsigned)chunks);
         if (vec) GE_LAUNCH(cols_partial_kernel<true>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
         else     GE_LAUNCH(cols_partial_kernel<false>, grid, dim3(256), 0, st, N, K, B, (long long)ldb, (float *)ws);
-        GE_LAUNCH(cols_finish_kernel, dim3((unsigned)ceil_div(K, 256) + 1), dim3(256), 0, st, K, chunks, (const float *)ws,
+        GE_LAUNCH(cols_finish_kernel, dim3((unsigned)ceil_div(K, kFinishCols) + 1), dim3(256), 0, st, K, chunks, (const float *)ws,
                            params, N, bias);
         g_last_config = "rowsum_params_cols";
     }
@@ -204,6 +308,6 @@ extern "C" ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda
     if (lda < K) return GE_ERR_LD;
     if ((((uintptr_t)A) & 1u) || (((uintptr_t)params) & 3u) || (((uintptr_t)y) & 3u)) return GE_ERR_ALIGN;
     launch_rows_dot(M, K, A, lda, params, alpha, params + K, y, (hipStream_t)stream);
-    g_last_config = vec_ok(A, lda) ? "rowsum_rows_vec8" : "rowsum_rows_generic";
+    g_last_config = rows_wide(M, K, A, lda) ? "rowsum_rows_wide" : vec_ok(A, lda) ? "rowsum_rows_vec8" : "rowsum_rows_generic";
     return ge_host::take_launch_error() == hipSuccess ? GE_OK : GE_ERR_LAUNCH;
 }

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 def run_conv_case(oracle, shape, *, stride=(1, 1), pad=(0, 0), dil=(1, 1), alpha=1.0, with_bias=True,
                   residual=None, beta=1.0, act="none", clamp=None, out="f32", seed=0, expect=None):
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     Nb, H, W, Cin, Cout, KH, KW = shape
     OH = oracle.conv_out_size(H, KH, stride[0], pad[0], dil[0])
     OW = oracle.conv_out_size(W, KW, stride[1], pad[1], dil[1])
@@ -110,7 +110,7 @@ def test_conv_split_k_for_few_tiles_and_long_k(oracle, monkeypatch):
     binding.set_option("force_config", None)
     # repeatable bit for bit
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     X = torch.from_numpy(gen.to_bf16_bits(gen.normal(43, 0, 8 * 8 * 512, 1.0).reshape(1, 8, 8, 512)).view(np.int16)).cuda()
     Wt = torch.from_numpy(gen.to_bf16_bits(gen.normal(43, 1, 256 * 9 * 512, 0.02).reshape(256, 3, 3, 512)).view(np.int16)).cuda()
     Y1 = torch.empty(1, 8, 8, 256, device="cuda")

@@ -164,7 +164,7 @@ def test_plain_operator_is_the_special_case(oracle):
 def test_diagonal_times_dense(oracle):
     """A = identity with a row scale: the row scaling diag(d) @ B as a special case of the operator."""
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     M, N = 256, 512
     dev = torch.device("cuda:0")
     B32 = gen.uniform(9, 1, M * N, -1.0, 1.0).reshape(M, N)
@@ -191,7 +191,7 @@ def test_diag_entry_point(oracle, M, N, batch, pad, act):
     """gemm_epilogue_diag_bf16 against the operator's definition with the dense matrix diag(d) as A
     (the fused oracle with A = I and row_scale = d, pinned to d[:, None] * B on the CPU)."""
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     dev = torch.device("cuda:0")
     ldb, ldc = N + pad[0], N + pad[1]
     Bb = gen.to_bf16_bits(gen.normal(50 + M, 1, batch * M * N, 1.0).reshape(batch, M, N))

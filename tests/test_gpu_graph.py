@@ -14,7 +14,7 @@ def test_calls_replay_from_a_captured_graph(force, monkeypatch):
     """As the planner routes them (128 x 128 tiles at these sizes) and with the 256 x 256 tile forced, which
     puts all three calls on the four-wave kernel (plain, partial tiles, bf16 output through LDS)."""
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     if force:
         binding.set_option("force_config", force)
     dev = torch.device("cuda:0")
@@ -66,7 +66,7 @@ def test_convolution_rowsum_and_structured_calls_replay_from_a_captured_graph():
     """The convolution, the row-sum pair (weights stored K x N: no workspace), the diagonal operand and a
     product with a promised triangular A: kernels only, so their capture replays bit for bit."""
     import torch
-    from paper_2604_01489_amd import binding, inputs as gen
+    from paper_2604_01489_amd import inputs as gen
     dev = torch.device("cuda:0")
 
     def bf16(seed, stream, shape, scale=1.0):

@@ -70,7 +70,20 @@ def test_rowsum_shapes(oracle, transB):
     cols = "rowsum_params_cols" if transB else "rowsum_params_rows"
     for M, N, K, pad in [(64, 48, 32, (0, 0)), (300, 520, 264, (8, 16)), (1024, 1032, 2048, (0, 0)), (33, 7, 13000, (0, 8))]:
         _, cfg_p, cfg_y = run_rowsum_case(oracle, M, N, K, transB=transB, alpha=0.5, pad=pad, seed=M + N)
-        assert cfg_p == cols and cfg_y == "rowsum_rows_vec8"
+        assert cfg_p == cols and cfg_y == ("rowsum_rows_wide" if K >= 384 else "rowsum_rows_vec8")
+
+
+@pytest.mark.parametrize("transB", [False, True])
+def test_rowsum_wide_rows(oracle, transB):
+    """Rows of 384 columns and more take the kernel in which a group of waves owns 8 rows and a block of
+    1024 threads 8 to 128 of them: every group width (sweeps of 512 ... 8192 columns), sweeps partly filled,
+    exactly one, two with a ragged second one, row counts that are no multiple of a block's rows, padded
+    leading dimensions; with B stored K x N and N wide the parameter pass takes it too (with no vector to
+    multiply by)."""
+    for M, N, K, pad in [(77, 40, 4096, (0, 0)), (8, 24, 8192, (16, 8)), (21, 16, 8192 + 520, (8, 0)), (16, 4104, 56, (0, 8)),
+                         (133, 8, 392, (0, 0)), (259, 8, 1016, (8, 0)), (70, 8, 2048, (0, 0)), (300, 8, 1032, (0, 0))]:
+        _, _, cfg_y = run_rowsum_case(oracle, M, N, K, transB=transB, alpha=0.5, pad=pad, seed=M + N + K)
+        assert cfg_y == ("rowsum_rows_wide" if K >= 384 else "rowsum_rows_vec8")
 
 
 @pytest.mark.parametrize("transB", [False, True])

@@ -197,9 +197,9 @@ def test_c12_rowsum_linear_full(oracle):
     binding.gemm_rowsum_params_bf16(w.N, w.K, dW, w.K, True, dbias, params)
     assert binding.last_config() == "rowsum_params_cols"
     binding.gemm_rowsum_bf16(w.M, w.K, dA, w.K, params, w.alpha, y)
-    assert binding.last_config() == "rowsum_rows_vec8"
+    assert binding.last_config() == "rowsum_rows_wide"
     torch.cuda.synchronize()
     rows = _sample_rows(w.M, 128)
     got = y[torch.from_numpy(rows).cuda()].cpu().numpy()[None, :, None]
     ref = oracle.gemm_rowsum(np.ascontiguousarray(A[rows]), np.ascontiguousarray(Wt.T), bias, w.alpha)[None, :, None]
-    compare(got, ref, "c12_rowsum_linear_8192 [rowsum_rows_vec8]")
+    compare(got, ref, "c12_rowsum_linear_8192 [rowsum_rows_wide]")
