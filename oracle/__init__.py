@@ -29,11 +29,14 @@ _FUSED_SRC = os.path.join(_HERE, "gemm_fused_oracle.c")
 _FUSED_LIB = os.path.join(_HERE, "libgemm_fused_oracle.so")
 _CONV_SRC = os.path.join(_HERE, "conv_oracle.c")
 _CONV_LIB = os.path.join(_HERE, "libconv_oracle.so")
+_SYMM_SRC = os.path.join(_HERE, "gemm_symm_oracle.c")
+_SYMM_LIB = os.path.join(_HERE, "libgemm_symm_oracle.so")
 OUT = {"f64": 0, "f32": 1, "bf16": 2}
 
 _lib = None
 _fused = None
 _conv = None
+_symm = None
 
 
 def compile_source(src: str, out: str) -> str:
@@ -47,7 +50,7 @@ def compile_source(src: str, out: str) -> str:
 def build(force: bool = False) -> str:
     """Compile the oracles that are missing or older than their source. Returns the path of the
     plain operator's library."""
-    for src, lib in ((_SRC, _LIB), (_FUSED_SRC, _FUSED_LIB), (_CONV_SRC, _CONV_LIB)):
+    for src, lib in ((_SRC, _LIB), (_FUSED_SRC, _FUSED_LIB), (_CONV_SRC, _CONV_LIB), (_SYMM_SRC, _SYMM_LIB)):
         if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
             compile_source(src, lib)
     return _LIB
@@ -225,6 +228,87 @@ def gemm_fused(M, N, K, A, B, *, batch=1, transA=False, transB=False, lda=None, 
         float(alpha), rs_p, bias_p, r_p, int(ldr), r_kind, float(beta),
         ACT[act], float(lo), float(hi), OUT[out],
         C.ctypes.data_as(ctypes.c_void_p), int(N))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return C.reshape(batch, M, N)
+
+
+# ---------------------------------------------------------------------------------------------
+# symmetric operand given by one stored triangle
+# ---------------------------------------------------------------------------------------------
+UPLO = {"lower": 0, "upper": 1}
+
+
+def _bind_symm(lib):
+    c = ctypes
+    lib.oracle_gemm_symm.restype = c.c_int
+    lib.oracle_gemm_symm.argtypes = [
+        c.c_int, c.c_int, c.c_int,
+        c.c_void_p, c.c_long, c.c_int, c.c_void_p, c.c_long, c.c_int, c.c_int,
+        c.c_double, c.c_void_p, c.c_void_p,
+        c.c_void_p, c.c_long, c.c_int, c.c_double,
+        c.c_int, c.c_double, c.c_double, c.c_int,
+        c.c_void_p, c.c_long]
+    return lib
+
+
+def use_symm_library(path: str | None) -> None:
+    """As ``use_library`` for the symmetric-operand oracle."""
+    global _symm
+    _symm = None if path is None else _bind_symm(ctypes.CDLL(path))
+
+
+def _load_symm():
+    global _symm
+    if _symm is None:
+        build()
+        _symm = _bind_symm(ctypes.CDLL(_SYMM_LIB))
+    return _symm
+
+
+def gemm_symm(M, N, A, B, *, uplo="lower", batch=1, transB=False, lda=None, ldb=None, alpha=1.0,
+              row_scale=None, bias=None, residual=None, ldr=None, beta=1.0, act="none", clamp=None, out="f64"):
+    """Reference for the widened operator's chain on ``S @ opB(B)``, S the symmetric M x M matrix whose
+    ``uplo`` triangle is stored in ``A`` (M x lda per batch); the other triangle of ``A`` is never read.
+    ``B`` is M x ldb (K = M) or, with ``transB``, N x ldb.  Dtypes and the remaining arguments as for
+    ``gemm_fused``.  Returns fp64 values of shape [batch, M, N]."""
+    lib = _load_symm()
+    A = np.ascontiguousarray(A).ravel()
+    B = np.ascontiguousarray(B).ravel()
+    if A.dtype != B.dtype or A.dtype not in _KIND:
+        raise TypeError("A and B must share a dtype among float64, float32, uint16(bf16 bits)")
+    lda = M if lda is None else lda
+    ldb = (M if transB else N) if ldb is None else ldb
+    if A.size < batch * M * lda or B.size < batch * (N if transB else M) * ldb:
+        raise ValueError("operand buffer too small")
+
+    def vec(x, n, name):
+        if x is None:
+            return None, None
+        v = np.ascontiguousarray(np.asarray(x), dtype=np.float64)
+        if v.shape != (n,):
+            raise ValueError(f"{name} must have length {n}")
+        return v, v.ctypes.data_as(ctypes.c_void_p)
+
+    rs_keep, rs_p = vec(row_scale, M, "row_scale")
+    bias_keep, bias_p = vec(bias, N, "bias")
+    if residual is not None:
+        R = np.ascontiguousarray(residual).ravel()
+        if R.dtype not in _KIND:
+            raise TypeError("residual dtype")
+        ldr = N if ldr is None else ldr
+        if R.size < batch * M * ldr:
+            raise ValueError("residual buffer too small")
+        r_p, r_kind = R.ctypes.data_as(ctypes.c_void_p), _KIND[R.dtype]
+    else:
+        r_p, r_kind, ldr = None, 0, 0
+    lo, hi = (-np.inf, np.inf) if clamp is None else clamp
+    C = np.full(batch * M * N, np.nan, dtype=np.float64)
+    rc = lib.oracle_gemm_symm(
+        int(M), int(N), int(batch), A.ctypes.data_as(ctypes.c_void_p), int(lda), UPLO[uplo],
+        B.ctypes.data_as(ctypes.c_void_p), int(ldb), int(bool(transB)), _KIND[A.dtype],
+        float(alpha), rs_p, bias_p, r_p, int(ldr), r_kind, float(beta),
+        ACT[act], float(lo), float(hi), OUT[out], C.ctypes.data_as(ctypes.c_void_p), int(N))
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return C.reshape(batch, M, N)
