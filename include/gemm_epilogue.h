@@ -202,6 +202,18 @@ size_t gemm_epilogue_static_scratch_bytes(void);
  *                     the K ranges in which a whole tile row of A is zero (about half the
  *                     multiply-adds of a square product).  With a false promise the skipped
  *                     terms are missing from the result.  Not with GE_PLAN_SPLITK.
+ *                     GE_A_SYM_LOWER / GE_A_SYM_UPPER (same prompt: a symmetric operand's reads can be
+ *                     reduced): A is a symmetric K x K matrix (M == K, transA == 0) GIVEN BY ONE
+ *                     TRIANGLE of the array: S[m,k] = A[m*lda + k] for k <= m (lower; k >= m for upper)
+ *                     and S[m,k] = S[k,m] otherwise; the operator is computed with S in place of
+ *                     opA(A).  No element of the other triangle enters the result, whatever it holds
+ *                     (the array must still be allocated in full: M rows of lda).  With N <= 32, M >= 512 a
+ *                     multiple of 8, A 16-byte aligned and lda a multiple of 8 every element of the
+ *                     stored triangle is fetched from memory once (the product is a stream of A there, so
+ *                     that halves its time: a kernel of its own, whose partial results go to the
+ *                     workspace, gemm_epilogue_fused_workspace_bytes of it); any other legal argument list
+ *                     takes the guarded kernel with the same result contract.  plan and split_k are
+ *                     honoured by the guarded kernel only.
  * Batches are packed: A advances by (transA ? K : M)*lda elements, B by
  * (transB ? N : K)*ldb, R by M*ldr, C by M*ldc.  C must not overlap any input.
  *
@@ -213,7 +225,7 @@ size_t gemm_epilogue_static_scratch_bytes(void);
  * Errors: as gemm_epilogue_bf16, plus GE_ERR_EPILOGUE.
  */
 typedef enum { GE_DTYPE_F32 = 0, GE_DTYPE_BF16 = 1 } ge_dtype_t;
-typedef enum { GE_A_GENERAL = 0, GE_A_LOWER = 1, GE_A_UPPER = 2 } ge_structure_t;
+typedef enum { GE_A_GENERAL = 0, GE_A_LOWER = 1, GE_A_UPPER = 2, GE_A_SYM_LOWER = 3, GE_A_SYM_UPPER = 4 } ge_structure_t;
 
 typedef struct ge_fused_args {
     int M, N, K, batch;
@@ -232,6 +244,11 @@ typedef struct ge_fused_args {
 } ge_fused_args_t;
 
 ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream);
+
+/* Bytes of workspace gemm_epilogue_bf16_fused needs for these arguments (0 when it runs in one
+ * pass, or when the arguments are not valid).  Reads sizes, flags and the alignment of the pointers
+ * only.  Host only. */
+size_t gemm_epilogue_fused_workspace_bytes(const ge_fused_args_t *args);
 
 /*
  * Convolution front-end of the fused operator (bf16 operands, fp32 accumulation), channels-last:
@@ -344,6 +361,12 @@ ge_status_t gemm_epilogue_diag_bf16(int M, int N, const float *d,
  */
 ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, int ldb, int transB,
                                     const float *bias, float *params, void *stream);
+/* The same with a caller's workspace (256-byte aligned, at least gemm_rowsum_params_workspace_bytes(N, K,
+ * transB) bytes, which is 0 for transB == 0): never allocates.  workspace == NULL selects the library's. */
+ge_status_t gemm_rowsum_params_bf16_ex(int N, int K, const uint16_t *B, int ldb, int transB,
+                                       const float *bias, float *params,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+size_t gemm_rowsum_params_workspace_bytes(int N, int K, int transB);
 ge_status_t gemm_rowsum_bf16(int M, int K, const uint16_t *A, int lda, const float *params,
                              float alpha, float *y, void *stream);
 

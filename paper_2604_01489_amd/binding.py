@@ -25,11 +25,12 @@ SYMBOLS = ("gemm_epilogue_bf16", "gemm_epilogue_f32", "gemm_epilogue_bf16_ex",
            "ge_release_workspace", "ge_status_string", "ge_last_config", "ge_set_option",
            "gemm_epilogue_bf16_static", "gemm_epilogue_static_scratch_bytes",
            "gemm_epilogue_bf16_fused", "gemm_epilogue_diag_bf16", "conv2d_epilogue_bf16",
-           "conv2d_epilogue_workspace_bytes", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16")
+           "conv2d_epilogue_workspace_bytes", "gemm_rowsum_params_bf16", "gemm_rowsum_bf16",
+           "gemm_epilogue_fused_workspace_bytes", "gemm_rowsum_params_bf16_ex", "gemm_rowsum_params_workspace_bytes")
 PROBE_SYMBOLS = ("ge_probe_mfma_bf16", "ge_probe_store_f32", "ge_probe_stream_mix")
 
 DTYPE = {"f32": 0, "bf16": 1}
-STRUCTURE = {"general": 0, "lower": 1, "upper": 2}
+STRUCTURE = {"general": 0, "lower": 1, "upper": 2, "sym_lower": 3, "sym_upper": 4}
 
 
 class FusedArgs(ctypes.Structure):
@@ -114,6 +115,12 @@ def load():
                                             c_void, c_int, c_int, c_void]
     lib.gemm_rowsum_params_bf16.restype = c_int
     lib.gemm_rowsum_params_bf16.argtypes = [c_int, c_int, c_void, c_int, c_int, c_void, c_void, c_void]
+    lib.gemm_rowsum_params_bf16_ex.restype = c_int
+    lib.gemm_rowsum_params_bf16_ex.argtypes = [c_int, c_int, c_void, c_int, c_int, c_void, c_void, c_void, c_size, c_void]
+    lib.gemm_rowsum_params_workspace_bytes.restype = c_size
+    lib.gemm_rowsum_params_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.gemm_epilogue_fused_workspace_bytes.restype = c_size
+    lib.gemm_epilogue_fused_workspace_bytes.argtypes = [ctypes.POINTER(FusedArgs)]
     lib.gemm_rowsum_bf16.restype = c_int
     lib.gemm_rowsum_bf16.argtypes = [c_int, c_int, c_void, c_int, c_void, c_float, c_void, c_void]
     lib.conv2d_epilogue_workspace_bytes.restype = c_size
@@ -274,6 +281,10 @@ def fused_args(M, N, K, A_ptr, lda, B_ptr, ldb, C_ptr, ldc, *, batch=1, transA=F
                      STRUCTURE[a_structure] if isinstance(a_structure, str) else int(a_structure))
 
 
+def fused_workspace_bytes(args: FusedArgs) -> int:
+    return int(load().gemm_epilogue_fused_workspace_bytes(ctypes.byref(args)))
+
+
 def raw_fused(args: FusedArgs, stream_handle=None) -> int:
     """The status code of ``gemm_epilogue_bf16_fused`` (for argument-error tests)."""
     return int(load().gemm_epilogue_bf16_fused(ctypes.byref(args), stream_handle))
@@ -356,12 +367,19 @@ def raw_diag(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch) -
     return int(load().gemm_epilogue_diag_bf16(M, N, d_ptr, B_ptr, ldb, bias_ptr, alpha, act, C_ptr, ldc, batch, None))
 
 
-def gemm_rowsum_params_bf16(N, K, B, ldb, transB, bias, params, stream=None):
+def gemm_rowsum_params_bf16(N, K, B, ldb, transB, bias, params, workspace=None, stream=None):
     """``params[k] = sum_n opB(B)[k, n]`` for k < K, ``params[K] = sum(bias)``: the parameter-only part of
     the row sum of a linear layer, on device tensors."""
-    _require_device(B, bias, params)
-    _check(load().gemm_rowsum_params_bf16(N, K, _ptr(B), ldb, int(bool(transB)), _ptr(bias), _ptr(params),
-                                          _stream_handle(stream)))
+    _require_device(B, bias, params, workspace)
+    _require_extent(B, N if transB else K, K if transB else N, ldb, 1, "B")
+    _require_extent(params, 1, K + 1, K + 1, 1, "params")
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().gemm_rowsum_params_bf16_ex(N, K, _ptr(B), ldb, int(bool(transB)), _ptr(bias), _ptr(params),
+                                             _ptr(workspace), ws_bytes, _stream_handle(stream)))
+
+
+def rowsum_params_workspace_bytes(N, K, transB) -> int:
+    return int(load().gemm_rowsum_params_workspace_bytes(N, K, int(bool(transB))))
 
 
 def gemm_rowsum_bf16(M, K, A, lda, params, alpha, y, stream=None):

@@ -57,7 +57,9 @@ struct GemmParams {
     int triA;                  // TRI_LOWER / TRI_UPPER: opA(A) is promised triangular (0: nothing known)
 };
 
-enum { TRI_NONE = 0, TRI_LOWER = 1, TRI_UPPER = 2 };
+// TRI_SYM_*: A is symmetric and given by that triangle of the array (the guarded kernel mirrors the
+// index of an element of the other one; the main kernels do not take such calls)
+enum { TRI_NONE = 0, TRI_LOWER = 1, TRI_UPPER = 2, TRI_SYM_LOWER = 3, TRI_SYM_UPPER = 4 };
 
 // The K range of a block whose tile covers rows [m0, m0 + BM) when opA(A) is promised triangular:
 // a lower-triangular A is zero for k > m, so nothing beyond k = m0 + BM - 1 contributes; an
@@ -90,7 +92,7 @@ __device__ inline TileCoord map_block(const GemmParams &p, unsigned bid)
     TileCoord c;
     c.b = (int)(rest % (unsigned)p.batch);
     c.s = (int)(rest / (unsigned)p.batch);
-    if (p.triA != TRI_NONE) {
+    if (p.triA == TRI_LOWER || p.triA == TRI_UPPER) {
         // Tiles of a triangular A differ in work by their tile row (the K range grows or shrinks
         // with it).  Walk the tiles in groups of four tile columns, every tile row of a group from
         // the longest K range to the shortest: each XCD's run of logical ids then holds the same mix

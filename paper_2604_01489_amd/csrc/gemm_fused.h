@@ -60,7 +60,11 @@ gemm_bf16_fused_generic_kernel(const GemmParams p)
             const int row = p.transA ? e % BM : e / BK, k = p.transA ? e / BM : e % BK;
             const int m = m0 + row, kk = k0 + k;
             uint16_t v = 0;
-            if (m < p.M && kk < kEnd) v = p.transA ? A[(long long)kk * p.lda + m] : A[(long long)m * p.lda + kk];
+            if (m < p.M && kk < kEnd) {
+                // a symmetric A given by one triangle: an element of the other triangle is its mirror image
+                const bool mirror = (p.triA == TRI_SYM_LOWER && kk > m) || (p.triA == TRI_SYM_UPPER && kk < m);
+                v = (p.transA != 0) != mirror ? A[(long long)kk * p.lda + m] : A[(long long)m * p.lda + kk];
+            }
             sA[row * LD + k] = v;
         }
 #pragma unroll

@@ -11,6 +11,7 @@
 #include "gemm_bf16_fast.h"
 #include "gemm_bf16_w4.h"
 #include "gemm_fused.h"
+#include "gemm_symm.h"
 #include "ge_host.h"
 
 namespace {
@@ -28,6 +29,8 @@ void set_config(const char *kernel, int transA, int transB, bool splitk)
     g_last_config = g_config_buf;
 }
 
+bool is_symmetric(const ge_fused_args_t &a) { return a.a_structure == GE_A_SYM_LOWER || a.a_structure == GE_A_SYM_UPPER; }
+
 ge_status_t validate(const ge_fused_args_t &a)
 {
     if (!a.A || !a.B || !a.C) return GE_ERR_NULL;
@@ -36,8 +39,10 @@ ge_status_t validate(const ge_fused_args_t &a)
     if (a.R && a.ldr < a.N) return GE_ERR_LD;
     if (a.act != GE_ACT_NONE && a.act != GE_ACT_RELU && a.act != GE_ACT_GELU_TANH) return GE_ERR_ACT;
     if (a.c_type != GE_DTYPE_F32 && a.c_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
-    if (a.a_structure != GE_A_GENERAL && a.a_structure != GE_A_LOWER && a.a_structure != GE_A_UPPER) return GE_ERR_CONFIG;
-    if (a.a_structure != GE_A_GENERAL && a.plan == GE_PLAN_SPLITK) return GE_ERR_CONFIG;
+    if (a.a_structure < GE_A_GENERAL || a.a_structure > GE_A_SYM_UPPER) return GE_ERR_CONFIG;
+    if ((a.a_structure == GE_A_LOWER || a.a_structure == GE_A_UPPER) && a.plan == GE_PLAN_SPLITK) return GE_ERR_CONFIG;
+    if (is_symmetric(a) && a.transA) return GE_ERR_CONFIG;
+    if (is_symmetric(a) && a.M != a.K) return GE_ERR_SHAPE;
     if (a.R && a.r_type != GE_DTYPE_F32 && a.r_type != GE_DTYPE_BF16) return GE_ERR_EPILOGUE;
     if (!(a.clamp_lo <= a.clamp_hi)) return GE_ERR_EPILOGUE;
     const uintptr_t cMask = a.c_type == GE_DTYPE_F32 ? 3u : 1u, rMask = a.r_type == GE_DTYPE_F32 ? 3u : 1u;
@@ -145,7 +150,91 @@ void launch_four_wave(const GemmParams &p, bool raw, dim3 grid, hipStream_t st)
     else launch_four_wave_layout<EDGE, 1>(p, grid, st);
 }
 
+// ---- symmetric A given by one triangle, few output columns: every stored element fetched once -------
+struct SymmPlan {
+    bool fast;
+    int st, np, terms;
+    size_t bytes;           // partial results
+};
+
+SymmPlan plan_symm(const ge_fused_args_t &a)
+{
+    SymmPlan sp{};
+    sp.fast = a.N <= 32 && a.M >= 512 && (a.M % 8) == 0 && (a.lda % 8) == 0 && !(((uintptr_t)a.A) & 15u) &&
+              (long long)a.lda * 2 * ge_symm::SUB + 4096 < (1ll << 31) && opt_force_config() != FORCE_GENERIC;
+    if (!sp.fast) return sp;
+    // super-tiles of 512 once they give every CU a workgroup, else of 256
+    const long long t512 = ceil_div(a.M, 512);
+    sp.st = t512 * (t512 + 1) / 2 * a.batch >= kNumCU ? 512 : 256;
+    sp.np = a.N <= 16 ? 16 : 32;
+    sp.terms = ceil_div(a.M, sp.st);
+    sp.bytes = (size_t)sp.terms * (size_t)a.batch * (size_t)a.M * (size_t)a.N * sizeof(float);
+    const long long blocks = (long long)sp.terms * (sp.terms + 1) / 2;
+    if (blocks > 0x7fffffffll || a.batch > 65535) sp.fast = false;
+    return sp;
+}
+
+template <int ST, int NP>
+void launch_symm(const ge::SymmParams &sp, bool upper, dim3 grid, hipStream_t st)
+{
+    if (upper) GE_LAUNCH((ge::gemm_symm_bf16_kernel<ST, NP, true>), grid, dim3(256), 0, st, sp);
+    else       GE_LAUNCH((ge::gemm_symm_bf16_kernel<ST, NP, false>), grid, dim3(256), 0, st, sp);
+}
+
+// p: the launch parameters of the call as the second pass needs them (epilogue, C, sizes)
+ge_status_t run_symm(const ge_fused_args_t &a, const SymmPlan &plan, GemmParams p, hipStream_t hs)
+{
+    void *ws = nullptr;
+    ge_status_t st = acquire_workspace(plan.bytes, a.workspace, a.workspace_bytes, hs, &ws);
+    if (st != GE_OK) return st;
+    ge::SymmParams sp{};
+    sp.A = a.A; sp.B = a.B; sp.W = (float *)ws;
+    sp.M = a.M; sp.N = a.N; sp.lda = a.lda; sp.ldb = a.ldb;
+    sp.transB = a.transB ? 1 : 0;
+    sp.upper = a.a_structure == GE_A_SYM_UPPER ? 1 : 0;
+    sp.batch = a.batch;
+    sp.tiles = plan.terms;
+    sp.bVec = (!a.transB && (a.N % 8) == 0 && (a.ldb % 8) == 0 && !(((uintptr_t)a.B) & 15u)) ? 1 : 0;
+    sp.bytesA = 2 * (((long long)a.M - 1) * a.lda + a.M);
+    const dim3 grid((unsigned)((long long)plan.terms * (plan.terms + 1) / 2), (unsigned)a.batch);
+    const bool upper = sp.upper != 0;
+    if (plan.st == 512) {
+        if (plan.np == 16) launch_symm<512, 16>(sp, upper, grid, hs);
+        else               launch_symm<512, 32>(sp, upper, grid, hs);
+    } else {
+        if (plan.np == 16) launch_symm<256, 16>(sp, upper, grid, hs);
+        else               launch_symm<256, 32>(sp, upper, grid, hs);
+    }
+    if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
+    // the terms are the slices of the second pass: added in their order, then the consumer chain
+    p.splitK = plan.terms;
+    p.sliceStride = (long long)a.batch * a.M * a.N;
+    const long long total = (long long)a.batch * a.M * a.N;
+    long long blocks = (total + 255) / 256;
+    if (blocks > 16 * kNumCU) blocks = 16 * kNumCU;
+    GE_LAUNCH(ge::splitk_reduce_fused_kernel, dim3((unsigned)blocks), dim3(256), 0, hs, p, (const float *)ws);
+    if (ge_host::take_launch_error() != hipSuccess) return GE_ERR_LAUNCH;
+    std::snprintf(g_config_buf, sizeof g_config_buf, "bf16_symm_%s_%dx%d_n%d", upper ? "upper" : "lower", plan.st, plan.st, plan.np);
+    g_last_config = g_config_buf;
+    return GE_OK;
+}
+
 }  // namespace
+
+extern "C" size_t gemm_epilogue_fused_workspace_bytes(const ge_fused_args_t *args)
+{
+    if (!args || validate(*args) != GE_OK) return 0;
+    const ge_fused_args_t &a = *args;
+    if (is_symmetric(a)) {
+        const SymmPlan sp = plan_symm(a);
+        if (sp.fast) return sp.bytes;
+    }
+    Plan pl;
+    const bool triangular = a.a_structure == GE_A_LOWER || a.a_structure == GE_A_UPPER;
+    const bool fast = fast_ok(a) && !is_symmetric(a);
+    if (make_plan_bf16(a.M, a.N, a.K, a.batch, fast, triangular ? GE_PLAN_DIRECT : a.plan, a.split_k, &pl) != GE_OK) return 0;
+    return partial_bytes(a.M, a.N, a.batch, pl.splitK);
+}
 
 extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, void *stream)
 {
@@ -160,9 +249,12 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
         return run_bf16(a.M, a.N, a.K, a.A, a.lda, a.B, a.ldb, a.bias, a.alpha, a.act, (float *)a.C, a.ldc, a.batch, a.plan,
                         a.split_k, a.workspace, a.workspace_bytes, stream);
     Plan pl;
-    // a triangular A: every tile walks its own K range, in one pass (K slices would cut across them)
-    const ge_plan_t plan = a.a_structure != GE_A_GENERAL ? GE_PLAN_DIRECT : a.plan;
-    st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a), plan, a.split_k, &pl);
+    // a triangular A: every tile walks its own K range, in one pass (K slices would cut across them);
+    // a symmetric A given by one triangle: the guarded kernel (it mirrors indices element by element),
+    // unless the kernel for few output columns takes the call (below)
+    const bool triangular = a.a_structure == GE_A_LOWER || a.a_structure == GE_A_UPPER;
+    const ge_plan_t plan = triangular ? GE_PLAN_DIRECT : a.plan;
+    st = make_plan_bf16(a.M, a.N, a.K, a.batch, fast_ok(a) && !is_symmetric(a), plan, a.split_k, &pl);
     if (st != GE_OK) return st;
 
     GemmParams p{};
@@ -200,6 +292,11 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
     p.transA = a.transA ? 1 : 0;
     p.transB = a.transB ? 1 : 0;
     p.triA = (int)a.a_structure;
+
+    if (is_symmetric(a)) {
+        const SymmPlan sp = plan_symm(a);
+        if (sp.fast) return run_symm(a, sp, p, (hipStream_t)stream);
+    }
 
     const bool raw = pl.splitK > 1;
     void *ws = nullptr;

@@ -269,8 +269,21 @@ void launch_rows_dot(int R, int C, const uint16_t *X, long long ldx, const float
 
 }  // namespace
 
+extern "C" size_t gemm_rowsum_params_workspace_bytes(int N, int K, int transB)
+{
+    if (N < 1 || K < 1 || !transB) return 0;
+    return (size_t)ceil_div(N, kColChunkRows) * (size_t)K * sizeof(float);
+}
+
 extern "C" ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, int ldb, int transB,
                                                const float *bias, float *params, void *stream)
+{
+    return gemm_rowsum_params_bf16_ex(N, K, B, ldb, transB, bias, params, nullptr, 0, stream);
+}
+
+extern "C" ge_status_t gemm_rowsum_params_bf16_ex(int N, int K, const uint16_t *B, int ldb, int transB,
+                                                  const float *bias, float *params, void *workspace,
+                                                  size_t workspace_bytes, void *stream)
 {
     if (!B || !params) return GE_ERR_NULL;
     if (N < 1 || K < 1) return GE_ERR_SHAPE;
@@ -287,7 +300,7 @@ extern "C" ge_status_t gemm_rowsum_params_bf16(int N, int K, const uint16_t *B, 
         // B is stored N x K: s[k] is the sum of column k, in two passes through the workspace
         const int chunks = ceil_div(N, kColChunkRows);
         void *ws = nullptr;
-        const ge_status_t rc = acquire_workspace((size_t)chunks * (size_t)K * sizeof(float), nullptr, 0, st, &ws);
+        const ge_status_t rc = acquire_workspace((size_t)chunks * (size_t)K * sizeof(float), workspace, workspace_bytes, st, &ws);
         if (rc != GE_OK) return rc;
         const bool vec = vec_ok(B, ldb);
         const dim3 grid((unsigned)ceil_div(K, 256 * (vec ? 8 : 1)), (unsigned)chunks);

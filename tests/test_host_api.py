@@ -61,6 +61,23 @@ def test_options_are_validated_and_restorable(lib):
             binding.set_option(name, None)
 
 
+def test_symmetric_plan_and_workspace_queries(lib):
+    """Host only: a symmetric A with few output columns asks for the workspace of its partial results
+    (terms x batch x M x N floats); the same call with many columns runs in the guarded kernel, one pass."""
+    few = binding.fused_args(8192, 16, 8192, P, 8192, P, 16, P, 16, a_structure="sym_lower")
+    assert binding.fused_workspace_bytes(few) == 32 * 8192 * 16 * 4          # 32 rows of super-tiles of 256
+    big = binding.fused_args(16384, 8, 16384, P, 16384, P, 8, P, 8, batch=2, a_structure="sym_upper")
+    assert binding.fused_workspace_bytes(big) == 32 * 2 * 16384 * 8 * 4      # 32 rows of super-tiles of 512
+    many = binding.fused_args(1024, 64, 1024, P, 1024, P, 64, P, 64, a_structure="sym_lower", plan="direct")
+    assert binding.fused_workspace_bytes(many) == 0
+    assert binding.fused_workspace_bytes(binding.fused_args(1024, 8, 512, P, 1024, P, 8, P, 8, a_structure="sym_lower")) == 0
+    # the general split-K call answers as gemm_epilogue_workspace_bytes does
+    g = binding.fused_args(1024, 1024, 65536, P, 65536, P, 1024, P, 1024)
+    assert binding.fused_workspace_bytes(g) == binding.workspace_bytes(1024, 1024, 65536)
+    assert binding.rowsum_params_workspace_bytes(8192, 8192, True) == 128 * 8192 * 4
+    assert binding.rowsum_params_workspace_bytes(8192, 8192, False) == 0
+
+
 def test_conv_workspace_query(lib):
     """Host only: a late layer (few output tiles, long K) is split over K and says how many bytes its
     partial results take; an early layer runs in one pass; invalid sizes report 0."""
@@ -131,7 +148,7 @@ def test_fused_argument_errors_return_codes(lib):
     assert call(c_type=2) == 9
     assert call(plan=7) == 8
     # the promise about A: a known value, and never together with K slices
-    assert call(a_structure=3) == 8 and call(a_structure=-1) == 8
+    assert call(a_structure=5) == 8 and call(a_structure=-1) == 8
     assert call(a_structure="lower", plan="splitk") == 8 and call(a_structure="upper", plan="splitk", split_k=4) == 8
     # bf16 output only needs 2-byte alignment of C
     assert call(C_ptr=P + 2, c_type="bf16", plan=7) == 8

@@ -12,3 +12,15 @@ def test_lds_layout_model(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
     assert "layout checks passed" in res.stdout
+
+
+def test_symmetric_kernel_layout_model(tmp_path):
+    """The same for the symmetric-operand kernel (csrc/symm_layout.h): slab map, the image read along and
+    across its rows, the small operand's fragments, and the bookkeeping of super-tiles and terms."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "symm_layout_check")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-o", exe, os.path.join(root, "tests", "symm_layout_check.cpp")],
+                   check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    assert "symmetric layout checks passed" in res.stdout
