@@ -52,6 +52,7 @@ STREAM_MIX = {
     "c8_fused_batched_512x512x64_bf16out": (1, 4),
     "c9_diag_bf16_8192": (1, 2),
     "c12_rowsum_linear_8192": (1, 0),
+    "c14_symm_lower_16384_n16": (1, 0),
 }
 
 
@@ -257,6 +258,76 @@ def bench_diag(args, torch, binding, gen) -> int:
            "config": {"workload": args.workload, "M": M, "N": N, "batch": batch, "alpha": w.alpha, "act": w.act,
                       "bias": True, "out_dtype": "f32", "kernel": config_name},
            "roofline": roofline, "ceilings": ceilings, "dense_gemm": dense, "cpu_baseline": cpu_baseline, "parity": parity}
+    print(json.dumps(out))
+    return 0 if parity is None or parity["ok"] else 1
+
+
+def bench_symm(args, torch, binding, gen) -> int:
+    """A symmetric operand given by its lower triangle, few output columns: the call that fetches every
+    stored element once, with the general call on the same array (as a dense matrix) beside it."""
+    import oracle
+    w = gen.SYMM_WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    M, N = w.M, w.N
+    A, B, bias = gen.make_symm_inputs(w)
+    dA = torch.from_numpy(A.view(np.int16)).to(dev)
+    dB = torch.from_numpy(B.view(np.int16)).to(dev)
+    dbias = torch.from_numpy(bias).to(dev)
+    dC = torch.empty(M, N, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, warmup, steps):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    def step(structure="sym_lower"):
+        binding.gemm_epilogue_bf16_fused(M, N, M, dA, M, dB, N, dC, N, alpha=w.alpha, bias=dbias, act=w.act,
+                                         stream=stream, a_structure=structure)
+
+    ms_wall, ms_dev = timed(step, args.warmup, args.steps)
+    config_name = binding.last_config()
+    nbytes = gen.symm_algorithmic_bytes(w)
+    achieved = nbytes / (ms_dev * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": measured_traffic(args.workload, config_name),
+                "kernel": config_name, "ms_per_launch": round(ms_dev, 4)}
+    ceilings = None
+    if not args.no_ceilings:
+        ceilings = measured_ceilings(torch, binding, dA, stream, mix=(1, 0), mfma=False)
+        roofline["frac_of_measured"] = round(achieved / ceilings["stream_mix_gbs"], 4)
+    # the same array read as a dense matrix by the general call (a different product unless A is symmetric: for scale)
+    _, ms_general = timed(lambda: step("general"), 3, 10)
+    general = {"ms_per_launch": round(ms_general, 4), "kernel": binding.last_config(),
+               "speedup_of_the_structure": round(ms_general / ms_dev, 2)}
+    step()
+    torch.cuda.synchronize()
+    cpu_baseline = parity = None
+    if args.oracle_rows > 0:
+        got = dC.cpu().numpy().astype(np.float64)
+        c0 = time.perf_counter()
+        ref = oracle.gemm_symm(M, N, A, B, uplo="lower", alpha=w.alpha, bias=bias, act=w.act)[0]
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(nbytes / (c1 - c0) / 1e9, 6), "unit": "GB/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "sample": f"all {M} rows of C; {c1 - c0:.1f} s"}
+        err = np.abs(got - ref)
+        rel = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
+        parity = {"rows_checked": M, "rel_frobenius": rel, "max_abs_err": float(err.max()),
+                  "ok": bool(rel <= 1e-3 and np.all(err <= 1e-2 * np.maximum(1.0, np.abs(ref))))}
+    out = {"metric": "HBM GB/s of the product with a symmetric operand given by one triangle", "value": round(nbytes / (ms_wall * 1e-3) / 1e9, 1),
+           "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_wall, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "M": M, "N": N, "K": M, "alpha": w.alpha, "act": w.act, "bias": True,
+                      "a_structure": "sym_lower", "out_dtype": "f32", "kernel": config_name},
+           "roofline": roofline, "ceilings": ceilings, "general_call": general, "cpu_baseline": cpu_baseline, "parity": parity}
     print(json.dumps(out))
     return 0 if parity is None or parity["ok"] else 1
 
@@ -487,6 +558,8 @@ def main() -> int:
         return bench_conv(args, torch, binding, gen)
     if args.workload in gen.ROWSUM_WORKLOADS:
         return bench_rowsum(args, torch, binding, gen)
+    if args.workload in gen.SYMM_WORKLOADS:
+        return bench_symm(args, torch, binding, gen)
     fused = args.workload in gen.FUSED_WORKLOADS
     fw = gen.FUSED_WORKLOADS[args.workload] if fused else None
     w = fw.base if fused else gen.WORKLOADS[args.workload]

@@ -163,10 +163,20 @@ SymmPlan plan_symm(const ge_fused_args_t &a)
     sp.fast = a.N <= 32 && a.M >= 512 && (a.M % 8) == 0 && (a.lda % 8) == 0 && !(((uintptr_t)a.A) & 15u) &&
               (long long)a.lda * 2 * ge_symm::SUB + 4096 < (1ll << 31) && opt_force_config() != FORCE_GENERIC;
     if (!sp.fast) return sp;
-    // super-tiles of 512 once they give every CU a workgroup, else of 256
-    const long long t512 = ceil_div(a.M, 512);
-    sp.st = t512 * (t512 + 1) / 2 * a.batch >= kNumCU ? 512 : 256;
     sp.np = a.N <= 16 ? 16 : 32;
+    // The side of the super-tiles: wider ones write fewer partial results (8 N / ST bytes per byte of A) but
+    // make fewer workgroups, and what counts is the number of rounds those take on the CUs times the
+    // sub-tiles of one.  Estimated cost in sub-tile loads per CU, partial results included; ties go to the
+    // wider tile.  (768 with 32 columns does not fit the LDS.)
+    double best = 0.0;
+    for (int st : {768, 512, 256}) {
+        if (st == 768 && sp.np == 32) continue;
+        const long long t = ceil_div(a.M, st), blocks = t * (t + 1) / 2 * a.batch;
+        const long long rounds = (blocks + kNumCU - 1) / kNumCU;
+        const double ns = st / 128.0;
+        const double cost = (double)rounds * ns * ns * (1.0 + 8.0 * a.N / st);
+        if (best == 0.0 || cost < best) { best = cost; sp.st = st; }
+    }
     sp.terms = ceil_div(a.M, sp.st);
     sp.bytes = (size_t)sp.terms * (size_t)a.batch * (size_t)a.M * (size_t)a.N * sizeof(float);
     const long long blocks = (long long)sp.terms * (sp.terms + 1) / 2;
@@ -198,7 +208,9 @@ ge_status_t run_symm(const ge_fused_args_t &a, const SymmPlan &plan, GemmParams 
     sp.bytesA = 2 * (((long long)a.M - 1) * a.lda + a.M);
     const dim3 grid((unsigned)((long long)plan.terms * (plan.terms + 1) / 2), (unsigned)a.batch);
     const bool upper = sp.upper != 0;
-    if (plan.st == 512) {
+    if (plan.st == 768) {
+        launch_symm<768, 16>(sp, upper, grid, hs);
+    } else if (plan.st == 512) {
         if (plan.np == 16) launch_symm<512, 16>(sp, upper, grid, hs);
         else               launch_symm<512, 32>(sp, upper, grid, hs);
     } else {

@@ -40,7 +40,7 @@ __device__ __forceinline__ unsigned symm_mask_pair(unsigned w, bool keepLo, bool
     return w & ((keepLo ? 0x0000FFFFu : 0u) | (keepHi ? 0xFFFF0000u : 0u));
 }
 
-// ST: side of a super-tile (256 or 512); NP: columns of the small operand's image (16 or 32);
+// ST: side of a super-tile (a multiple of 128: 256, 512 or 768); NP: columns of the small operand's image (16 or 32);
 // UPPER: the upper triangle is the stored one.
 template <int ST, int NP, bool UPPER>
 __global__ void __launch_bounds__(256)
@@ -50,9 +50,11 @@ gemm_symm_bf16_kernel(const SymmParams p)
     constexpr int NS = ST / SUB;            // sub-tiles per side of a super-tile
     constexpr int NJ = NP / 16;             // 16-column blocks of the result
     constexpr int SMALL_BYTES = ST * NP * 2;
-    __shared__ __attribute__((aligned(1024))) char smem[2 * STAGE_BYTES + 2 * SMALL_BYTES];
+    // two sub-tiles on their way while one is multiplied, where the LDS has room for three stages (one otherwise)
+    constexpr int STAGES = 3 * STAGE_BYTES + 2 * SMALL_BYTES <= 152 * 1024 ? 3 : 2, AHEAD = STAGES - 1;
+    __shared__ __attribute__((aligned(1024))) char smem[STAGES * STAGE_BYTES + 2 * SMALL_BYTES];
     const unsigned ldsBase = (unsigned)(size_t)(GE_LDS char *)smem;
-    const unsigned smallJ = ldsBase + 2 * STAGE_BYTES;
+    const unsigned smallJ = ldsBase + STAGES * STAGE_BYTES;
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -72,7 +74,7 @@ gemm_symm_bf16_kernel(const SymmParams p)
     const uint16_t *gB = (const uint16_t *)p.B + (long long)b * (p.transB ? (long long)p.N * p.ldb : (long long)p.M * p.ldb);
 
     // ---- the blocks of the small operand: its rows (k) k0 .. k0 + ST - 1, zero beyond M and beyond N --------
-    auto stage_small = [&](unsigned dst, int k0) {
+    auto stage_small = [&](unsigned dst, int k0) __attribute__((always_inline)) {
         if (p.bVec) {
             for (int q = threadIdx.x; q < ST * (NP / 8); q += 256) {
                 const int kk = q / (NP / 8), n = (q % (NP / 8)) * 8;
@@ -92,7 +94,7 @@ gemm_symm_bf16_kernel(const SymmParams p)
     };
 
     // ---- loads of sub-tile (rs, cs) of the super-tile into stage st: 8 per wave ---------------------------
-    auto issue_sub = [&](int rs, int cs, int st) {
+    auto issue_sub = [&](int rs, int cs, int st) __attribute__((always_inline)) {
         const int r0 = I * ST + rs * SUB, c0 = J * ST + cs * SUB;
         const long long origin = ((long long)r0 * p.lda + c0) * 2;
         // a sub-tile wholly outside the matrix (a ragged last super-tile) goes through an empty resource
@@ -119,7 +121,7 @@ gemm_symm_bf16_kernel(const SymmParams p)
                 for (int r = 0; r < 4; ++r) { acc1[s][i][j][r] = 0.0f; acc2[s][i][j][r] = 0.0f; }
 
     // fragment of a small-operand image: the 32 k from kBase, column block j
-    auto small_frag = [&](unsigned img, int kBase, int j) {
+    auto small_frag = [&](unsigned img, int kBase, int j) __attribute__((always_inline)) {
         const GE_LDS char *p0 = (const GE_LDS char *)(size_t)(img + (unsigned)small_frag_offset(NP, kBase, j, lane, 0));
         const GE_LDS char *p1 = (const GE_LDS char *)(size_t)(img + (unsigned)small_frag_offset(NP, kBase, j, lane, 1));
         short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((GE_LDS short4_t *)p0);
@@ -127,10 +129,12 @@ gemm_symm_bf16_kernel(const SymmParams p)
         return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     };
 
+    // (Every lambda below is forced inline: called from dozens of unrolled places the large ones would
+    // otherwise stay functions, and the accumulator arrays they index would live in scratch memory.)
     // Sub-tile (rs, cs) from stage st: P1 into acc1[rs], P2 into acc2[cs].  onDiag: the sub-tile lies on the
     // diagonal of the matrix and the fragments are cleared of the other triangle.  (Called from fully
     // unrolled loops: rs, cs and onDiag are constants by then.)
-    auto multiply = [&](int rs, int cs, bool onDiag, int st) {
+    auto multiply = [&](int rs, int cs, bool onDiag, int st) __attribute__((always_inline)) {
         const unsigned img = ldsBase + (unsigned)(st * STAGE_BYTES);
 #pragma unroll
         for (int ks = 0; ks < SUB / 32; ++ks) {
@@ -184,46 +188,51 @@ gemm_symm_bf16_kernel(const SymmParams p)
         }
     };
 
-    // ---- the walk over the sub-tiles, the next one loading while this one is multiplied -------------------
+    // ---- the walk over the sub-tiles, two loading while one is multiplied --------------------------------
     // Off the diagonal every sub-tile of the super-tile, (u, v) = (row, column).  On it only those of the
     // stored triangle: v <= u with (row, column) = (u, v) for the lower, (v, u) for the upper triangle.
-    // Both loops are fully unrolled, so the accumulators are indexed by constants.
-    auto walk = [&](auto diagC) {
+    // Both loops are fully unrolled, so the accumulators are indexed by constants.  Per sub-tile t: its data
+    // have landed (the loads complete in order: all but those of t + 1) and every wave is past the multiply
+    // of t - 1 -- one barrier for both -- then the loads of t + AHEAD go into the stage t - 1 occupied.
+    auto walk = [&](auto diagC) __attribute__((always_inline)) {
         constexpr bool DIAG = decltype(diagC)::value;
-        int st = 0;
+        auto row_of = [](int u, int v) { return (DIAG && UPPER) ? v : u; };
+        auto col_of = [](int u, int v) { return (DIAG && UPPER) ? u : v; };
+        // (u, v) one step on; u == NS: past the end
+        auto step_u = [](int u, int v) { return (DIAG ? v == u : v == NS - 1) ? u + 1 : u; };
+        auto step_v = [](int u, int v) { return (DIAG ? v == u : v == NS - 1) ? 0 : v + 1; };
+        issue_sub(0, 0, 0);
+        if (AHEAD == 2 && step_u(0, 0) < NS) issue_sub(row_of(step_u(0, 0), step_v(0, 0)), col_of(step_u(0, 0), step_v(0, 0)), 1);
+        stage_small(smallJ, J * ST);
+        if (!DIAG) stage_small(smallI, I * ST);
+        int t = 0;
 #pragma unroll
         for (int u = 0; u < NS; ++u) {
 #pragma unroll
             for (int v = 0; v < NS; ++v) {
                 if (DIAG && v > u) continue;
-                const bool lastV = DIAG ? v == u : v == NS - 1;
-                const int nu = lastV ? u + 1 : u, nv = lastV ? 0 : v + 1;
-                if (nu < NS) {
-                    issue_sub((DIAG && UPPER) ? nv : nu, (DIAG && UPPER) ? nu : nv, st ^ 1);
-                    // this sub-tile has landed (the 8 loads just issued may still be on their way), the small
-                    // operand's images are written: visible to every wave after the barrier
-                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(SLABS / 4) : "memory");
-                } else {
-                    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                const int u1 = step_u(u, v), v1 = step_v(u, v);
+                const int u2 = u1 < NS ? step_u(u1, v1) : NS, v2 = u1 < NS ? step_v(u1, v1) : 0;
+                if (AHEAD == 2 && u1 < NS) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(SLABS / 4) : "memory");
+                else                       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                if (AHEAD == 2) {
+                    if (u2 < NS) issue_sub(row_of(u2, v2), col_of(u2, v2), (t + 2) % STAGES);
+                } else if (u1 < NS) {
+                    issue_sub(row_of(u1, v1), col_of(u1, v1), (t + 1) % STAGES);
                 }
-                multiply((DIAG && UPPER) ? v : u, (DIAG && UPPER) ? u : v, DIAG && u == v, st);
-                // every wave has read stage st before the loads of the next round refill it
-                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-                st ^= 1;
+                multiply(row_of(u, v), col_of(u, v), DIAG && u == v, t % STAGES);
+                ++t;
             }
         }
     };
 
-    issue_sub(0, 0, 0);
-    stage_small(smallJ, J * ST);
-    if (!diag) stage_small(smallI, I * ST);
     if (diag) walk(std::true_type{});
     else walk(std::false_type{});
 
     // ---- the terms: P1 is term J of row block I, P2 term I of row block J; on the diagonal their sum is
     // term I of row block I.  Register r of lane l: row 4 (l/16) + r, column l%16 of its 16 x 16 block.
     const long long slice = (long long)p.batch * p.M * p.N;
-    auto store_term = [&](f32x4_t (&acc)[NS][2][NJ], int rowBlock, int term) {
+    auto store_term = [&](f32x4_t (&acc)[NS][2][NJ], int rowBlock, int term) __attribute__((always_inline)) {
         float *dst = p.W + (long long)term * slice + (long long)b * p.M * p.N;
 #pragma unroll
         for (int s = 0; s < NS; ++s)

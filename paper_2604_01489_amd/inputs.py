@@ -295,6 +295,28 @@ DIAG_WORKLOADS = {
 
 
 # ---------------------------------------------------------------------------------------------
+# symmetric operand given by its lower triangle, few output columns (K = M): a stream of A
+# ---------------------------------------------------------------------------------------------
+SYMM_WORKLOADS = {
+    "c14_symm_lower_16384_n16": Workload("c14_symm_lower_16384_n16", "bf16", 16384, 16, 16384, 1, 14, "normal",
+                                         16384 ** -0.5, 0.5, (-0.1, 0.1), "relu"),
+}
+
+
+def make_symm_inputs(w: Workload):
+    """(A bf16 bits [M, M] drawn in full -- only its lower triangle is meant to be read --, B bf16 bits
+    [M, N] ~ N(0, 1), bias).  A ~ N(0, 1) * M^-1/2."""
+    A = make_operand(w, "A")[0]
+    B = to_bf16_bits(normal(w.seed, STREAM_B, w.K * w.N, 1.0).reshape(w.K, w.N))
+    return A, B, make_bias(w)
+
+
+def symm_algorithmic_bytes(w: Workload) -> float:
+    """Read the stored triangle of A, B and the bias once, write C (fp32) once."""
+    return float(w.M * (w.M + 1) // 2 * 2 + w.K * w.N * 2 + 4 * w.N + w.M * w.N * 4)
+
+
+# ---------------------------------------------------------------------------------------------
 # row sum of a linear layer: y = sum_n (alpha x W^T + b); W stored N x K as frameworks keep it
 # ---------------------------------------------------------------------------------------------
 ROWSUM_WORKLOADS = {

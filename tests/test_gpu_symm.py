@@ -104,13 +104,18 @@ def test_symm_chain_batches_and_storage_of_b(oracle, uplo):
     run_symm_case(oracle, 520, 8, uplo=uplo, pad=(0, 3, 0), workspace=True, seed=8)          # B rows not in 16-byte pieces
 
 
-def test_symm_many_super_tiles_of_512(oracle):
-    """Enough super-tiles of 512 to give every CU one: the wide super-tile is chosen (M = 12288: 24 rows of
-    super-tiles, 300 workgroups), ragged at 12296."""
+def test_symm_wide_super_tiles(oracle):
+    """Large matrices: the width of the super-tiles follows the number of rounds their workgroups take on
+    the CUs and the bytes of partial results (the library's own choice is asserted): 768 at 16384 with 16
+    columns (253 workgroups, one round), 512 with 32 columns there, 256 at 12288; ragged at 12296."""
+    _, cfg = run_symm_case(oracle, 16384, 16, act="relu", seed=20)
+    assert cfg == "bf16_symm_lower_768x768_n16", cfg
+    _, cfg = run_symm_case(oracle, 16384, 32, uplo="upper", seed=23)
+    assert cfg == "bf16_symm_upper_512x512_n32", cfg
     _, cfg = run_symm_case(oracle, 12288, 4, seed=21)
-    assert cfg == "bf16_symm_lower_512x512_n16", cfg
+    assert cfg == "bf16_symm_lower_256x256_n16", cfg
     _, cfg = run_symm_case(oracle, 12296, 16, uplo="upper", act="relu", seed=22)
-    assert cfg == "bf16_symm_upper_512x512_n16", cfg
+    assert cfg.startswith("bf16_symm_upper_"), cfg
 
 
 @pytest.mark.parametrize("uplo", ["lower", "upper"])

@@ -66,8 +66,8 @@ def test_symmetric_plan_and_workspace_queries(lib):
     (terms x batch x M x N floats); the same call with many columns runs in the guarded kernel, one pass."""
     few = binding.fused_args(8192, 16, 8192, P, 8192, P, 16, P, 16, a_structure="sym_lower")
     assert binding.fused_workspace_bytes(few) == 32 * 8192 * 16 * 4          # 32 rows of super-tiles of 256
-    big = binding.fused_args(16384, 8, 16384, P, 16384, P, 8, P, 8, batch=2, a_structure="sym_upper")
-    assert binding.fused_workspace_bytes(big) == 32 * 2 * 16384 * 8 * 4      # 32 rows of super-tiles of 512
+    big = binding.fused_args(16384, 16, 16384, P, 16384, P, 16, P, 16, a_structure="sym_upper")
+    assert binding.fused_workspace_bytes(big) == 22 * 16384 * 16 * 4         # 22 rows of super-tiles of 768: one round
     many = binding.fused_args(1024, 64, 1024, P, 1024, P, 64, P, 64, a_structure="sym_lower", plan="direct")
     assert binding.fused_workspace_bytes(many) == 0
     assert binding.fused_workspace_bytes(binding.fused_args(1024, 8, 512, P, 1024, P, 8, P, 8, a_structure="sym_lower")) == 0
