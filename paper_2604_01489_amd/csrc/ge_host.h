@@ -89,6 +89,17 @@ bool four_wave_ok(const Plan &pl, int K);
 // ge_release_workspace).
 ge_status_t acquire_workspace(size_t need, void *user, size_t user_bytes, hipStream_t stream, void **out);
 
+// A symmetric A given by one triangle with few output columns (gemm_symm_api.hip): whether the kernel
+// that fetches every stored element once takes the call, with which super-tile width, and the bytes
+// of its partial results; run_symm launches it and the second pass (p: the call's launch parameters).
+struct SymmPlan {
+    bool fast;
+    int st, np, terms;
+    size_t bytes;
+};
+SymmPlan plan_symm(const ge_fused_args_t &a);
+ge_status_t run_symm(const ge_fused_args_t &a, const SymmPlan &plan, GemmParams p, hipStream_t hs);
+
 // The plain operator C = act(alpha A B + bias) (row-major operands, fp32 out): what the plain
 // entry points call, and what the widened one calls when none of its extras is in use.
 ge_status_t run_bf16(int M, int N, int K, const uint16_t *A, int lda, const uint16_t *B, int ldb,
