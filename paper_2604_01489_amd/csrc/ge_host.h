@@ -20,7 +20,7 @@ constexpr int kNumCU = 256;          // MI355X
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // ---- shape -> plan -------------------------------------------------------
-enum TileKind { TILE_256 = 0, TILE_128 = 1, TILE_GENERIC = 2 };
+enum TileKind { TILE_256 = 0, TILE_128 = 1, TILE_GENERIC = 2, TILE_SKINNY = 3 };
 
 struct Plan {
     TileKind tile;
@@ -73,7 +73,9 @@ bool opt_eight_waves();   // keep full 256 x 256 tiles on the eight-wave kernel
 bool opt_stage_k32();     // no 64-k load phases in the eight-wave kernel
 
 int choose_split(long long tiles, int K, int minSlice);
-ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out);
+// skinny: the caller can launch the tall-skinny kernel (the plain operator only), so the plan may name it
+ge_status_t make_plan_bf16(int M, int N, int K, int batch, bool fast, ge_plan_t plan, int split_k, Plan *out,
+                           bool skinny = false);
 size_t partial_bytes(int M, int N, int batch, int splitK);
 int choose_group_m(int tilesM, int tilesN);
 // The four-wave kernel (gemm_bf16_w4.h) takes launches of 256 x 256 tiles whose blocks walk a K range

@@ -24,3 +24,14 @@ def test_symmetric_kernel_layout_model(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
     assert "symmetric layout checks passed" in res.stdout
+
+
+def test_skinny_kernel_layout_model(tmp_path):
+    """The same for the tall-skinny kernel (csrc/skinny_layout.h)."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "skinny_layout_check")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-o", exe, os.path.join(root, "tests", "skinny_layout_check.cpp")],
+                   check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    assert "skinny layout checks passed" in res.stdout
