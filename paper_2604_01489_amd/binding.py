@@ -78,6 +78,10 @@ def load():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch ships a HIP runtime of its own.  It has to be in the process before this library is, or the
+    # library binds to a second copy of the runtime that knows nothing of the devices and streams torch
+    # hands over (every launch then fails with "no device").
+    import torch  # noqa: F401
     path = os.environ.get("GE_LIBRARY", LIB_PATH)     # another build of the same library, for A/B timing
     if not os.path.exists(path):
         raise FileNotFoundError(
@@ -139,6 +143,7 @@ def load_probes():
     if not os.path.exists(PROBES_LIB_PATH):
         raise FileNotFoundError(
             f"{PROBES_LIB_PATH} is missing: run `python -m paper_2604_01489_amd.build` first")
+    import torch  # noqa: F401  (as in load(): torch's HIP runtime first)
     lib = ctypes.CDLL(PROBES_LIB_PATH)
     c_int, c_void, c_float, c_size = ctypes.c_int, ctypes.c_void_p, ctypes.c_float, ctypes.c_size_t
     lib.ge_probe_mfma_bf16.restype = c_int
