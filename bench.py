@@ -59,38 +59,38 @@ STREAM_MIX = {
 # HBM-side traffic per launch of the dominant kernel, from rocprofv3 --pmc runs of this file
 # (profiles/): FETCH_SIZE and WRITE_SIZE in KiB per dispatch, each scaled by what the same counter
 # reads for a plain 1 GiB device-to-device copy (FETCH_SIZE reads 0.5 KiB per KiB copied there,
-# WRITE_SIZE 1.0).  Valid only for the kernel sources the counters were taken on: the entry is
-# dropped (reported as null) as soon as the hash of csrc/ changes.
+# WRITE_SIZE 1.0).  An entry is valid only for the kernel it was taken on: it names the kernel
+# configuration and carries a hash of the source files that kernel is compiled from, and is dropped
+# (reported as null) as soon as either changes.
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
+_MAIN_W4 = ("bf16_layout.h", "ge_device.h", "gemm_bf16_w4.h")
+_MAIN_W8 = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h")
+_F32 = ("bf16_layout.h", "ge_device.h", "gemm_f32_fast.h")
+# workload -> (kernel configuration, FETCH_SIZE KiB, WRITE_SIZE KiB, source files, their hash)
+# TRAFFIC-BEGIN (rows written from the counter runs; see profiles/)
 TRAFFIC = {
-    "source_hash": "e6bf02425a731431",
-    # workload -> (kernel configuration the counters were taken on, bytes per launch)
-    "bytes_per_launch": {
-        "c2_bf16_4096": ("bf16_256x256x64_w4", (98452 * 2.0 + 65536 * 1.0) * 1024),
-        "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", (799687 * 2.0 + 262237 * 1.0) * 1024),
-        "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", (16488 * 2.0 + 262170 * 1.0) * 1024),
-        # the GEMM pass of the pair (the reduce pass: 32824 * 2.0 + 4096 KiB)
-        "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", (131408 * 2.0 + 65536 * 1.0) * 1024),
-        "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", (787727 * 2.0 + 131072 * 1.0) * 1024),
-        "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", (852470 * 2.0 + 131072 * 1.0) * 1024),
-        "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", (16578 * 2.0 + 131072 * 1.0) * 1024),
-        "c9_diag_bf16_8192": ("diag_rows_vec4", (65731 * 2.0 + 262144 * 1.0) * 1024),
-        "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", (101448 * 2.0 + 50176 * 1.0) * 1024),
-        "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", (627895 * 2.0 + 262144 * 1.0) * 1024),
-        # the three kernels of a step: column sums of the weights (two passes), then the pass over the input
-        "c12_rowsum_linear_8192": ("rowsum_rows_vec8", ((65582 + 2080 + 65691) * 2.0 + (4096 + 32 + 32) * 1.0) * 1024),
-    },
+    "c1_f32_256": ("f32_64x64x16_w4", 831, 256, _F32, "7331e69379e6c73c"),
+    "c2_bf16_4096": ("bf16_256x256x64_w4", 98453, 65536, _MAIN_W4, "a647dac677fa53c8"),
+    "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 803321, 262258, _MAIN_W4, "a647dac677fa53c8"),
+    "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16485, 262159, _MAIN_W8, "c0cbc78b10224327"),
+    "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", 131331, 65536, _MAIN_W4, "a647dac677fa53c8"),
+    "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", 789960, 131184, _MAIN_W4, "a647dac677fa53c8"),
+    "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 852644, 131072, _MAIN_W8, "c0cbc78b10224327"),
+    "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", 16650, 131072, _MAIN_W8, "c0cbc78b10224327"),
+    "c9_diag_bf16_8192": ("diag_rows_vec4", 65967, 262563, ('gemm_diag.hip',), "95489dc912964713"),
+    "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", 100752, 50176, _MAIN_W8, "c0cbc78b10224327"),
+    "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 600771, 262144, _MAIN_W4, "a647dac677fa53c8"),
+    "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133341, 4356, ('gemm_rowsum.hip',), "96d60999fe041ad6"),
+    "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 784014, 262144, _F32, "7331e69379e6c73c"),
+    "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146163, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "ad6151516cd89209"),
 }
+# TRAFFIC-END
 
 
-# the device code of the kernels (host-side dispatch of the GEMMs is covered by the kernel name stored with each entry)
-KERNEL_SOURCES = ("bf16_layout.h", "ge_device.h", "gemm_bf16_fast.h", "gemm_bf16_w4.h", "gemm_f32_fast.h", "gemm_generic.h", "gemm_fused.h",
-                  "gemm_diag.hip", "gemm_rowsum.hip")
-
-
-def kernel_source_hash() -> str:
+def kernel_source_hash(files) -> str:
     import hashlib
     h = hashlib.sha256()
-    for f in KERNEL_SOURCES:
+    for f in files:
         with open(os.path.join(ROOT, "paper_2604_01489_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
@@ -163,12 +163,12 @@ def blas_yardstick(torch, dA, dB, transA: bool, transB: bool, flops: float, warm
 
 
 def measured_traffic(workload: str, config_name: str):
-    """HBM-side bytes per launch from the stored counters, or None when the kernel sources or the
-    kernel chosen for the workload are no longer the ones the counters were taken on."""
-    if kernel_source_hash() != TRAFFIC["source_hash"]:
+    """HBM-side bytes per launch from the stored counters, or None when the kernel chosen for the
+    workload or its source files are no longer the ones the counters were taken on."""
+    v = TRAFFIC.get(workload)
+    if v is None or v[0] != config_name or kernel_source_hash(v[3]) != v[4]:
         return None
-    v = TRAFFIC["bytes_per_launch"].get(workload)
-    return None if v is None or v[0] != config_name else float(v[1])
+    return float((v[1] * FETCH_SCALE + v[2] * WRITE_SCALE) * 1024)
 
 
 def sample_rows(M: int, count: int) -> np.ndarray:

@@ -8,6 +8,7 @@
 #include <cstring>
 
 #include "../../include/gemm_epilogue.h"
+#include "conv_rows.h"
 #include "gemm_bf16_fast.h"
 #include "gemm_fused.h"
 #include "ge_host.h"
@@ -45,8 +46,41 @@ void launch_conv(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_
 struct ConvPlan {
     int OH, OW;
     long long M, K, xElems;
+    bool rows;          // the few-channel kernel: a K step is one filter row
+    bool rowsPairs;     //   ... whose input rows are 4-byte aligned and even in length
     Plan pl;
 };
+
+// Workgroups of the few-channel kernel that the device holds at once (they walk over the output rows);
+// a host-side computation of the runtime, nothing is enqueued.
+template <int NT, bool OUTBF16, bool PAIRS, int KHT>
+int rows_resident_blocks(size_t ldsBytes)
+{
+    int perCU = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&perCU, ge::conv_rows_bf16_kernel<NT, OUTBF16, PAIRS, KHT>, 256, ldsBytes) != hipSuccess ||
+        perCU < 1) {
+        (void)hipGetLastError();
+        perCU = 1;
+    }
+    return perCU * kNumCU;
+}
+
+template <int NT, bool OUTBF16, bool PAIRS, int KHT>
+void launch_rows_kh(const GemmParams &p, int items, size_t ldsBytes, hipStream_t st)
+{
+    const int resident = rows_resident_blocks<NT, OUTBF16, PAIRS, KHT>(ldsBytes);
+    const int blocks = items < resident ? items : resident;
+    GE_LAUNCH((ge::conv_rows_bf16_kernel<NT, OUTBF16, PAIRS, KHT>), dim3((unsigned)blocks), dim3(256), ldsBytes, st, p, items);
+}
+
+// 7 and 3 filter rows (first layers) have kernels of their own, any other count one with a run-time count
+template <int NT, bool OUTBF16, bool PAIRS>
+void launch_rows(const GemmParams &p, int items, size_t ldsBytes, hipStream_t st)
+{
+    if (p.convKH == 7) launch_rows_kh<NT, OUTBF16, PAIRS, 7>(p, items, ldsBytes, st);
+    else if (p.convKH == 3) launch_rows_kh<NT, OUTBF16, PAIRS, 3>(p, items, ldsBytes, st);
+    else launch_rows_kh<NT, OUTBF16, PAIRS, 0>(p, items, ldsBytes, st);
+}
 
 ge_status_t plan_conv(const ge_conv_args_t &a, ConvPlan *out)
 {
@@ -76,7 +110,23 @@ ge_status_t plan_conv(const ge_conv_args_t &a, ConvPlan *out)
                 xElems * 2 < (1ll << 31) - (1 << 20) && K * 2 * 256 + 1024 < (1ll << 31);
     if (a.y_type == GE_DTYPE_BF16 && (((uintptr_t)a.Y) & 15u)) fast = false;
     out->OH = OH; out->OW = OW; out->M = M; out->K = K; out->xElems = xElems;
-    return make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &out->pl);
+    // few input channels: one filter row per K step (conv_rows.h) where a row of the filter fits the
+    // 32 elements of a step, its image of an input row fits 512 dwords, and a lane's 8 channels of Y
+    // (and of R) are 16 aligned bytes or two such pieces
+    out->rows = false; out->rowsPairs = false;
+    if (!fast && opt_force_config() != FORCE_GENERIC && a.dil_w == 1 && (long long)a.KW * a.Cin <= ge_conv_rows::KSTEP &&
+        a.KH <= ge_conv_rows::KH_MAX && (a.Cout == 32 || a.Cout == 64) && (long long)a.W * a.Cin < (1 << 20) && a.pad_w < 4096 &&
+        a.stride_w < 4096 && (long long)OW * a.stride_w * a.Cin < (1 << 20) && !(((uintptr_t)a.Y) & 15u) &&
+        !(a.R && (((uintptr_t)a.R) & 15u))) {
+        const int pitch = ge_conv_rows::pitch_dwords(a.W, a.Cin, OW, a.stride_w, a.pad_w);
+        if (pitch <= 512) {
+            out->rows = true;
+            out->rowsPairs = ((a.W * a.Cin) % 2 == 0) && !(((uintptr_t)a.X) & 3u);
+        }
+    }
+    ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &out->pl);
+    if (st == GE_OK && out->rows) { out->pl.splitK = 1; out->pl.kPerSlice = (int)K; }
+    return st;
 }
 
 }  // namespace
@@ -131,6 +181,23 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
     p.convOH = OH; p.convOW = OW;
     p.convSh = a.stride_h; p.convSw = a.stride_w; p.convPh = a.pad_h; p.convPw = a.pad_w;
     p.convDh = a.dil_h; p.convDw = a.dil_w;
+
+    if (cp.rows) {
+        const int pitch = ge_conv_rows::pitch_dwords(a.W, a.Cin, OW, a.stride_w, a.pad_w);
+        const size_t ldsBytes = (size_t)2 * a.KH * pitch * 4;      // two sets of row images
+        const int items = a.N * OH;                      // N * OH * OW fits 30 bits (checked by the plan)
+        hipStream_t hs = (hipStream_t)stream;
+        const bool h = a.y_type == GE_DTYPE_BF16;
+        if (a.Cout == 64) {
+            if (cp.rowsPairs) { if (h) launch_rows<4, true, true>(p, items, ldsBytes, hs); else launch_rows<4, false, true>(p, items, ldsBytes, hs); }
+            else              { if (h) launch_rows<4, true, false>(p, items, ldsBytes, hs); else launch_rows<4, false, false>(p, items, ldsBytes, hs); }
+        } else {
+            if (cp.rowsPairs) { if (h) launch_rows<2, true, true>(p, items, ldsBytes, hs); else launch_rows<2, false, true>(p, items, ldsBytes, hs); }
+            else              { if (h) launch_rows<2, true, false>(p, items, ldsBytes, hs); else launch_rows<2, false, false>(p, items, ldsBytes, hs); }
+        }
+        g_last_config = "conv_bf16_rows_k32";
+        return ge_host::take_launch_error() != hipSuccess ? GE_ERR_LAUNCH : GE_OK;
+    }
 
     // few output tiles and a long K (late layers: small images, many channels): K slices into the
     // library's workspace, summed in slice order by the second pass, which also runs the chain

@@ -174,16 +174,16 @@ def choose_structure(M: int, N: int, K: int, batch: int = 1, workdir: str | None
 
 
 # ---- the planner's cost model, measured -----------------------------------------------------------
-def _time_us(M, N, K, tile, plan, split, reps=20, warmup=5):
+def _time_us(M, N, K, tile, plan, split, reps=20, warmup=5, batch=1):
     import torch
     dev = torch.device("cuda:0")
-    A = torch.randn(M, K, device=dev).to(torch.bfloat16).view(torch.int16)
-    B = torch.randn(K, N, device=dev).to(torch.bfloat16).view(torch.int16)
-    C = torch.empty(M, N, device=dev)
+    A = torch.randn(batch * M, K, device=dev).to(torch.bfloat16).view(torch.int16)
+    B = torch.randn(batch * K, N, device=dev).to(torch.bfloat16).view(torch.int16)
+    C = torch.empty(batch * M, N, device=dev)
     binding.set_option("force_config", tile)
     try:
         def call():
-            binding.gemm_epilogue_bf16_ex(M, N, K, A, K, B, N, None, 1.0, "none", C, N, 1, plan=plan, split_k=split)
+            binding.gemm_epilogue_bf16_ex(M, N, K, A, K, B, N, None, 1.0, "none", C, N, batch, plan=plan, split_k=split)
         best = None
         for _ in range(3):                      # the least disturbed of three measurements
             for _ in range(warmup):
@@ -204,9 +204,12 @@ def _time_us(M, N, K, tile, plan, split, reps=20, warmup=5):
 
 def calibrate():
     """The rates of ``plan_cost_us`` (csrc/gemm_epilogue_api.hip), each from two timings that differ in
-    one quantity: microseconds per 32-wide K step and per block for a 256 x 256 block alone on a CU,
-    for a 128 x 128 block alone on a CU and for two sharing one; and the second pass of K slices
-    (launch and bytes of partial tiles per microsecond)."""
+    one quantity.  Per 32-wide K step and per launch (what a launch of one round costs beyond its steps):
+    two K extents of a launch with 256 x 256 blocks one to a CU, of one with 128 x 128 blocks alone on
+    their CUs and of one with two sharing a CU.  Per further round of blocks: a short-K batch of several
+    rounds against the same batch four times as large.  The second pass of K slices: its launch from a
+    sliced call against the direct call over one slice's K extent, its bytes per microsecond from the
+    duration of the second kernel under the profiler's kernel trace (a child process)."""
     out = {}
 
     def line(tile, M, N, k1, k2):
@@ -214,15 +217,26 @@ def calibrate():
         step = (t2 - t1) / ((k2 - k1) / 32.0)
         return step, t1 - step * (k1 / 32.0), (t1, t2)
 
+    def per_round(tile, blocks_per_round, step):
+        # 512 x 512 x 64 per batch (four 256 blocks or sixteen 128 blocks), 128 and 512 batches: both
+        # write more than the 256 MB memory-side cache holds, as a launch of many rounds does
+        per_batch = 4 if tile == "256x256" else 16
+        t_lo = _time_us(512, 512, 64, tile, "direct", 1, batch=128)
+        t_hi = _time_us(512, 512, 64, tile, "direct", 1, batch=512)
+        rounds = (512 - 128) * per_batch / blocks_per_round
+        return (t_hi - t_lo) / rounds - 2.0 * step, (t_lo, t_hi)
+
     out["step256"], out["fixed256"], raw256 = line("256x256", 4096, 4096, 2048, 8192)         # 256 blocks: one to a CU
     out["step128_alone"], out["fixed128_alone"], raw128a = line("128x128", 2048, 2048, 2048, 8192)   # 256 blocks of 128
     out["step128_shared"], out["fixed128_shared"], raw128s = line("128x128", 4096, 2048, 2048, 8192)  # 512 blocks: two to a CU
-    # second pass of K slices: 1024 x 1024 x 65536 in 16 slices under the profiler's kernel trace (a child
-    # process): the partial tiles over the duration of the second kernel, and what the pair of launches
-    # costs beyond its two kernels
+    out["round256"], rawr256 = per_round("256x256", 256, out["step256"])
+    out["round128_shared"], rawr128 = per_round("128x128", 512, out["step128_shared"])
+    # the second launch: one tile, two slices of 4096 against the direct call over 4096
+    pair_small = _time_us(128, 128, 8192, "128x128", "splitk", 2)
+    direct_small = _time_us(128, 128, 4096, "128x128", "direct", 1)
+    out["second_pass_launch"] = max(pair_small - direct_small, 0.5)
     M = N = 1024
     K, S, reps = 65536, 16, 10
-    total = _time_us(M, N, K, "256x256", "splitk", S)
     with tempfile.TemporaryDirectory() as tmp:
         cmd = ["rocprofv3", "--kernel-trace", "--stats", "-d", tmp, "-o", "c", "--output-format", "csv", "--",
                sys.executable, "-m", "paper_2604_01489_amd.tune", "--one", str(M), str(N), str(K), "1", "256x256", str(S), str(reps)]
@@ -231,21 +245,17 @@ def calibrate():
         files = glob.glob(os.path.join(tmp, "**", "*kernel_stats.csv"), recursive=True)
         if res.returncode != 0 or not files:
             raise RuntimeError(f"kernel trace failed ({res.returncode}): {res.stderr[-400:]}")
-        gemm_us = reduce_us = None
+        reduce_us = None
         with open(files[0], newline="") as fh:
             for row in csv.DictReader(fh):
-                # the mean without the slowest dispatch (the first one runs before the clocks have settled)
-                mean_us = (float(row["TotalDurationNs"]) - float(row["MaxNs"])) / max(int(row["Calls"]) - 1, 1) / 1e3
                 if "splitk_reduce_kernel" in row["Name"]:
-                    reduce_us = mean_us
-                elif "gemm_bf16_w4_kernel" in row["Name"]:
-                    gemm_us = mean_us
-    if gemm_us is None or reduce_us is None:
-        raise RuntimeError("the kernel trace does not name the two kernels of the split plan")
+                    # the mean without the slowest dispatch (the first one runs before the clocks have settled)
+                    reduce_us = (float(row["TotalDurationNs"]) - float(row["MaxNs"])) / max(int(row["Calls"]) - 1, 1) / 1e3
+    if reduce_us is None:
+        raise RuntimeError("the kernel trace does not name the second kernel of the split plan")
     out["second_pass_bytes_per_us"] = (S + 1) * M * N * 4.0 / reduce_us
-    out["second_pass_launch"] = max(total - gemm_us - reduce_us, 0.0)
-    out["raw"] = {"256": raw256, "128_alone": raw128a, "128_shared": raw128s,
-                  "split": {"pair_us": total, "gemm_us": gemm_us, "reduce_us": reduce_us}}
+    out["raw"] = {"256": raw256, "128_alone": raw128a, "128_shared": raw128s, "rounds256": rawr256, "rounds128_shared": rawr128,
+                  "second_launch": {"pair_us": pair_small, "direct_us": direct_small}, "reduce_us": reduce_us}
     return out
 
 
@@ -258,11 +268,13 @@ RATES_HEADER = """// Rates of the planner's cost model (plan_cost_us in gemm_epi
 namespace ge_host {{
 
 constexpr double kStep256Us = {step256:.3f};          // 256 x 256 block, one to a CU: per 32-wide K step
-constexpr double kFixed256Us = {fixed256:.2f};        //   ... and per block (pipeline fill, tile store)
+constexpr double kFixed256Us = {fixed256:.2f};        //   ... and per launch of one round (launch, pipeline fill, tile store)
+constexpr double kRound256Us = {round256:.2f};        //   ... and per further round of blocks
 constexpr double kStep128AloneUs = {step128_alone:.3f};     // 128 x 128 block alone on a CU
 constexpr double kFixed128AloneUs = {fixed128_alone:.2f};
 constexpr double kStep128SharedUs = {step128_shared:.3f};    // two 128 x 128 blocks sharing a CU, per round of two
 constexpr double kFixed128SharedUs = {fixed128_shared:.2f};
+constexpr double kRound128SharedUs = {round128_shared:.2f};
 constexpr double kSecondPassLaunchUs = {second_pass_launch:.2f};      // K slices: the second launch
 constexpr double kSecondPassBytesPerUs = {second_pass_bytes_per_us:.4g};  //   ... and its partial tiles, written and read
 

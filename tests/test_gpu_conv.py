@@ -59,8 +59,8 @@ def test_conv_3x3_tiles_256(oracle, monkeypatch):
     run_conv_case(oracle, (4, 16, 16, 32, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=3,
                   expect="conv_bf16_256x256x32_w8")                                                      # 1024 x 256: full tiles
     run_conv_case(oracle, (1, 18, 19, 64, 264, 3, 3), pad=(1, 1), act="relu", seed=4, expect="conv_bf16_256x256x32_w8")
-    run_conv_case(oracle, (2, 16, 16, 128, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=5,
-                  expect="conv_bf16_256x256x32_w8_splitk")                                # 512 x 256: two full tiles, K = 1152
+    run_conv_case(oracle, (2, 16, 16, 256, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=5,
+                  expect="conv_bf16_256x256x32_w8_splitk")                                # 512 x 256: two full tiles, K = 2304
 
 
 @pytest.mark.parametrize("stride,pad,dil,k", [
@@ -89,10 +89,70 @@ def test_conv_chain(oracle, out, residual):
 
 def test_conv_guarded_kernel(oracle):
     run_conv_case(oracle, (2, 21, 19, 3, 10, 7, 7), stride=(2, 2), pad=(3, 3), act="relu", seed=30,
-                  expect="conv_bf16_generic_64x64x32")                                    # first-layer shape: Cin = 3
+                  expect="conv_bf16_generic_64x64x32")                                    # Cin = 3 with 10 output channels
     run_conv_case(oracle, (1, 9, 9, 40, 24, 3, 3), pad=(1, 1), residual="f32", out="bf16", seed=31,
                   expect="conv_bf16_generic_64x64x32")                                    # Cin not a multiple of 32
     run_conv_case(oracle, (1, 8, 8, 32, 12, 1, 1), seed=32, expect="conv_bf16_generic_64x64x32")   # Cout not a multiple of 8
+
+
+ROWS = "conv_bf16_rows_k32"
+
+
+def test_conv_few_channels_first_layer(oracle):
+    """Few input channels: the kernel whose K step is one filter row.  The first layer's geometry (7 x 7, stride 2,
+    padding 3, 3 -> 64) on images whose rows are even and odd in length (staged dword by dword, or element by
+    element), several tiles of 16 output columns and a ragged last one, rows above and below the image."""
+    run_conv_case(oracle, (2, 40, 40, 3, 64, 7, 7), stride=(2, 2), pad=(3, 3), act="relu", out="bf16", seed=50, expect=ROWS)
+    run_conv_case(oracle, (3, 23, 37, 3, 64, 7, 7), stride=(2, 2), pad=(3, 3), act="relu", seed=51, expect=ROWS)
+    run_conv_case(oracle, (1, 70, 150, 3, 64, 7, 7), stride=(2, 2), pad=(3, 3), act="gelu_tanh", alpha=0.5, out="bf16", seed=52,
+                  expect=ROWS)                                  # 75 output columns: five tiles, the last with 11
+
+
+@pytest.mark.parametrize("shape,stride,pad,dil", [
+    ((2, 12, 33, 1, 32, 7, 7), (2, 2), (3, 3), (1, 1)),       # one channel, 32 output channels
+    ((2, 14, 19, 4, 64, 5, 7), (2, 3), (2, 2), (2, 1)),       # four channels, stride 3 along the row, dilated filter rows
+    ((1, 9, 50, 2, 32, 1, 16), (1, 1), (0, 0), (1, 1)),       # a filter row of exactly 32 elements, no padding
+    ((2, 10, 21, 3, 64, 3, 3), (1, 1), (1, 1), (1, 1)),       # 3 x 3, stride 1: windows begin at odd and even elements
+    ((1, 6, 16, 3, 64, 2, 2), (1, 2), (0, 1), (1, 1)),        # even filter
+    ((5, 3, 5, 3, 32, 7, 7), (2, 2), (3, 3), (1, 1)),         # an image smaller than the filter
+])
+def test_conv_few_channels_geometry(oracle, shape, stride, pad, dil):
+    run_conv_case(oracle, shape, stride=stride, pad=pad, dil=dil, act="relu", seed=sum(shape), expect=ROWS)
+
+
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+@pytest.mark.parametrize("residual", [None, "f32", "bf16"])
+def test_conv_few_channels_chain(oracle, out, residual):
+    for cout in (32, 64):
+        run_conv_case(oracle, (2, 18, 26, 3, cout, 7, 7), stride=(2, 2), pad=(3, 3), alpha=0.75, residual=residual, beta=0.5,
+                      act="relu", clamp=(0.0, 1.5), out=out, seed=60 + cout, expect=ROWS)
+    run_conv_case(oracle, (1, 18, 26, 3, 64, 7, 7), stride=(2, 2), pad=(3, 3), with_bias=False, residual=residual, out=out,
+                  seed=61, expect=ROWS)
+
+
+def test_conv_few_channels_falls_back(oracle):
+    """Shapes the row kernel does not take go to the guarded kernel: other channel counts of the output, a filter
+    row longer than 32 elements, a dilated filter row, more than 7 filter rows."""
+    g = "conv_bf16_generic_64x64x32"
+    run_conv_case(oracle, (1, 12, 12, 3, 48, 3, 3), pad=(1, 1), seed=70, expect=g)
+    run_conv_case(oracle, (1, 12, 20, 3, 64, 3, 11), pad=(1, 5), seed=71, expect=g)
+    run_conv_case(oracle, (1, 12, 20, 3, 64, 3, 3), pad=(1, 2), dil=(1, 2), seed=72, expect=g)
+    run_conv_case(oracle, (1, 20, 12, 3, 64, 9, 3), pad=(4, 1), seed=73, expect=g)
+
+
+def test_conv_few_channels_is_repeatable(oracle):
+    import torch
+    from paper_2604_01489_amd import inputs as gen
+    X = torch.from_numpy(gen.to_bf16_bits(gen.normal(80, 0, 4 * 64 * 64 * 3, 1.0).reshape(4, 64, 64, 3)).view(np.int16)).cuda()
+    Wt = torch.from_numpy(gen.to_bf16_bits(gen.normal(80, 1, 64 * 49 * 3, 0.1).reshape(64, 7, 7, 3)).view(np.int16)).cuda()
+    outs = []
+    for _ in range(3):
+        Y = torch.empty(4, 32, 32, 64, dtype=torch.bfloat16, device="cuda:0")
+        binding.conv2d_epilogue_bf16(X, Wt, Y, stride=(2, 2), pad=(3, 3), act="relu")
+        torch.cuda.synchronize()
+        assert binding.last_config() == ROWS
+        outs.append(Y.view(torch.int16).cpu().numpy().tobytes())
+    assert outs[0] == outs[1] == outs[2]
 
 
 def test_conv_split_k_for_few_tiles_and_long_k(oracle, monkeypatch):

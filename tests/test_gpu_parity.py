@@ -107,11 +107,16 @@ def test_bf16_batched(oracle):
 
 def test_bf16_batched_small_k_many_rounds(oracle):
     """More blocks than CUs at small K: the first round of blocks also touches the inputs of
-    later rounds (up-front reads); full and ragged tiles."""
+    later rounds (up-front reads); full and ragged tiles, on both block tiles (the planner's
+    choice between them for such shapes follows its measured per-round costs)."""
     _, _, _, cfg = run_case(oracle, "bf16", 512, 512, 64, batch=80, act="relu", seed=20, dist="normal")
-    assert cfg == "bf16_256x256x32_w8"
-    run_case(oracle, "bf16", 520, 264, 72, batch=70, act="gelu_tanh", alpha=0.25, seed=21, lda=80, ldb=272, ldc=268)
-    run_case(oracle, "bf16", 256, 256, 128, batch=300, act="none", with_bias=False, seed=22)
+    assert cfg in ("bf16_256x256x32_w8", "bf16_128x128x32_w4")
+    for tile, name in (("256x256", "bf16_256x256x32_w8"), ("128x128", "bf16_128x128x32_w4")):
+        binding.set_option("force_config", tile)
+        _, _, _, cfg = run_case(oracle, "bf16", 512, 512, 64, batch=80, act="relu", seed=20, dist="normal")
+        assert cfg == name
+        run_case(oracle, "bf16", 520, 264, 72, batch=70, act="gelu_tanh", alpha=0.25, seed=21, lda=80, ldb=272, ldc=268)
+        run_case(oracle, "bf16", 256, 256, 128, batch=300, act="none", with_bias=False, seed=22)
 
 
 # ------------------------------------------------------------------ split-K

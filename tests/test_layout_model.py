@@ -35,3 +35,15 @@ def test_skinny_kernel_layout_model(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
     assert "skinny layout checks passed" in res.stdout
+
+
+def test_conv_rows_kernel_layout_model(tmp_path):
+    """The same for the few-channel convolution kernel (csrc/conv_rows_layout.h): staged rows, shifted and
+    masked fragments, the matrix instruction's lanes and the channel map, against the definition."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "conv_rows_layout_check")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-o", exe, os.path.join(root, "tests", "conv_rows_layout_check.cpp")],
+                   check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    assert "conv rows layout checks passed" in res.stdout

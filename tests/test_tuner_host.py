@@ -49,11 +49,12 @@ def test_ties_go_to_the_counters_and_clear_winners_do_not(monkeypatch):
 
 
 def test_rates_header_is_generated_from_the_record(tmp_path):
-    rates = dict(step256=0.65, fixed256=16.5, step128_alone=0.24, fixed128_alone=8.9, step128_shared=0.47,
-                 fixed128_shared=8.2, second_pass_launch=3.5, second_pass_bytes_per_us=5.6e6, raw={})
+    rates = dict(step256=0.65, fixed256=16.5, round256=11.25, step128_alone=0.24, fixed128_alone=8.9, step128_shared=0.47,
+                 fixed128_shared=8.2, round128_shared=6.75, second_pass_launch=3.5, second_pass_bytes_per_us=5.6e6, raw={})
     path = tune.write_rates(rates, str(tmp_path / "plan_rates.h"))
     text = open(path).read()
-    for needle in ("kStep256Us = 0.650", "kFixed256Us = 16.50", "kStep128SharedUs = 0.470", "kSecondPassBytesPerUs = 5.6e+06",
+    for needle in ("kStep256Us = 0.650", "kFixed256Us = 16.50", "kRound256Us = 11.25", "kStep128SharedUs = 0.470",
+                   "kRound128SharedUs = 6.75", "kSecondPassBytesPerUs = 5.6e+06",
                    "GENERATED"):
         assert needle in text
     # the committed header has the same shape (the same names, generated the same way)
