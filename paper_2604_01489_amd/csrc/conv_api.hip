@@ -111,13 +111,13 @@ ge_status_t plan_conv(const ge_conv_args_t &a, ConvPlan *out)
     if (a.y_type == GE_DTYPE_BF16 && (((uintptr_t)a.Y) & 15u)) fast = false;
     out->OH = OH; out->OW = OW; out->M = M; out->K = K; out->xElems = xElems;
     // few input channels: one filter row per K step (conv_rows.h) where a row of the filter fits the
-    // 32 elements of a step, its image of an input row fits 512 dwords, and a lane's 8 channels of Y
-    // (and of R) are 16 aligned bytes or two such pieces
+    // 32 elements of a step, its image of an input row fits 512 dwords, a lane's 8 channels of Y (and
+    // of R) are 16 aligned bytes or two such pieces, and the filter bank can be copied dword by dword
     out->rows = false; out->rowsPairs = false;
     if (!fast && opt_force_config() != FORCE_GENERIC && a.dil_w == 1 && (long long)a.KW * a.Cin <= ge_conv_rows::KSTEP &&
         a.KH <= ge_conv_rows::KH_MAX && (a.Cout == 32 || a.Cout == 64) && (long long)a.W * a.Cin < (1 << 20) && a.pad_w < 4096 &&
         a.stride_w < 4096 && (long long)OW * a.stride_w * a.Cin < (1 << 20) && !(((uintptr_t)a.Y) & 15u) &&
-        !(a.R && (((uintptr_t)a.R) & 15u))) {
+        !(a.R && (((uintptr_t)a.R) & 15u)) && !(((uintptr_t)a.Wt) & 3u)) {
         const int pitch = ge_conv_rows::pitch_dwords(a.W, a.Cin, OW, a.stride_w, a.pad_w);
         if (pitch <= 512) {
             out->rows = true;
@@ -184,7 +184,7 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
 
     if (cp.rows) {
         const int pitch = ge_conv_rows::pitch_dwords(a.W, a.Cin, OW, a.stride_w, a.pad_w);
-        const size_t ldsBytes = (size_t)2 * a.KH * pitch * 4;      // two sets of row images
+        const size_t ldsBytes = (size_t)ge_conv_rows::lds_dwords(a.KH, pitch, a.Cout, a.KW * a.Cin) * 4;
         const int items = a.N * OH;                      // N * OH * OW fits 30 bits (checked by the plan)
         hipStream_t hs = (hipStream_t)stream;
         const bool h = a.y_type == GE_DTYPE_BF16;

@@ -15,8 +15,8 @@
 //      masked to zero in registers (a zero weight would not silence an infinity there);
 //   3. the consumer chain runs on the accumulators and a lane stores 8 consecutive channels of its
 //      position in one piece (16 bytes of bf16).
-// The weights cost 8 two-byte loads per fragment, which is why a workgroup keeps them and walks:
-// the launch is sized to the workgroups the CUs hold at once.
+// The weights are the same for every output row, which is why a workgroup keeps them and walks: the
+// launch is sized to the workgroups the CUs hold at once.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -42,6 +42,7 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
     constexpr int KHR = KHT ? KHT : KH_MAX;             // filter rows the registers are laid out for
     constexpr int ROWS_PER_WAVE = (KHR + 3) / 4;        // image rows a wave stages
     constexpr int DW_PER_LANE = 8;           // dwords of one image row per lane: pitch <= 512
+    constexpr int BANK_PAD = ge_conv_rows::BANK_PAD;
     extern __shared__ __attribute__((aligned(16))) char rowsLds[];
     unsigned *img = (unsigned *)rowsLds;
 
@@ -56,23 +57,37 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
     const unsigned short *X = (const unsigned short *)p.A;
     const unsigned short *Wt = (const unsigned short *)p.B;
 
-    // the weights of every filter row, as row operands: lane (m, g) holds 8 k of channel_of(t, m)
+    unsigned kmask[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kmask[j] = k_mask(g, j, kwcin);
+
+    // The weights of every filter row, as row operands: lane (m, g) holds 8 k of channel_of(t, m).  A
+    // lane's 8 elements lie at any even or odd element of the filter bank and neighbouring lanes are
+    // whole filters apart, so fetched from memory they would be eight two-byte loads per fragment,
+    // each touching sixteen cache lines (measured: 36 us of a 57 us launch).  The bank (a few KB) is
+    // copied to LDS once, dword by dword, and the fragments are cut from it the way the input
+    // windows are: five aligned dwords, a shift, the mask of the step's unused elements.
+    const int bankDwords = Cout * KH * kwcin / 2;                 // Cout is even
+    unsigned *bank = img + 2 * KH * pitch;                        // behind the two sets of row images
+    for (int d = threadIdx.x; d < bankDwords + BANK_PAD; d += 256)
+        bank[d] = d < bankDwords ? ((const unsigned *)Wt)[d] : 0u;
+    __syncthreads();
     bf16x8_t wf[KHR][NT];
 #pragma unroll
     for (int kh = 0; kh < KHR; ++kh) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            unsigned d[4] = {0u, 0u, 0u, 0u};
+            i32x4_t dv = {0, 0, 0, 0};
             if (KHT || kh < KH) {
-                const unsigned short *src = Wt + ((long long)channel_of(t, m) * KH + kh) * kwcin;
+                const int e0 = (channel_of(t, m) * KH + kh) * kwcin + 8 * g;
+                const unsigned sh = (unsigned)(e0 & 1) * 2u;
+                const unsigned *src = bank + (e0 >> 1);
+                unsigned q[5];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int k = 8 * g + e;
-                    const unsigned v = k < kwcin ? (unsigned)src[k] : 0u;
-                    d[e >> 1] |= v << (16 * (e & 1));
-                }
+                for (int j = 0; j < 5; ++j) q[j] = src[j];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dv[j] = (int)(__builtin_amdgcn_alignbyte(q[j + 1], q[j], sh) & kmask[j]);
             }
-            const i32x4_t dv = {(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
             wf[kh][t] = __builtin_bit_cast(bf16x8_t, dv);
         }
     }
@@ -82,10 +97,6 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) bv[t][r] = p.bias ? p.bias[channel_of(t, 4 * g + r)] : 0.0f;
-    unsigned kmask[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) kmask[j] = k_mask(g, j, kwcin);
-
     // the rows of one output row: wave w fetches filter rows w and w + 4, all of a lane's loads in
     // flight together, and writes them to the image once they are needed
     unsigned staged[ROWS_PER_WAVE][DW_PER_LANE];

@@ -21,6 +21,8 @@ namespace ge_conv_rows {
 constexpr int KSTEP = 32;        // elements of one K step: one filter row, KW * Cin <= KSTEP
 constexpr int KH_MAX = 7;        // filter rows whose fragments a lane keeps in registers
 constexpr int PIX = 16;          // output positions of one matrix-instruction tile
+constexpr int BANK_PAD = 16;     // dwords of zeros behind the filter bank's copy in LDS: the last filters' fragments read up to
+                                 // (24 - KW * Cin) / 2 + 4 dwords past its end
 
 // Elements of zero padding written at the left of a staged row: the layer's own, made even so that an
 // element pair of the input (one dword of a 4-byte aligned row) stays a pair in the image.
@@ -63,5 +65,8 @@ GE_ROWS_HD constexpr unsigned k_mask(int g, int j, int kwcin)
     const int e = 8 * g + 2 * j;
     return (e < kwcin ? 0x0000ffffu : 0u) | (e + 1 < kwcin ? 0xffff0000u : 0u);
 }
+
+// Dwords of LDS the kernel uses: two sets of KH row images, the filter bank and its padding.
+GE_ROWS_HD constexpr int lds_dwords(int KH, int pitch, int Cout, int kwcin) { return 2 * KH * pitch + Cout * KH * kwcin / 2 + BANK_PAD; }
 
 }  // namespace ge_conv_rows

@@ -396,7 +396,13 @@ class ConvWorkload:
 CONV_WORKLOADS = {
     "c10_conv3x3_256_bf16out": ConvWorkload("c10_conv3x3_256_bf16out", 32, 56, 56, 256, 256, 3, 3, (1, 1), (1, 1), (1, 1),
                                             10, 1.0, (-0.1, 0.1), "bf16", 1.0, "relu", None, "bf16"),
+    # the first layer of a residual network: 3 input channels, 7 x 7, stride 2, padding 3, 64 filters; bound by the
+    # bytes of its input and output (7.6 GFLOP over 61 MB), not by the matrix pipes
+    "c15_conv7x7_first_layer_bf16out": ConvWorkload("c15_conv7x7_first_layer_bf16out", 32, 224, 224, 3, 64, 7, 7, (2, 2), (3, 3),
+                                                    (1, 1), 15, 1.0, (-0.1, 0.1), None, 1.0, "relu", None, "bf16"),
 }
+# which roofline bounds a convolution workload: the matrix pipes, or (few channels) the bytes moved
+CONV_BOUND = {"c10_conv3x3_256_bf16out": "mfma", "c15_conv7x7_first_layer_bf16out": "hbm"}
 
 
 def make_conv_inputs(cw: ConvWorkload, images=None):

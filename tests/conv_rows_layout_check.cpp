@@ -35,6 +35,11 @@ static void run(const Geo &g, unsigned seed)
     for (auto &v : X) v = (int16_t)(std::rand() % 7 - 3);
     for (auto &v : Wt) v = (int16_t)(std::rand() % 5 - 2);
 
+    // the filter bank as the kernel keeps it in LDS: its dwords, then BANK_PAD dwords (zeros in the kernel;
+    // a pattern here, to show that the mask hides whatever lies behind a filter row)
+    std::vector<uint32_t> bank(Wt.size() / 2 + BANK_PAD, 0x7fc07fc0u);
+    for (size_t d = 0; d < Wt.size() / 2; ++d) bank[d] = (uint32_t)(uint16_t)Wt[2 * d] | ((uint32_t)(uint16_t)Wt[2 * d + 1] << 16);
+    CHECK((int)(Wt.size() / 2 + BANK_PAD) + 2 * g.KH * pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw) == lds_dwords(g.KH, pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw), g.Cout, kwcin), "LDS size");
     const int pitch = pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw);
     const int tilesW = (OW + PIX - 1) / PIX;
     CHECK(left_pad(g.pw, g.Cin) % 2 == 0 && left_pad(g.pw, g.Cin) >= g.pw * g.Cin, "left pad");
@@ -74,11 +79,16 @@ static void run(const Geo &g, unsigned seed)
                         xf[lane][2 * j] = (int16_t)(f & 0xffffu);
                         xf[lane][2 * j + 1] = (int16_t)(f >> 16);
                     }
-                    for (int t = 0; t < NT; ++t)
-                        for (int e = 0; e < 8; ++e) {
-                            const int k = 8 * grp + e;
-                            wf[t][lane][e] = k < kwcin ? Wt[((size_t)channel_of(t, m) * g.KH + kh) * kwcin + k] : (int16_t)0;
+                    // the filters' fragments are cut from the bank's copy the same way
+                    for (int t = 0; t < NT; ++t) {
+                        const int w0 = (channel_of(t, m) * g.KH + kh) * kwcin + 8 * grp;
+                        CHECK((w0 >> 1) + 4 < (int)bank.size(), "read beyond the bank: %d of %d", (w0 >> 1) + 4, (int)bank.size());
+                        for (int j = 0; j < 4; ++j) {
+                            const uint32_t f = alignbyte(bank[(w0 >> 1) + j + 1], bank[(w0 >> 1) + j], (unsigned)(w0 & 1) * 2u) & k_mask(grp, j, kwcin);
+                            wf[t][lane][2 * j] = (int16_t)(f & 0xffffu);
+                            wf[t][lane][2 * j + 1] = (int16_t)(f >> 16);
                         }
+                    }
                 }
                 // D[i][j] += sum_k A[i][k] B[k][j]: lane l supplies A[l % 16][8 (l / 16) + e] and B[8 (l / 16) + e][l % 16],
                 // and holds D[4 (l / 16) + r][l % 16]
@@ -130,6 +140,8 @@ int main()
         {8, 19, 4, 5, 7, 2, 3, 2, 2, 2, 64},     // four channels, stride 3, dilated rows
         {6, 50, 2, 1, 16, 1, 1, 0, 0, 1, 32},    // the widest filter row: all 32 elements of the step, no padding
         {5, 16, 3, 2, 2, 1, 2, 0, 1, 1, 64},     // even filter, padding on one side in effect
+        {8, 20, 1, 3, 3, 1, 1, 1, 1, 1, 32},     // three elements to a filter row: the last filters' fragments reach farthest past the bank
+        {4, 9, 1, 1, 1, 1, 1, 0, 0, 1, 32},      // one element to a filter row
     };
     unsigned seed = 1;
     for (const Geo &g : cases) run(g, seed++);

@@ -163,32 +163,42 @@ def test_c9_diag_full(oracle):
     compare(got, ref, "c9_diag_bf16_8192 [diag_rows_vec4]")
 
 
-def test_c10_conv_full(oracle):
-    """The 3x3 convolution workload at full size: first and last image (first and last tiles of the implicit
-    GEMM) against the convolution oracle, every position and channel."""
+def _run_conv_workload(oracle, name, expect, imgs):
     import torch
     from paper_2604_01489_amd import binding, inputs as gen
-    cw = gen.CONV_WORKLOADS["c10_conv3x3_256_bf16out"]
+    cw = gen.CONV_WORKLOADS[name]
     host = gen.make_conv_inputs(cw)
     oh, ow = cw.out_hw()
     dX, dW, dbias, dR = to_device(host["X"]), to_device(host["Wt"]), to_device(host["bias"]), to_device(host["residual"])
     if dR is not None and cw.residual == "bf16":
         dR = dR.view(torch.bfloat16)
     Y = torch.empty(cw.N, oh, ow, cw.Cout, dtype=torch.float32 if cw.out == "f32" else torch.bfloat16, device="cuda:0")
-    print("workload c10_conv3x3_256_bf16out", flush=True)
+    print(f"workload {name}", flush=True)
     binding.conv2d_epilogue_bf16(dX, dW, Y, stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha, bias=dbias,
                                  residual=dR, beta=cw.beta, act=cw.act, clamp=cw.clamp)
     torch.cuda.synchronize()
     cfg = binding.last_config()
-    assert cfg == "conv_bf16_256x256x32_w8"
-    imgs = [0, cw.N - 1]
+    assert cfg == expect
     sub = gen.make_conv_inputs(cw, imgs)
     got = Y[torch.tensor(imgs, device="cuda:0")].to(torch.float32).cpu().numpy()
     ref = oracle.conv2d_nhwc(sub["X"], sub["Wt"], stride=cw.stride, pad=cw.pad, dil=cw.dil, alpha=cw.alpha,
                              bias=sub["bias"], residual=sub["residual"], beta=cw.beta, act=cw.act, clamp=cw.clamp,
                              out=cw.out)
-    compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"c10_conv3x3_256_bf16out [{cfg}]",
-            bf16_out=(cw.out == "bf16"))
+    compare(got.reshape(1, -1, cw.Cout), ref.reshape(1, -1, cw.Cout), f"{name} [{cfg}]", bf16_out=(cw.out == "bf16"))
+    return Y, cw
+
+
+def test_c10_conv_full(oracle):
+    """The 3x3 convolution workload at full size: first and last image (first and last tiles of the implicit
+    GEMM) against the convolution oracle, every position and channel."""
+    _run_conv_workload(oracle, "c10_conv3x3_256_bf16out", "conv_bf16_256x256x32_w8", [0, 31])
+
+
+def test_c15_conv_first_layer_full(oracle):
+    """The first-layer workload (3 channels, 7 x 7, stride 2) at full size: the first, a middle and the last image
+    against the convolution oracle, every position and channel; relu output, so nothing negative anywhere."""
+    Y, _ = _run_conv_workload(oracle, "c15_conv7x7_first_layer_bf16out", "conv_bf16_rows_k32", [0, 13, 31])
+    assert float(Y.float().min()) >= 0.0
 
 
 def test_c11_fused_lower_triangular(oracle):
