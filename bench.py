@@ -82,7 +82,7 @@ TRAFFIC = {
     "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 600771, 262144, _MAIN_W4, "a647dac677fa53c8"),
     "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133341, 4356, ('gemm_rowsum.hip',), "96d60999fe041ad6"),
     "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 784014, 262144, _F32, "7331e69379e6c73c"),
-    "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16648, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "8f8618d4a1b2de10"),
+    "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16596, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "13cc16fa399a445d"),
     "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146163, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "ad6151516cd89209"),
 }
 # TRAFFIC-END

@@ -56,13 +56,17 @@ struct ConvPlan {
 template <int NT, bool OUTBF16, bool PAIRS, int KHT>
 int rows_resident_blocks(size_t ldsBytes)
 {
+    // the answer depends on the variant and on its LDS bytes only: kept per thread for the last size asked
+    static thread_local size_t knownFor = ~(size_t)0;
+    static thread_local int known = 0;
+    if (knownFor == ldsBytes) return known;
     int perCU = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&perCU, ge::conv_rows_bf16_kernel<NT, OUTBF16, PAIRS, KHT>, 256, ldsBytes) != hipSuccess ||
-        perCU < 1) {
-        (void)hipGetLastError();
+        perCU < 1)
         perCU = 1;
-    }
-    return perCU * kNumCU;
+    knownFor = ldsBytes;
+    known = perCU * kNumCU;
+    return known;
 }
 
 template <int NT, bool OUTBF16, bool PAIRS, int KHT>

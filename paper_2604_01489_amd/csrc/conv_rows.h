@@ -26,6 +26,29 @@
 
 namespace ge {
 
+typedef __attribute__((ext_vector_type(4))) int rows_rsrc_t;
+
+// A raw buffer over one input row: `bytes` of it from `base`, or nothing (every load returns 0).
+__device__ inline rows_rsrc_t rows_make_rsrc(const void *base, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)base;
+    rows_rsrc_t r;
+    r[0] = (int)(unsigned)a;
+    r[1] = (int)((unsigned)(a >> 32) & 0xFFFFu);
+    r[2] = (int)bytes;
+    r[3] = (int)0x00020000u;             // raw buffer, 32-bit data format
+    return r;
+}
+
+// 4 bytes per lane from a raw buffer straight into LDS at ldsAddr + 4 * lane; a lane whose offset is
+// not inside the buffer lands a zero.  Inline assembly, as in the main kernels: the compiler does not
+// track it, the caller awaits it with s_waitcnt vmcnt.
+__device__ inline void rows_lds_dma4(rows_rsrc_t rs, unsigned ldsAddr, unsigned voff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+                 :: "s"(ldsAddr), "v"(voff), "s"(rs) : "memory", "m0");
+}
+
 // NT: matrix-instruction tiles across the output channels (Cout = 16 NT: 32 or 64);
 // PAIRS: an input row is 4-byte aligned and even in length, so the image is staged dword by dword;
 // KHT: the number of filter rows when it is known at compile time (3 or 7), 0 for any other up to
@@ -65,12 +88,29 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
     // lane's 8 elements lie at any even or odd element of the filter bank and neighbouring lanes are
     // whole filters apart, so fetched from memory they would be eight two-byte loads per fragment,
     // each touching sixteen cache lines (measured: 36 us of a 57 us launch).  The bank (a few KB) is
-    // copied to LDS once, dword by dword, and the fragments are cut from it the way the input
-    // windows are: five aligned dwords, a shift, the mask of the step's unused elements.
+    // copied to LDS once, dword by dword; the workgroup then cuts every fragment from it once -- five
+    // aligned dwords, a shift, the mask of the step's unused elements, as for the input windows -- into
+    // a table in fragment order, 16 bytes per lane, from which each wave fills its registers without
+    // bank conflicts (cut by every wave for itself, the scattered reads of the bank were 30 % of the
+    // kernel's LDS instructions and half its LDS cycles).  The table lies where the row images will
+    // (and may reach beyond them: front_dwords).
     const int bankDwords = Cout * KH * kwcin / 2;                 // Cout is even
-    unsigned *bank = img + 2 * KH * pitch;                        // behind the two sets of row images
+    unsigned *bank = img + front_dwords(KH, pitch, Cout);         // behind the row images (and the table)
     for (int d = threadIdx.x; d < bankDwords + BANK_PAD; d += 256)
         bank[d] = d < bankDwords ? ((const unsigned *)Wt)[d] : 0u;
+    __syncthreads();
+    i32x4_t *table = (i32x4_t *)img;                              // [kh][t][lane]
+    for (int f = threadIdx.x; f < KH * NT * 64; f += 256) {
+        const int fl = f & 63, ft = (f >> 6) % NT, fkh = (f >> 6) / NT;
+        const int fm = fl & 15, fg = fl >> 4;
+        const int e0 = (channel_of(ft, fm) * KH + fkh) * kwcin + 8 * fg;
+        const unsigned sh = (unsigned)(e0 & 1) * 2u;
+        const unsigned *src = bank + (e0 >> 1);
+        i32x4_t dv;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dv[j] = (int)(__builtin_amdgcn_alignbyte(src[j + 1], src[j], sh) & k_mask(fg, j, kwcin));
+        table[f] = dv;
+    }
     __syncthreads();
     bf16x8_t wf[KHR][NT];
 #pragma unroll
@@ -78,16 +118,7 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             i32x4_t dv = {0, 0, 0, 0};
-            if (KHT || kh < KH) {
-                const int e0 = (channel_of(t, m) * KH + kh) * kwcin + 8 * g;
-                const unsigned sh = (unsigned)(e0 & 1) * 2u;
-                const unsigned *src = bank + (e0 >> 1);
-                unsigned q[5];
-#pragma unroll
-                for (int j = 0; j < 5; ++j) q[j] = src[j];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) dv[j] = (int)(__builtin_amdgcn_alignbyte(q[j + 1], q[j], sh) & kmask[j]);
-            }
+            if (KHT || kh < KH) dv = table[(kh * NT + t) * 64 + lane];
             wf[kh][t] = __builtin_bit_cast(bf16x8_t, dv);
         }
     }
@@ -97,10 +128,27 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) bv[t][r] = p.bias ? p.bias[channel_of(t, 4 * g + r)] : 0.0f;
-    // the rows of one output row: wave w fetches filter rows w and w + 4, all of a lane's loads in
-    // flight together, and writes them to the image once they are needed
-    unsigned staged[ROWS_PER_WAVE][DW_PER_LANE];
-    auto fetch_rows = [&](int item) __attribute__((always_inline)) {
+    __syncthreads();                                   // the table has been read: the images may be written
+
+    // The rows of one output row: wave w fetches filter rows w and w + 4.
+    // PAIRS: straight into LDS, 4 bytes per lane and load, through a raw buffer over the row: a lane
+    // left of the row (its byte offset is negative: a huge unsigned one) or right of it lands a
+    // zero, which is the horizontal padding, and a row above or below the input is an empty buffer.
+    // No register, no bounds arithmetic and no LDS store is spent on it.  Otherwise element by
+    // element through registers, written to the image once they are needed.
+    const int imageDwords = KH * pitch;            // two sets of images: one is read while the next is written
+    const unsigned ldsBase = (unsigned)(size_t)(GE_LDS char *)rowsLds;
+    // byte offset of the lane's dword i of a row, from the row's first element; left of it: out of range
+    unsigned rowOff[PAIRS ? DW_PER_LANE : 1];
+    if (PAIRS) {
+#pragma unroll
+        for (int i = 0; i < DW_PER_LANE; ++i) {
+            const int o = 4 * (lane + 64 * i) - 2 * left_pad(p.convPw, Cin);
+            rowOff[i] = o < 0 ? 0x80000000u : (unsigned)o;
+        }
+    }
+    unsigned staged[PAIRS ? 1 : ROWS_PER_WAVE][PAIRS ? 1 : DW_PER_LANE];
+    auto fetch_rows = [&](int item, int set) __attribute__((always_inline)) {
         const int n = item / OH, oh = item - n * OH;
         const int ih0 = oh * p.convSh - p.convPh;
 #pragma unroll
@@ -109,41 +157,49 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
             const int ih = ih0 + kh * p.convDh;
             const bool rowOk = kh < KH && ih >= 0 && ih < H;
             const unsigned short *src = X + ((long long)n * H + (rowOk ? ih : 0)) * rowElems;
+            if (PAIRS) {
+                if (kh < KH) {
+                    const rows_rsrc_t rs = rows_make_rsrc(src, rowOk ? (unsigned)rowElems * 2u : 0u);
+                    const unsigned row = ldsBase + (unsigned)((set * KH + kh) * pitch) * 4u;
 #pragma unroll
-            for (int i = 0; i < DW_PER_LANE; ++i) {
-                const int d = lane + 64 * i;
-                const int j0 = source_element(d, 0, p.convPw, Cin);
-                unsigned v = 0u;
-                if (PAIRS) {
-                    // j0 is even and so is the row length: both halves are inside or both outside
-                    if (rowOk && d < pitch && j0 >= 0 && j0 < rowElems) v = *(const unsigned *)(src + j0);
-                } else {
-                    if (rowOk && d < pitch && j0 >= 0 && j0 < rowElems) v = (unsigned)src[j0];
-                    if (rowOk && d < pitch && j0 + 1 >= 0 && j0 + 1 < rowElems) v |= ((unsigned)src[j0 + 1]) << 16;
+                    for (int i = 0; i < DW_PER_LANE; ++i)
+                        if (64 * i < pitch) rows_lds_dma4(rs, row + 256u * i, rowOff[i]);      // pitch is a multiple of 64
                 }
-                staged[rr][i] = v;
-            }
-        }
-    };
-    auto write_rows = [&](unsigned *image) __attribute__((always_inline)) {
-#pragma unroll
-        for (int rr = 0; rr < ROWS_PER_WAVE; ++rr) {
-            const int kh = wave + 4 * rr;
-            if (kh < KH) {
+            } else {
 #pragma unroll
                 for (int i = 0; i < DW_PER_LANE; ++i) {
                     const int d = lane + 64 * i;
-                    if (d < pitch) image[kh * pitch + d] = staged[rr][i];
+                    const int j0 = source_element(d, 0, p.convPw, Cin);
+                    unsigned v = 0u;
+                    if (rowOk && d < pitch && j0 >= 0 && j0 < rowElems) v = (unsigned)src[j0];
+                    if (rowOk && d < pitch && j0 + 1 >= 0 && j0 + 1 < rowElems) v |= ((unsigned)src[j0 + 1]) << 16;
+                    staged[PAIRS ? 0 : rr][PAIRS ? 0 : i] = v;
+                }
+            }
+        }
+    };
+    auto land_rows = [&](int set) __attribute__((always_inline)) {
+        if (PAIRS) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+#pragma unroll
+            for (int rr = 0; rr < ROWS_PER_WAVE; ++rr) {
+                const int kh = wave + 4 * rr;
+                if (kh < KH) {
+#pragma unroll
+                    for (int i = 0; i < DW_PER_LANE; ++i) {
+                        const int d = lane + 64 * i;
+                        if (d < pitch) img[(set * KH + kh) * pitch + d] = staged[PAIRS ? 0 : rr][PAIRS ? 0 : i];
+                    }
                 }
             }
         }
     };
 
-    const int imageDwords = KH * pitch;            // two images: one is read while the next is written
     int cur = 0;
     if ((int)blockIdx.x < items) {
-        fetch_rows(blockIdx.x);
-        write_rows(img);
+        fetch_rows(blockIdx.x, 0);
+        land_rows(0);
     }
     __syncthreads();
     const bool hasR = p.R != nullptr;
@@ -152,7 +208,7 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
         const unsigned *image = img + cur * imageDwords;
         // the next output row's input is on its way while this one is multiplied
         const int next = item + gridDim.x;
-        if (next < items) fetch_rows(next);
+        if (next < items) fetch_rows(next, cur ^ 1);
 
         for (int tile = wave; tile < tilesW; tile += 4) {
             const int ow = tile * PIX + m;
@@ -215,7 +271,7 @@ conv_rows_bf16_kernel(const GemmParams p, const int items)
                 }
             }
         }
-        if (next < items) write_rows(img + (cur ^ 1) * imageDwords);
+        if (next < items) land_rows(cur ^ 1);
         // the image just read may be overwritten, the one just written may be read
         __syncthreads();
         cur ^= 1;

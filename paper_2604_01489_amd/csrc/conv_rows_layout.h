@@ -34,8 +34,8 @@ GE_ROWS_HD constexpr int window_start(int ow, int sw, int cin, int pw)
     return ow * sw * cin + (left_pad(pw, cin) - pw * cin);
 }
 
-// Dwords per staged row: the image holds the left padding and the W * Cin elements of the row, and
-// every fragment read stays inside it: lane group g of the last tile of a row (whose positions at or
+// Dwords per staged row, a multiple of 64 (a row is filled by wave-wide loads of 64 dwords): the image
+// holds the left padding and the W * Cin elements of the row, and every fragment read stays inside it: lane group g of the last tile of a row (whose positions at or
 // beyond OW are computed and dropped) reads the five dwords from element (start + 8 g) / 2 * 2.
 GE_ROWS_HD constexpr int pitch_dwords(int W, int cin, int OW, int sw, int pw)
 {
@@ -43,7 +43,7 @@ GE_ROWS_HD constexpr int pitch_dwords(int W, int cin, int OW, int sw, int pw)
     const int lastRead = window_start(tilesW * PIX - 1, sw, cin, pw) + 24 + 10;   // one past the last element read
     const int data = left_pad(pw, cin) + W * cin;
     const int elems = lastRead > data ? lastRead : data;
-    return (elems + 1) / 2;
+    return ((elems + 1) / 2 + 63) / 64 * 64;        // whole wave-wide loads of 64 dwords
 }
 
 // Staged rows of one output row: input rows oh * sh - ph + [0, rows_in).
@@ -66,7 +66,18 @@ GE_ROWS_HD constexpr unsigned k_mask(int g, int j, int kwcin)
     return (e < kwcin ? 0x0000ffffu : 0u) | (e + 1 < kwcin ? 0xffff0000u : 0u);
 }
 
-// Dwords of LDS the kernel uses: two sets of KH row images, the filter bank and its padding.
-GE_ROWS_HD constexpr int lds_dwords(int KH, int pitch, int Cout, int kwcin) { return 2 * KH * pitch + Cout * KH * kwcin / 2 + BANK_PAD; }
+// Dwords of LDS in front of the filter bank's copy: the two sets of KH row images, or the table of the
+// filters' fragments (16 bytes per lane, filter row and 16-channel tile) that is built there first.
+GE_ROWS_HD constexpr int front_dwords(int KH, int pitch, int Cout)
+{
+    const int images = 2 * KH * pitch, table = KH * (Cout / 16) * 64 * 4;
+    return images > table ? images : table;
+}
+
+// Dwords of LDS the kernel uses: the front, the filter bank and its padding.
+GE_ROWS_HD constexpr int lds_dwords(int KH, int pitch, int Cout, int kwcin)
+{
+    return front_dwords(KH, pitch, Cout) + Cout * KH * kwcin / 2 + BANK_PAD;
+}
 
 }  // namespace ge_conv_rows

@@ -39,7 +39,15 @@ static void run(const Geo &g, unsigned seed)
     // a pattern here, to show that the mask hides whatever lies behind a filter row)
     std::vector<uint32_t> bank(Wt.size() / 2 + BANK_PAD, 0x7fc07fc0u);
     for (size_t d = 0; d < Wt.size() / 2; ++d) bank[d] = (uint32_t)(uint16_t)Wt[2 * d] | ((uint32_t)(uint16_t)Wt[2 * d + 1] << 16);
-    CHECK((int)(Wt.size() / 2 + BANK_PAD) + 2 * g.KH * pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw) == lds_dwords(g.KH, pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw), g.Cout, kwcin), "LDS size");
+    {
+        const int pd = pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw), front = front_dwords(g.KH, pd, g.Cout);
+        CHECK(pd % 64 == 0, "a row is filled by whole wave-wide loads");
+        CHECK(front >= 2 * g.KH * pd && front >= g.KH * (g.Cout / 16) * 64 * 4, "row images and fragment table fit in front of the bank");
+        CHECK(lds_dwords(g.KH, pd, g.Cout, kwcin) == front + (int)(Wt.size() / 2) + BANK_PAD, "LDS size");
+        // a wave-wide load lands lane l's dword at image dword d = l + 64 i, from byte 4 d - 2 left_pad of the row
+        for (int d = 0; d < pd; ++d)
+            CHECK(4 * d - 2 * left_pad(g.pw, g.Cin) == 2 * source_element(d, 0, g.pw, g.Cin), "byte offset of image dword %d", d);
+    }
     const int pitch = pitch_dwords(g.W, g.Cin, OW, g.sw, g.pw);
     const int tilesW = (OW + PIX - 1) / PIX;
     CHECK(left_pad(g.pw, g.Cin) % 2 == 0 && left_pad(g.pw, g.Cin) >= g.pw * g.Cin, "left pad");
