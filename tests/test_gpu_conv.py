@@ -130,6 +130,35 @@ def test_conv_few_channels_chain(oracle, out, residual):
                   seed=61, expect=ROWS)
 
 
+def test_conv_few_channels_random_sweep(oracle):
+    """Seeded random geometries and consumer chains on the row kernel: 1 to 4 input channels, filter rows of up to 32
+    elements and up to 7 of them, strides 1 to 3, paddings 0 to 3, dilated filter rows, even and odd image rows
+    (staged straight into LDS or through registers), both channel counts of the output."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 24:
+        cin = int(rng.integers(1, 5))
+        kw = int(rng.integers(1, 32 // cin + 1))
+        kh = int(rng.integers(1, 8))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        ph, pw = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        dh = int(rng.integers(1, 3))
+        H = int(rng.integers(dh * (kh - 1) + 1, dh * (kh - 1) + 14))
+        W = int(rng.integers(kw, kw + 40))
+        nb = int(rng.integers(1, 4))
+        cout = int(rng.choice([32, 64]))
+        out = str(rng.choice(["f32", "bf16"]))
+        residual = [None, "f32", "bf16"][int(rng.integers(0, 3))]
+        act = str(rng.choice(["none", "relu", "gelu_tanh"]))
+        clamp = None if rng.integers(0, 2) else (-0.5, 0.75)
+        if nb * H * W * cout * kh * kw * cin > 3.0e8:       # keep the oracle quick
+            continue
+        run_conv_case(oracle, (nb, H, W, cin, cout, kh, kw), stride=(sh, sw), pad=(ph, pw), dil=(dh, 1), alpha=0.5 + 0.25 * done % 1.0,
+                      with_bias=bool(rng.integers(0, 2)), residual=residual, beta=-0.5, act=act, clamp=clamp, out=out,
+                      seed=100 + done, expect=ROWS)
+        done += 1
+
+
 def test_conv_few_channels_falls_back(oracle):
     """Shapes the row kernel does not take go to the guarded kernel: other channel counts of the output, a filter
     row longer than 32 elements, a dilated filter row, more than 7 filter rows."""
