@@ -63,8 +63,9 @@ def test_calls_replay_from_a_captured_graph(force, monkeypatch):
 
 
 def test_convolution_rowsum_and_structured_calls_replay_from_a_captured_graph():
-    """The convolution, the row-sum pair (weights stored K x N: no workspace), the diagonal operand and a
-    product with a promised triangular A: kernels only, so their capture replays bit for bit."""
+    """The convolution (gathering kernel and few-channel kernel), the row-sum pair (weights stored K x N: no
+    workspace), the diagonal operand, a product with a promised triangular A, a tall product with 8 columns and a
+    symmetric operand with the caller's workspace: kernels only, so their capture replays bit for bit."""
     import torch
     from paper_2604_01489_amd import inputs as gen
     dev = torch.device("cuda:0")
@@ -79,17 +80,33 @@ def test_convolution_rowsum_and_structured_calls_replay_from_a_captured_graph():
     B = bf16(81, 1, (K, N))
     bias = torch.from_numpy(gen.uniform(81, 2, N, -1.0, 1.0)).to(dev)
     d = torch.from_numpy(gen.uniform(82, 7, K, 0.5, 1.5)).to(dev)
+    X3, W3 = bf16(83, 0, (2, 30, 38, 3)), bf16(83, 1, (64, 7, 7, 3), 147 ** -0.5)
+    Mt, Nt, Kt = 2080, 8, 520
+    At, Bt = bf16(84, 0, (Mt, Kt), Kt ** -0.5), bf16(84, 1, (Kt, Nt))
+    Ms, Ns = 768, 16
+    As, Bs = bf16(85, 0, (Ms, Ms), Ms ** -0.5), bf16(85, 1, (Ms, Ns))
+    sym_args = binding.fused_args(Ms, Ns, Ms, As.data_ptr(), Ms, Bs.data_ptr(), Ns, As.data_ptr(), Ns, a_structure="sym_lower")      # sizes and alignment only
+    ws = torch.empty(max(binding.fused_workspace_bytes(sym_args) // 4, 1), dtype=torch.float32, device=dev)
 
-    def enqueue(Y, C, params, y, D, stream):
+    def enqueue(Y, C, params, y, D, Y3, Ct, Cs, stream):
         binding.conv2d_epilogue_bf16(X, Wt, Y, pad=(1, 1), act="relu", stream=stream)
         binding.gemm_epilogue_bf16_fused(M, N, K, A, K, B, N, C, N, bias=bias, act="relu", a_structure="lower", stream=stream)
         binding.gemm_rowsum_params_bf16(N, K, B, N, False, bias, params, stream=stream)
         binding.gemm_rowsum_bf16(M, K, A, K, params, 0.5, y, stream=stream)
         binding.gemm_epilogue_diag_bf16(K, N, d, B, N, bias, 0.5, "relu", D, N, 1, stream=stream)
+        binding.conv2d_epilogue_bf16(X3, W3, Y3, stride=(2, 2), pad=(3, 3), act="relu", stream=stream)
+        assert binding.last_config() == "conv_bf16_rows_k32"
+        binding.gemm_epilogue_bf16(Mt, Nt, Kt, At, Kt, Bt, Nt, None, 0.5, "gelu_tanh", Ct, Nt, stream=stream)
+        assert binding.last_config().startswith("bf16_skinny")
+        binding.gemm_epilogue_bf16_fused(Ms, Ns, Ms, As, Ms, Bs, Ns, Cs, Ns, act="relu", a_structure="sym_lower", workspace=ws,
+                                         stream=stream)
+        assert binding.last_config().startswith("bf16_symm_lower")
 
     def buffers():
         return [torch.empty(2, 20, 20, 72, dtype=torch.bfloat16, device=dev), torch.empty(M, N, device=dev),
-                torch.empty(K + 1, device=dev), torch.empty(M, device=dev), torch.empty(K, N, device=dev)]
+                torch.empty(K + 1, device=dev), torch.empty(M, device=dev), torch.empty(K, N, device=dev),
+                torch.empty(2, 15, 19, 64, dtype=torch.bfloat16, device=dev), torch.empty(Mt, Nt, device=dev),
+                torch.empty(Ms, Ns, device=dev)]
 
     eager = buffers()
     enqueue(*eager, torch.cuda.current_stream())
