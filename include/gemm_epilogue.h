@@ -109,7 +109,11 @@ ge_status_t gemm_epilogue_bf16(int M, int N, int K,
                                const float *bias, float alpha, ge_act_t act,
                                float *C, int ldc, int batch, void *stream);
 
-/* fp32 operands, fp32 matrix instructions, fp32 output.  Same contract. */
+/* fp32 operands, fp32 matrix instructions, fp32 output.  Same contract.  A product whose tiles
+ * would leave more than half of the CUs idle and whose K is long is sliced over K and summed in slice
+ * order (bitwise repeatable); this call has no workspace argument, so its partial sums always go to
+ * the library's buffer of the stream (see "Partial results" above: inside a stream capture such a
+ * call needs one earlier call of the same size on that stream, else GE_ERR_WORKSPACE). */
 ge_status_t gemm_epilogue_f32(int M, int N, int K,
                               const float *A, int lda,
                               const float *B, int ldb,

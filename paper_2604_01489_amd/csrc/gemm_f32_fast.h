@@ -11,7 +11,9 @@
 //     MFMAs; the k each lane group contributes to an MFMA is a free choice as long as A and B
 //     agree, here k = 8*rho + 4*(lane/32) + e for read rho, element e.  B fragments: ds_read_b32 of
 //     B[k][n = lane%32], consecutive lanes on consecutive addresses;
-//   * epilogue in registers: a store instruction writes 128 contiguous bytes of 2 rows.
+//   * epilogue in registers: a store instruction writes 128 contiguous bytes of 2 rows;
+//   * K slices (few tiles, long K): block slice s walks k in [s kPerSlice, (s + 1) kPerSlice) and, RAW,
+//     leaves its sums unscaled in the workspace W[s][batch][M][N] for the second pass.
 // Resources carry the exact extent of the operands, so a wrong offset reads zeros, never faults.
 #pragma once
 #include "bf16_layout.h"
@@ -34,7 +36,7 @@ struct F32Tile {
     static_assert((BN & (BN - 1)) == 0 && BN >= 64, "BN must be a power of two, at least 64");
 };
 
-template <int BM, int BN, bool EDGE>
+template <int BM, int BN, bool EDGE, bool RAW = false>
 __global__ void __launch_bounds__(256)
 gemm_f32_fast_kernel(const GemmParams p)
 {
@@ -49,10 +51,12 @@ gemm_f32_fast_kernel(const GemmParams p)
 
     const TileCoord tc = map_block(p);
     const int m0 = tc.tm * BM, n0 = tc.tn * BN;
-    const int nk = (p.K + BK - 1) / BK;
+    const int kBegin = tc.s * p.kPerSlice;                  // the whole K range when there are no slices
+    const int kLen = min(p.K, kBegin + p.kPerSlice) - kBegin;
+    const int nk = (kLen + BK - 1) / BK;
 
-    const long long offA = 4 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda);
-    const long long offB = 4 * ((long long)tc.b * p.strideB + n0);
+    const long long offA = 4 * ((long long)tc.b * p.strideA + (long long)m0 * p.lda + kBegin);
+    const long long offB = 4 * ((long long)tc.b * p.strideB + (long long)kBegin * p.ldb + n0);
     const char *gA = (const char *)p.A + offA;
     const char *gB = (const char *)p.B + offB;
 
@@ -81,7 +85,7 @@ gemm_f32_fast_kernel(const GemmParams p)
         const unsigned leftB = records_left(p.bytesB, offB + stepB);
         const rsrc_words_t rA = make_rsrc(gA + stepA, kt < nk ? leftA : 0u);
         const rsrc_words_t rB = make_rsrc(gB + stepB, kt < nk ? leftB : 0u);
-        const int kLeft = p.K - kt * BK;
+        const int kLeft = kLen - kt * BK;
         GE_LDS char *dA = ldsBase + stage * T::A_BYTES;
         GE_LDS char *dB = ldsBase + 4 * T::A_BYTES + stage * T::B_BYTES;
 #pragma unroll
@@ -172,14 +176,14 @@ gemm_f32_fast_kernel(const GemmParams p)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-    float *cBase = p.C + (long long)tc.b * p.strideC;
+    float *cBase = p.C + (long long)tc.b * p.strideC + (RAW ? (long long)tc.s * p.sliceStride : 0ll);
     const int rowLane = m0 + wm * T::WTM + 4 * g;
     const int colLane = n0 + wn * T::WTN + l32;
     float bv[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = colLane + j * 32;
-        bv[j] = (p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
+        bv[j] = (!RAW && p.bias != nullptr && (!EDGE || n < p.N)) ? p.bias[n] : 0.0f;
     }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -189,7 +193,7 @@ gemm_f32_fast_kernel(const GemmParams p)
             float *rowPtr = cBase + (long long)m * p.ldc + colLane;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const float v = epilogue_value_rt(acc[i][j][r], p.alpha, bv[j], p.act);
+                const float v = RAW ? acc[i][j][r] : epilogue_value_rt(acc[i][j][r], p.alpha, bv[j], p.act);
                 if (!EDGE || (m < p.M && colLane + j * 32 < p.N)) rowPtr[j * 32] = v;
             }
         }

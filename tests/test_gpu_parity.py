@@ -89,6 +89,25 @@ def test_f32_fast_kernels(oracle):
     assert cfg == "f32_generic_128x128x16"
 
 
+def test_f32_k_slices(oracle):
+    """Few tiles and a long K: the fp32 kernels slice K (direct-to-LDS kernel on both tiles, full and ragged slices;
+    the guarded kernel), partial sums added in slice order by the second pass: matches the oracle, repeats bit for bit."""
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 4096, alpha=0.5, act="gelu_tanh", seed=40)
+    assert cfg == "f32_64x64x16_w4_splitk"
+    _, _, _, cfg = run_case(oracle, "f32", 200, 136, 2076, alpha=0.25, act="relu", seed=41, lda=2080, ldb=140, ldc=137)
+    assert cfg == "f32_64x64x16_w4_splitk"                      # ragged tiles, K not a multiple of 16
+    _, _, _, cfg = run_case(oracle, "f32", 2048, 1024, 2048, act="none", with_bias=False, seed=42)
+    assert cfg == "f32_128x128x16_w4_splitk"                    # 128 tiles of 128 x 128: two slices
+    _, _, _, cfg = run_case(oracle, "f32", 130, 257, 2075, alpha=0.5, act="relu", seed=43)
+    assert cfg == "f32_generic_128x128x16_splitk"
+    _, _, _, cfg = run_case(oracle, "f32", 128, 64, 1536, batch=3, act="none", seed=44)
+    assert cfg == "f32_64x64x16_w4_splitk"
+    outs = [run_case(oracle, "f32", 256, 256, 4096, alpha=0.5, act="gelu_tanh", seed=40)[0].tobytes() for _ in range(2)]
+    assert outs[0] == outs[1]
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 512, act="none", seed=45)       # K too short to slice
+    assert cfg == "f32_64x64x16_w4"
+
+
 def test_f32_layouts(oracle):
     run_case(oracle, "f32", 200, 136, 72, lda=76, ldb=140, ldc=137, act="relu", seed=3)
     run_case(oracle, "f32", 200, 136, 72, lda=75, ldb=139, ldc=137, act="relu", seed=4)
