@@ -69,7 +69,7 @@ _F32 = ("bf16_layout.h", "ge_device.h", "gemm_f32_fast.h")
 # workload -> (kernel configuration, FETCH_SIZE KiB, WRITE_SIZE KiB, source files, their hash)
 # TRAFFIC-BEGIN (rows written from the counter runs; see profiles/)
 TRAFFIC = {
-    "c1_f32_256": ("f32_64x64x16_w4", 826, 256, _F32, "16e8b58ad3582ac4"),
+    "c1_f32_256": ("f32_small_32x32_k4", 1234, 256, ('ge_device.h', 'gemm_f32_small.h'), "f2982a669e15793b"),
     "c2_bf16_4096": ("bf16_256x256x64_w4", 98453, 65536, _MAIN_W4, "a647dac677fa53c8"),
     "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 803321, 262258, _MAIN_W4, "a647dac677fa53c8"),
     "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16485, 262159, _MAIN_W8, "c0cbc78b10224327"),

@@ -75,7 +75,7 @@ def test_f32(oracle, M, N, K):
 
 def test_f32_fast_kernels(oracle):
     """direct-to-LDS fp32 kernels: 64x64 and 128x128 tiles, full and ragged, several K tiles"""
-    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 256, act="none", with_bias=False, seed=30)
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 272, act="none", with_bias=False, seed=30)
     assert cfg == "f32_64x64x16_w4"
     _, _, _, cfg = run_case(oracle, "f32", 1024, 2048, 64, alpha=0.5, act="gelu_tanh", seed=31)
     assert cfg == "f32_128x128x16_w4"
@@ -104,7 +104,26 @@ def test_f32_k_slices(oracle):
     assert cfg == "f32_64x64x16_w4_splitk"
     outs = [run_case(oracle, "f32", 256, 256, 4096, alpha=0.5, act="gelu_tanh", seed=40)[0].tobytes() for _ in range(2)]
     assert outs[0] == outs[1]
-    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 512, act="none", seed=45)       # K too short to slice
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 528, act="none", seed=45)       # K too short to slice
+    assert cfg == "f32_64x64x16_w4"
+
+
+def test_f32_small_products(oracle):
+    """Small fp32 products (the 256^3 workload's class): 32 x 32 tiles whose four waves share K and add their partial
+    tiles through LDS in wave order; one chunk of 64 k per wave, two and three (the prefetch's both buffers);
+    batches, padded leading dimensions, every activation; exact on integers; repeatable bit for bit."""
+    small = "f32_small_32x32_k4"
+    _, _, _, cfg = run_case(oracle, "f32", 256, 256, 256, act="none", with_bias=False, seed=50)
+    assert cfg == small
+    _, _, _, cfg = run_case(oracle, "f32", 512, 512, 512, alpha=0.5, act="gelu_tanh", seed=51)
+    assert cfg == small
+    _, _, _, cfg = run_case(oracle, "f32", 32, 64, 768, alpha=0.25, act="relu", seed=52, lda=772, ldb=68, ldc=65)
+    assert cfg == small
+    _, _, _, cfg = run_case(oracle, "f32", 64, 96, 256, batch=3, act="relu", seed=53)
+    assert cfg == small
+    outs = [run_case(oracle, "f32", 256, 256, 256, alpha=0.5, act="gelu_tanh", seed=54)[0].tobytes() for _ in range(2)]
+    assert outs[0] == outs[1]
+    _, _, _, cfg = run_case(oracle, "f32", 256, 264, 256, act="none", seed=55)       # N not a multiple of 32
     assert cfg == "f32_64x64x16_w4"
 
 
