@@ -87,6 +87,9 @@ def test_conv_workspace_query(lib):
     n = binding.conv_workspace_bytes(late)
     assert n > 0 and n % (32 * 7 * 7 * 512 * 4) == 0
     assert binding.conv_workspace_bytes(early) == 0 and binding.conv_workspace_bytes(bad) == 0
+    # few input channels: the row kernel runs in one pass whatever the guarded kernel's planner would have sliced
+    first = binding.conv_args((1, 12, 12, 3, 64, 7, 7), P, P, P, stride=(2, 2), pad=(3, 3), y_type="bf16")
+    assert binding.conv_workspace_bytes(first) == 0
     # a workspace that is too small or misaligned is refused before anything is enqueued
     small = binding.conv_args((32, 7, 7, 512, 512, 3, 3), P, P, P, pad=(1, 1), y_type="bf16", workspace_ptr=P,
                               workspace_bytes=n - 1)
