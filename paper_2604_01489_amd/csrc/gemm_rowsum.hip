@@ -199,10 +199,11 @@ __device__ inline void block_vector_sum(int n, const float *__restrict__ x, floa
 }
 
 // s[c] = sum of the chunks' partial sums; the block past the last column block adds up the bias into
-// s[C].  A block covers 32 columns with 8 threads each: thread g of a column adds chunks g, g + 8, ...
-// in ascending order, then the 8 sums are added in the order of g (one thread per column over all
-// chunks left the pass at the latency of a chain of dependent loads: 10 us for 2 MB).
-constexpr int kFinishCols = 32, kFinishWays = 8;
+// s[C].  A block covers 64 columns: 16 groups of 16 threads, a thread 4 consecutive columns (16 bytes per
+// load).  Group g adds chunks g, g + 16, ... in ascending order, eight loads in flight at a time, then
+// the 16 sums are added in the order of g (32 groups of 8 threads: the same 5 us, a launch and a round trip).  (One thread per column over all chunks left the pass at
+// the latency of a chain of dependent loads: 10 us for 2 MB; 8 groups of single columns: 6.9 us.)
+constexpr int kFinishCols = 64, kFinishWays = 16;
 __global__ void __launch_bounds__(256)
 cols_finish_kernel(int C, int chunks, const float *__restrict__ partial, float *__restrict__ s, int nBias,
                    const float *__restrict__ bias)
@@ -212,18 +213,46 @@ cols_finish_kernel(int C, int chunks, const float *__restrict__ partial, float *
         return;
     }
     __shared__ float part[kFinishWays][kFinishCols];
-    const int g = threadIdx.x / kFinishCols, cl = threadIdx.x % kFinishCols;
+    const int g = threadIdx.x / (kFinishCols / 4), cl = (threadIdx.x % (kFinishCols / 4)) * 4;
     const int c = blockIdx.x * kFinishCols + cl;
-    float acc = 0.0f;
-    if (c < C)
-        for (int q = g; q < chunks; q += kFinishWays) acc += partial[(long long)q * C + c];
-    part[g][cl] = acc;
-    __syncthreads();
-    if (g == 0 && c < C) {
-        float t = part[0][cl];
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const bool vec = (C % 4 == 0) && c + 4 <= C;          // rows of the partial sums are then 16-byte aligned
+    for (int q0 = g; q0 < chunks; q0 += 8 * kFinishWays) {
+        float v[8][4];
 #pragma unroll
-        for (int k = 1; k < kFinishWays; ++k) t += part[k][cl];
-        s[c] = t;
+        for (int u = 0; u < 8; ++u) {
+            const int q = q0 + u * kFinishWays;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[u][e] = 0.0f;
+            if (q < chunks) {
+                const float *src = partial + (long long)q * C + c;
+                if (vec) {
+                    const ge::f32x4_t t = *(const ge::f32x4_t *)src;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[u][e] = t[e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c + e < C) v[u][e] = src[e];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += v[u][e];
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) part[g][cl + e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < kFinishCols) {
+        const int cc = blockIdx.x * kFinishCols + threadIdx.x;
+        if (cc < C) {
+            float t = part[0][threadIdx.x];
+#pragma unroll
+            for (int k = 1; k < kFinishWays; ++k) t += part[k][threadIdx.x];
+            s[cc] = t;
+        }
     }
 }
 
