@@ -80,7 +80,7 @@ TRAFFIC = {
     "c9_diag_bf16_8192": ("diag_rows_vec4", 65967, 262563, ('gemm_diag.hip',), "95489dc912964713"),
     "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", 100752, 50176, _MAIN_W8, "c0cbc78b10224327"),
     "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 600771, 262144, _MAIN_W4, "a647dac677fa53c8"),
-    "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133341, 4356, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
+    "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133354, 4359, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
     "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 784003, 262144, _F32, "16e8b58ad3582ac4"),
     "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16596, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "13cc16fa399a445d"),
     "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146163, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "ad6151516cd89209"),
