@@ -11,7 +11,7 @@ JSON line with the whole-job rate, the roofline fraction of the dominant kernel
 (algorithmic FLOP or bytes per launch over the launch time measured with HIP
 events on the launch stream) and the CPU oracle timed on a sample of the same
 workload (`--oracle-rows`; the default is every row of C at 8192^3, about 15 s on the 16
-host cores of a GPU machine; the widened operator's oracle takes 512 rows).
+host cores; the widened operator's oracle takes 512 rows).
 fp32 workloads (c1_f32_256, c13_f32_8192x8192x2048) are measured against the fp32 matrix peak.
 """
 from __future__ import annotations

@@ -261,7 +261,7 @@ def calibrate():
 
 RATES_HEADER = """// Rates of the planner's cost model (plan_cost_us in gemm_epilogue_api.hip), in microseconds.
 // GENERATED by `python -m paper_2604_01489_amd.tune --calibrate --write` on one MI355X; the run that
-// produced these numbers is summarised in profiles/planner_calibration.md.  The model ranks structures,
+// produced these numbers is kept with the profile summaries.  The model ranks structures,
 // it does not predict times: regenerate on a part whose clocks differ, do not edit by hand.
 #pragma once
 
