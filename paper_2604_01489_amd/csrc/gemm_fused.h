@@ -200,8 +200,16 @@ splitk_reduce_fused_kernel(const GemmParams p, const float *__restrict__ W)
         const long long bm = e / p.N;
         const int m = (int)(bm % p.M);
         const long long b = bm / p.M;
-        float s = W[e];
-        for (int i = 1; i < p.splitK; ++i) s += W[e + (long long)i * p.sliceStride];
+        // the slices in ascending order, eight loads in flight at a time (one by one, behind the loop's test,
+        // a sum of 22 terms was a chain of 22 round trips to memory: 8.4 us for a 1 MB result)
+        float s = 0.0f;
+        for (int i0 = 0; i0 < p.splitK; i0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i0 + u < p.splitK ? W[e + (long long)(i0 + u) * p.sliceStride] : 0.0f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
         fused_store(p, b, m, n, s);
     }
 }
