@@ -396,9 +396,12 @@ ge_status_t ge_release_workspace(void);
  *                   ("generic" also for fp32), whatever the planner would pick
  *   "waves"         "8": full 256 x 256 tiles stay on the eight-wave kernel ("4": default)
  *   "stage_k"       "32": no 64-k load phases in the eight-wave kernel ("64": default)
+ *   "conv_halo"     "off": 3 x 3 convolutions stay on the gathering kernel; "on": the
+ *                   halo-staged kernel for every shape it can take, however few tiles;
+ *                   "14_11" | "12_12": that variant of it for every shape it can take
  * value == NULL restores the default.  Process-wide, effective from the next call.  The
- * initial values come from the environment variables GE_FORCE_CONFIG, GE_WAVES and
- * GE_STAGE_K, read once when the library is loaded; no entry point reads the
+ * initial values come from the environment variables GE_FORCE_CONFIG, GE_WAVES,
+ * GE_STAGE_K and GE_CONV_HALO, read once when the library is loaded; no entry point reads the
  * environment afterwards.
  * Errors: GE_ERR_NULL (name), GE_ERR_CONFIG (unknown name or value).
  */

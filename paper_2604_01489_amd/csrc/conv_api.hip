@@ -8,6 +8,7 @@
 #include <cstring>
 
 #include "../../include/gemm_epilogue.h"
+#include "conv_halo.h"
 #include "conv_rows.h"
 #include "gemm_bf16_fast.h"
 #include "gemm_fused.h"
@@ -48,8 +49,24 @@ struct ConvPlan {
     long long M, K, xElems;
     bool rows;          // the few-channel kernel: a K step is one filter row
     bool rowsPairs;     //   ... whose input rows are 4-byte aligned and even in length
+    int halo;           // the halo-staged 3 x 3 kernel: 0 no, else 1 + index into kHaloVariants
+    ge_halo::HaloPlan haloPlan;
     Plan pl;
 };
+
+// The variants of the halo-staged kernel that are built: row blocks of 16 positions multiplied for a tile
+// of the first and of the second kind.  14 and 11 serve rows of 49 to 56 positions cut 4 + 3 (residual
+// networks' 56 x 56 images), 12 and 12 any cut of at most 192 positions.
+constexpr int kHaloVariants[2][2] = {{14, 11}, {12, 12}};
+constexpr int kHaloTileOverhead = 2;      // prologue and epilogue of a tile, in row blocks of its main loop
+
+template <int TMB1, int TMB2>
+void launch_halo(const GemmParams &p, const ge::HaloTiles &ht, hipStream_t st)
+{
+    const dim3 grid((unsigned)(ht.tiles1 + ht.tiles2));
+    if (p.cType == ge::DT_BF16) GE_LAUNCH((ge::conv_halo_bf16_kernel<TMB1, TMB2, true>), grid, dim3(256), 0, st, p, ht);
+    else GE_LAUNCH((ge::conv_halo_bf16_kernel<TMB1, TMB2, false>), grid, dim3(256), 0, st, p, ht);
+}
 
 // Workgroups of the few-channel kernel that the device holds at once (they walk over the output rows);
 // a host-side computation of the runtime, nothing is enqueued.
@@ -128,7 +145,28 @@ ge_status_t plan_conv(const ge_conv_args_t &a, ConvPlan *out)
             out->rowsPairs = ((a.W * a.Cin) % 2 == 0) && !(((uintptr_t)a.X) & 3u);
         }
     }
+    // 3 x 3, unit stride and dilation, whole 256-channel tiles, 64-channel pairs of slabs, an output row
+    // with its two halo columns within the 64 positions of a staged row: the halo-staged kernel
+    out->halo = 0;
+    const int haloOpt = opt_conv_halo();
+    if (fast && opt_force_config() == FORCE_NONE && haloOpt != HALO_OFF && a.KH == 3 && a.KW == 3 && a.stride_h == 1 &&
+        a.stride_w == 1 && a.dil_h == 1 && a.dil_w == 1 && a.Cin % 64 == 0 && a.Cout % 256 == 0 && OW <= ge_halo::MAX_OW &&
+        a.pad_w <= 2 && a.pad_h <= 2) {
+        for (int v = 0; v < 2; ++v) {
+            if (haloOpt >= HALO_VARIANT0 && haloOpt != HALO_VARIANT0 + v) continue;
+            const ge_halo::HaloPlan hp = ge_halo::halo_plan(a.N, OH, OW, a.Cout / 256, kNumCU, kHaloTileOverhead,
+                                                             kHaloVariants[v][0], kHaloVariants[v][1]);
+            if (hp.cost < 0) continue;
+            // left to itself: tiles for at least half of the CUs (fewer: the gathering kernel has K slices), and
+            // at least 0.7 of the positions its loops multiply are output positions
+            const long long n1 = (long long)a.N * hp.g1 * (a.Cout / 256), n2 = (long long)a.N * hp.g2 * (a.Cout / 256);
+            const long long multiplied = 16 * (n1 * hp.blocks16a + n2 * hp.blocks16b);
+            if (haloOpt == HALO_AUTO && (n1 + n2 < kNumCU / 2 || 10 * M * (a.Cout / 256) < 7 * multiplied)) continue;
+            if (!out->halo || hp.cost < out->haloPlan.cost) { out->halo = 1 + v; out->haloPlan = hp; }
+        }
+    }
     ge_status_t st = make_plan_bf16((int)M, a.Cout, (int)K, 1, fast, GE_PLAN_AUTO, 0, &out->pl);
+    if (st == GE_OK && out->halo) { out->pl.splitK = 1; out->pl.kPerSlice = (int)K; }
     if (st == GE_OK && out->rows) { out->pl.splitK = 1; out->pl.kPerSlice = (int)K; }
     return st;
 }
@@ -200,6 +238,20 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
             else              { if (h) launch_rows<2, true, false>(p, items, ldsBytes, hs); else launch_rows<2, false, false>(p, items, ldsBytes, hs); }
         }
         g_last_config = "conv_bf16_rows_k32";
+        return ge_host::take_launch_error() != hipSuccess ? GE_ERR_LAUNCH : GE_OK;
+    }
+
+    if (cp.halo) {
+        const ge_halo::HaloPlan &hp = cp.haloPlan;
+        ge::HaloTiles ht{};
+        ht.R1 = hp.R1; ht.g1 = hp.g1; ht.R2 = hp.R2; ht.g2 = hp.g2;
+        ht.tilesN = a.Cout / 256;
+        ht.tiles1 = a.N * hp.g1 * ht.tilesN;
+        ht.tiles2 = a.N * hp.g2 * ht.tilesN;
+        ht.posMul = 65536 / OW + 1;
+        hipStream_t hs = (hipStream_t)stream;
+        if (cp.halo == 1) { launch_halo<kHaloVariants[0][0], kHaloVariants[0][1]>(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_14_11"; }
+        else              { launch_halo<kHaloVariants[1][0], kHaloVariants[1][1]>(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_12_12"; }
         return ge_host::take_launch_error() != hipSuccess ? GE_ERR_LAUNCH : GE_OK;
     }
 

@@ -71,6 +71,10 @@ enum { FORCE_NONE = 0, FORCE_256 = 1, FORCE_128 = 2, FORCE_GENERIC = 3 };
 int opt_force_config();   // FORCE_*
 bool opt_eight_waves();   // keep full 256 x 256 tiles on the eight-wave kernel
 bool opt_stage_k32();     // no 64-k load phases in the eight-wave kernel
+// the halo-staged 3 x 3 convolution kernel: by the plan's rule, never, whenever the shape allows it, or
+// one of its variants whenever the shape allows that one (HALO_VARIANT0 + index)
+enum { HALO_AUTO = 0, HALO_OFF = 1, HALO_ON = 2, HALO_VARIANT0 = 3 };
+int opt_conv_halo();
 
 int choose_split(long long tiles, int K, int minSlice);
 // skinny: the caller can launch the tall-skinny kernel (the plain operator only), so the plan may name it

@@ -25,5 +25,5 @@ def _library_options_back_to_default(request):
     yield
     if request.node.get_closest_marker("gpu") is not None:
         from paper_2604_01489_amd import binding
-        for name in ("force_config", "waves", "stage_k"):
+        for name in ("force_config", "waves", "stage_k", "conv_halo"):
             binding.set_option(name, None)

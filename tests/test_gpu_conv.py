@@ -95,6 +95,87 @@ def test_conv_guarded_kernel(oracle):
     run_conv_case(oracle, (1, 8, 8, 32, 12, 1, 1), seed=32, expect="conv_bf16_generic_64x64x32")   # Cout not a multiple of 8
 
 
+HALO_56 = "conv_bf16_halo_3x3_w4_14_11"
+HALO_ANY = "conv_bf16_halo_3x3_w4_12_12"
+
+
+def test_conv_halo_56_wide(oracle):
+    """3 x 3, stride 1 on 56-wide images: tiles of 4 and of 3 output rows in one launch (8 + 8 per image), the
+    channel slabs walked in pairs, bf16 and fp32 output, one and two tile columns of 256 channels.  (With so few
+    images the plan would take the variant for shorter tiles, whose tiles all run at once: this one is asked for.)"""
+    binding.set_option("conv_halo", "14_11")
+    try:
+        _halo_56_wide_cases(oracle)
+    finally:
+        binding.set_option("conv_halo", None)
+
+
+def _halo_56_wide_cases(oracle):
+    run_conv_case(oracle, (1, 56, 56, 64, 256, 3, 3), pad=(1, 1), act="relu", residual="bf16", out="bf16", seed=90, expect=HALO_56)
+    run_conv_case(oracle, (2, 56, 56, 128, 256, 3, 3), pad=(1, 1), act="gelu_tanh", alpha=0.5, seed=91, expect=HALO_56)
+    run_conv_case(oracle, (1, 56, 56, 64, 512, 3, 3), pad=(1, 1), residual="f32", beta=0.5, clamp=(-0.5, 0.5), out="bf16", seed=92,
+                  expect=HALO_56)
+
+
+@pytest.mark.parametrize("shape,pad,expect", [
+    ((3, 12, 12, 64, 256, 3, 3), (1, 1), HALO_ANY),        # 5 + 5 + 2 rows of 12: ragged last row block
+    ((2, 9, 62, 64, 256, 3, 3), (1, 1), HALO_ANY),         # the widest row: 62 + 2 halo columns = a staged row
+    ((2, 20, 30, 128, 512, 3, 3), (0, 0), HALO_ANY),       # no padding: 18 x 28 outputs, four slabs, two tile columns
+    ((2, 10, 17, 64, 256, 3, 3), (2, 2), HALO_ANY),        # padding 2: two halo rows above the image
+    ((1, 7, 52, 192, 256, 3, 3), (1, 0), HALO_56),         # 50 outputs per row, 4 + 3 rows; six slabs
+    ((3, 12, 12, 64, 256, 3, 3), (1, 1), HALO_56),         # short rows on the 14- and 11-block loops
+    ((5, 1, 1, 64, 256, 3, 3), (1, 1), HALO_ANY),          # one position per image
+])
+def test_conv_halo_geometry(oracle, shape, pad, expect):
+    binding.set_option("conv_halo", "14_11" if expect == HALO_56 else "12_12")
+    try:
+        run_conv_case(oracle, shape, pad=pad, act="relu", seed=sum(shape), expect=expect)
+        run_conv_case(oracle, shape, pad=pad, with_bias=False, residual="bf16", out="bf16", seed=1 + sum(shape), expect=expect)
+    finally:
+        binding.set_option("conv_halo", None)
+
+
+def test_conv_halo_taken_by_default_and_switched_off(oracle):
+    """Tiles for half of the CUs, nearly all of their positions in use: the halo-staged kernel without being asked;
+    "off" keeps the gathering one.  Short rows (a third of the loop's positions in use), few tiles: not taken."""
+    assert "halo" not in run_conv_case(oracle, (32, 20, 12, 64, 256, 3, 3), pad=(1, 1), seed=94)
+    assert "halo" not in run_conv_case(oracle, (8, 6, 62, 64, 256, 3, 3), pad=(1, 1), seed=94)
+    shape = (64, 6, 62, 64, 256, 3, 3)                       # 64 images x 2 tiles of 3 rows of 62
+    run_conv_case(oracle, shape, pad=(1, 1), act="relu", out="bf16", seed=95, expect=HALO_ANY)
+    binding.set_option("conv_halo", "off")
+    try:
+        assert "halo" not in run_conv_case(oracle, shape, pad=(1, 1), act="relu", out="bf16", seed=95)
+    finally:
+        binding.set_option("conv_halo", None)
+    # shapes it does not take: stride 2, 5 x 5, Cin not a multiple of 64, Cout not a multiple of 256, rows too wide
+    binding.set_option("conv_halo", "on")
+    try:
+        for shape, kw in [((1, 16, 16, 64, 256, 3, 3), dict(stride=(2, 2), pad=(1, 1))), ((1, 16, 16, 64, 256, 5, 5), dict(pad=(2, 2))),
+                          ((1, 16, 16, 96, 256, 3, 3), dict(pad=(1, 1))), ((1, 16, 16, 64, 128, 3, 3), dict(pad=(1, 1))),
+                          ((1, 4, 70, 64, 256, 3, 3), dict(pad=(1, 1))), ((1, 16, 16, 64, 256, 3, 3), dict(pad=(1, 1), dil=(2, 2)))]:
+            cfg = run_conv_case(oracle, shape, seed=96, **kw)
+            assert "halo" not in cfg, cfg
+    finally:
+        binding.set_option("conv_halo", None)
+
+
+def test_conv_halo_is_repeatable():
+    import torch
+    binding.set_option("conv_halo", "14_11")
+    from paper_2604_01489_amd import inputs as gen
+    X = torch.from_numpy(gen.to_bf16_bits(gen.normal(97, 0, 2 * 56 * 56 * 64, 1.0).reshape(2, 56, 56, 64)).view(np.int16)).cuda()
+    Wt = torch.from_numpy(gen.to_bf16_bits(gen.normal(97, 1, 256 * 9 * 64, 0.05).reshape(256, 3, 3, 64)).view(np.int16)).cuda()
+    outs = []
+    for _ in range(3):
+        Y = torch.empty(2, 56, 56, 256, dtype=torch.bfloat16, device="cuda:0")
+        binding.conv2d_epilogue_bf16(X, Wt, Y, pad=(1, 1), act="relu")
+        torch.cuda.synchronize()
+        assert binding.last_config() == HALO_56
+        outs.append(Y.view(torch.int16).cpu().numpy().tobytes())
+    binding.set_option("conv_halo", None)
+    assert outs[0] == outs[1] == outs[2]
+
+
 ROWS = "conv_bf16_rows_k32"
 
 

@@ -190,8 +190,17 @@ def _run_conv_workload(oracle, name, expect, imgs):
 
 def test_c10_conv_full(oracle):
     """The 3x3 convolution workload at full size: first and last image (first and last tiles of the implicit
-    GEMM) against the convolution oracle, every position and channel."""
-    _run_conv_workload(oracle, "c10_conv3x3_256_bf16out", "conv_bf16_256x256x32_w8", [0, 31])
+    GEMM) and one in the middle against the convolution oracle, every position and channel: on the halo-staged
+    kernel, which the plan picks (tiles of 4 and of 3 output rows, one of each per CU), and on the gathering kernel;
+    the two outputs also against each other over all images."""
+    import torch
+    from paper_2604_01489_amd import binding
+    Yh, _ = _run_conv_workload(oracle, "c10_conv3x3_256_bf16out", "conv_bf16_halo_3x3_w4_14_11", [0, 13, 31])
+    binding.set_option("conv_halo", "off")
+    Yg, _ = _run_conv_workload(oracle, "c10_conv3x3_256_bf16out", "conv_bf16_256x256x32_w8", [0, 31])
+    # same products, summed in a different order, rounded to bf16: within two units in the last place of each other
+    diff = (Yh.to(torch.float32) - Yg.to(torch.float32)).abs()
+    assert bool((diff <= 2.0 ** -7 * torch.maximum(Yg.to(torch.float32).abs(), torch.tensor(2.0 ** -3, device="cuda:0"))).all())
 
 
 def test_c15_conv_first_layer_full(oracle):

@@ -47,3 +47,15 @@ def test_conv_rows_kernel_layout_model(tmp_path):
     res = subprocess.run([exe], capture_output=True, text=True)
     assert res.returncode == 0, res.stdout[-2000:]
     assert "conv rows layout checks passed" in res.stdout
+
+
+def test_conv_halo_kernel_layout_model(tmp_path):
+    """The same for the halo-staged 3 x 3 convolution kernel (csrc/conv_halo_layout.h): the staged input rows, every
+    tap's fragments against the definition of the gather, bank groups, and the plan's cuts against a simulation."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "conv_halo_layout_check")
+    subprocess.run(["g++", "-std=c++17", "-O1", "-o", exe, os.path.join(root, "tests", "conv_halo_layout_check.cpp")],
+                   check=True)
+    res = subprocess.run([exe], capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    assert "conv halo layout checks passed" in res.stdout
