@@ -78,7 +78,7 @@ TRAFFIC = {
     "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 852644, 131072, _MAIN_W8, "c0cbc78b10224327"),
     "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", 16650, 131072, _MAIN_W8, "c0cbc78b10224327"),
     "c9_diag_bf16_8192": ("diag_rows_vec4", 65967, 262563, ('gemm_diag.hip',), "95489dc912964713"),
-    "c10_conv3x3_256_bf16out": ("conv_bf16_256x256x32_w8", 100752, 50176, _MAIN_W8, "c0cbc78b10224327"),
+    "c10_conv3x3_256_bf16out": ("conv_bf16_halo_3x3_w4_14_11", 60910, 50180, ('bf16_layout.h', 'conv_halo.h', 'conv_halo_launch.h', 'conv_halo_layout.h', 'ge_device.h', 'gemm_bf16_fast.h'), "2c897a6ab3fc04ab"),
     "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 600771, 262144, _MAIN_W4, "a647dac677fa53c8"),
     "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133354, 4359, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
     "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 784003, 262144, _F32, "16e8b58ad3582ac4"),

@@ -14,7 +14,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgemm_epilogue.so")
 PROBES_LIB = os.path.join(HERE, "libge_probes.so")
-LIB_SOURCES = ["gemm_fused_api.hip", "gemm_epilogue_api.hip", "gemm_symm_api.hip", "conv_api.hip", "gemm_diag.hip", "gemm_rowsum.hip"]
+# the longest compiles first (the pool takes the sources in this order)
+LIB_SOURCES = ["conv_halo_14_11.hip", "conv_halo_12_12.hip", "conv_api.hip", "gemm_fused_t256.hip", "gemm_fused_t256_edge.hip", "gemm_fused_t128.hip", "gemm_fused_t128_edge.hip",
+               "gemm_fused_w4_e0.hip", "gemm_fused_w4_e1.hip", "gemm_fused_w4_e2.hip", "gemm_epilogue_api.hip",
+               "gemm_fused_api.hip", "gemm_symm_api.hip", "gemm_diag.hip", "gemm_rowsum.hip"]
 PROBE_SOURCES = ["ge_probes.hip"]
 SOURCES = LIB_SOURCES + PROBE_SOURCES
 # packed fp32 instructions are kept off: some of their forms have misbehaved on this hardware
@@ -57,7 +60,7 @@ def build_library(verbose: bool = False, extra_flags=(), incremental: bool = Fal
             raise RuntimeError(f"hipcc failed on {src}")
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as pool:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as pool:
         objs = list(pool.map(compile_one, SOURCES))
     n = len(LIB_SOURCES)
     for out, group in ((LIB, objs[:n]), (PROBES_LIB, objs[n:])):

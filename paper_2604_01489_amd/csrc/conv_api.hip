@@ -8,7 +8,7 @@
 #include <cstring>
 
 #include "../../include/gemm_epilogue.h"
-#include "conv_halo.h"
+#include "conv_halo_launch.h"
 #include "conv_rows.h"
 #include "gemm_bf16_fast.h"
 #include "gemm_fused.h"
@@ -57,16 +57,8 @@ struct ConvPlan {
 // The variants of the halo-staged kernel that are built: row blocks of 16 positions multiplied for a tile
 // of the first and of the second kind.  14 and 11 serve rows of 49 to 56 positions cut 4 + 3 (residual
 // networks' 56 x 56 images), 12 and 12 any cut of at most 192 positions.
-constexpr int kHaloVariants[2][2] = {{14, 11}, {12, 12}};
+constexpr int kHaloVariants[2][2] = {{14, 11}, {12, 12}};     // launch_conv_halo_14_11, launch_conv_halo_12_12
 constexpr int kHaloTileOverhead = 2;      // prologue and epilogue of a tile, in row blocks of its main loop
-
-template <int TMB1, int TMB2>
-void launch_halo(const GemmParams &p, const ge::HaloTiles &ht, hipStream_t st)
-{
-    const dim3 grid((unsigned)(ht.tiles1 + ht.tiles2));
-    if (p.cType == ge::DT_BF16) GE_LAUNCH((ge::conv_halo_bf16_kernel<TMB1, TMB2, true>), grid, dim3(256), 0, st, p, ht);
-    else GE_LAUNCH((ge::conv_halo_bf16_kernel<TMB1, TMB2, false>), grid, dim3(256), 0, st, p, ht);
-}
 
 // Workgroups of the few-channel kernel that the device holds at once (they walk over the output rows);
 // a host-side computation of the runtime, nothing is enqueued.
@@ -250,8 +242,8 @@ extern "C" ge_status_t conv2d_epilogue_bf16(const ge_conv_args_t *args, void *st
         ht.tiles2 = a.N * hp.g2 * ht.tilesN;
         ht.posMul = 65536 / OW + 1;
         hipStream_t hs = (hipStream_t)stream;
-        if (cp.halo == 1) { launch_halo<kHaloVariants[0][0], kHaloVariants[0][1]>(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_14_11"; }
-        else              { launch_halo<kHaloVariants[1][0], kHaloVariants[1][1]>(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_12_12"; }
+        if (cp.halo == 1) { launch_conv_halo_14_11(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_14_11"; }
+        else              { launch_conv_halo_12_12(p, ht, hs); g_last_config = "conv_bf16_halo_3x3_w4_12_12"; }
         return ge_host::take_launch_error() != hipSuccess ? GE_ERR_LAUNCH : GE_OK;
     }
 

@@ -24,18 +24,11 @@
 // Needs: 3 x 3 filter, unit strides and dilations, OW + 2 <= 64, Cin a multiple of 64, Cout a multiple
 // of 256, X and Wt 16-byte aligned, the input smaller than 2 GiB; bf16 output in 16-byte row pieces.
 #pragma once
+#include "conv_halo_launch.h"
 #include "conv_halo_layout.h"
 #include "gemm_bf16_fast.h"
 
 namespace ge {
-
-struct HaloTiles {
-    int R1, g1, R2, g2;
-    int tiles1;       // blocks of the first kind: images * g1 * tilesN; the rest are of the second
-    int tiles2;
-    int tilesN;       // Cout / 256
-    int posMul;       // floor(65536 / OW) + 1: pos / OW == (pos * posMul) >> 16 for pos < 256
-};
 
 struct HaloGeom {
     static constexpr int NSTG = 6;                                 // filter stages: loads run six steps ahead
@@ -57,6 +50,26 @@ constexpr int loads_in_last_four_steps(int tap)
 }
 static_assert(ge_halo::HALO_ROWS == 7, "the halo loads of steps 0..3 cover seven rows");
 
+// s_waitcnt vmcnt(N) lgkmcnt(0) as an instruction the compiler sees.  Written as inline assembly, the wait
+// is opaque to the compiler's own bookkeeping of LDS reads: it goes on believing that the fragment reads of
+// the step before are still on their way and guards the first MFMAs of a step with waits of its own --
+// "at most 3, 2, 1 LDS operations outstanding" -- which by then count the reads just issued for the next
+// step, so each such wait stalls the wave for a round trip to LDS (four per step: 0.18 us of a 0.63 us step).
+template <int N>
+__device__ __forceinline__ void wait_loads_and_lds()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    // vmcnt[3:0] | expcnt[6:4] = 7 (none) | lgkmcnt[11:8] = 0 | vmcnt[5:4] at [15:14]
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+}
+
+// lds_dma16 with a scalar byte offset into the buffer on top of the lane's
+__device__ inline void lds_dma16_at(rsrc_words_t rs, unsigned ldsAddr, unsigned voff, unsigned soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(ldsAddr), "v"(voff), "s"(rs), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory", "m0");
+}
+
 // ids of a launch's blocks go round the 8 XCDs; give each XCD a contiguous run of the `total` logical ids
 __device__ inline unsigned xcd_contiguous(unsigned id, unsigned total)
 {
@@ -70,7 +83,7 @@ __device__ __forceinline__ void conv_halo_tile(const GemmParams &p, GE_LDS char 
     using namespace ge_halo;
     using G = HaloGeom;
     constexpr int TN = 4, NW = 4, NMFMA = TMB * TN, NREAD = TMB + TN, NSTG = G::NSTG;
-    static_assert(2 * NREAD <= NMFMA && NMFMA >= 24, "a step has room for its loads and fragment reads");
+    static_assert(2 * NREAD <= NMFMA && NMFMA >= 28, "a step has room for its loads and fragment reads");
     static_assert(18 % NSTG == 0 && NSTG == 6, "the ring divides the 18 steps of the loop body; two lane bases cover six stages");
 
     const int lane = threadIdx.x & 63;
@@ -87,21 +100,23 @@ __device__ __forceinline__ void conv_halo_tile(const GemmParams &p, GE_LDS char 
         const int iw = halo_slot_col(w, lane) - p.convPw;
         voffH = (iw >= 0 && iw < p.convW) ? (unsigned)(iw * Cin * 2 + halo_slot_chunk(w, lane) * 16) : OOB_OFFSET;
     }
-    // resource of halo row j of channel slab `slab`: nothing is read for a row outside the image or the
-    // tile's halo, or for a slab past the last (a zero-length resource; selected without a branch, the
-    // steps of the main loop are straight-line code)
+    // One resource for the halo and one for the filters for the whole tile; a load's place in the operand is
+    // its scalar offset (halo: row j of channel slab `slab`; filters: 32 channels of tap `tap` in slab `slab`),
+    // so a step spends a handful of scalar instructions on its loads.  A load that must fetch nothing (a
+    // halo row outside the image or beyond the tile's R + 2, a slab past the last) has the out-of-range
+    // bit ORed into its lane offsets: zeros land, no memory is touched.
     const long long rowBytes = (long long)p.convW * Cin * 2;
-    const long long haloBase = ((long long)img * p.convH + ihTop) * rowBytes;
+    const long long haloBase = ((long long)img * p.convH + ihTop) * rowBytes;      // may lie before X: rows above the image are dead
     unsigned liveRows = 0u;
 #pragma unroll
     for (int j = 0; j < HALO_ROWS; ++j) {
         const int ih = ihTop + j;
         liveRows |= ((unsigned)(j < R + 2) & (unsigned)(ih >= 0) & (unsigned)(ih < p.convH)) << j;
     }
-    auto halo_rsrc = [&](int j, int slab) {
-        const unsigned live = (liveRows >> j) & (unsigned)(slab < nSlabs) & 1u;
-        return make_rsrc((const char *)p.A + haloBase + j * rowBytes + slab * 64, (0u - live) & RSRC_RECORDS);
-    };
+    const rsrc_words_t rH = make_rsrc((const char *)p.A + haloBase, RSRC_RECORDS);
+    const unsigned rowBytes32 = (unsigned)rowBytes;                                 // the input is smaller than 2 GiB
+    auto halo_soff = [&](int j, int slab) { return (unsigned)j * rowBytes32 + (unsigned)slab * 64u; };
+    auto halo_dead = [&](int j, int slab) { return (0u - (1u ^ ((liveRows >> j) & (unsigned)(slab < nSlabs) & 1u))) & OOB_OFFSET; };
 
     // ---- filter loads: 256 rows of 64 bytes, the k-contiguous stage of the GEMM kernels ----------
     const char *gB = (const char *)p.B + (long long)n0 * p.ldb * 2;
@@ -109,11 +124,23 @@ __device__ __forceinline__ void conv_halo_tile(const GemmParams &p, GE_LDS char 
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         voffB[j] = (unsigned)a_slot_row(j * NW + w, lane) * (unsigned)p.ldb * 2u + (unsigned)a_slot_chunk(lane) * 16u;
-    auto filt_rsrc = [&](int tap, int slab) {
-        return make_rsrc(gB + ((long long)tap * Cin + slab * 32) * 2, (0u - (unsigned)(slab < nSlabs)) & RSRC_RECORDS);
-    };
+    const rsrc_words_t rB = make_rsrc(gB, RSRC_RECORDS);
+    const unsigned cin2 = (unsigned)Cin * 2u;
+    auto filt_soff = [&](int tap, int slab) { return (unsigned)tap * cin2 + (unsigned)slab * 64u; };
+    auto filt_dead = [&](int slab) { return (0u - (unsigned)(slab >= nSlabs)) & OOB_OFFSET; };
 
     const unsigned ldsBase = (unsigned)(size_t)smem;
+
+    // the halo of slab 0 and the filter stages of steps 0..5 are on their way before anything else is set up
+#pragma unroll
+    for (int j = 0; j < HALO_ROWS; ++j)
+        lds_dma16_at(rH, ldsBase + (unsigned)(j * HALO_ROW_BYTES + w * 1024), voffH | halo_dead(j, 0), halo_soff(j, 0));
+#pragma unroll
+    for (int t = 0; t < NSTG; ++t) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+            lds_dma16_at(rB, ldsBase + (unsigned)(G::B_BASE + t * G::B_STAGE + (d * NW + w) * 1024), voffB[d] | filt_dead(0), filt_soff(t, 0));
+    }
 
     // ---- fragment read addresses: one lane base per row block and filter column ------------------
     unsigned aAddr[3][TMB], bAddr[2];
@@ -174,42 +201,38 @@ __device__ __forceinline__ void conv_halo_tile(const GemmParams &p, GE_LDS char 
 #define GE_HALO_STEP(TAP, PAR, CU, NX)                                                                 \
     {                                                                                                  \
         constexpr int K_ = (PAR) * 9 + (TAP);                                                          \
-        const rsrc_words_t rB_ = filt_rsrc(((TAP) + NSTG) % 9, s + (PAR) + ((TAP) + NSTG) / 9);        \
-        rsrc_words_t rH0_ = rB_, rH1_ = rB_;                                                           \
-        if (halo_loads_in_step(TAP) > 0) rH0_ = halo_rsrc(2 * (TAP), s + (PAR) + 1);                   \
-        if (halo_loads_in_step(TAP) > 1) rH1_ = halo_rsrc(2 * (TAP) + 1, s + (PAR) + 1);               \
-        __builtin_amdgcn_sched_barrier(0);                                                             \
+        unsigned soffB_ = 0u, deadB_ = 0u, soffH0_ = 0u, deadH0_ = 0u, soffH1_ = 0u, deadH1_ = 0u;     \
         _Pragma("unroll") for (int q = 0; q < NMFMA; ++q) {                                            \
             GE_HALO_MFMA(q / TN, q % TN, CU);                                                          \
-            if (q == 0 && halo_loads_in_step(TAP) > 0)                                                 \
-                lds_dma16(rH0_, ldsBase + (unsigned)((((PAR) + 1) & 1) * G::HALO_BUF + 2 * (TAP) * HALO_ROW_BYTES + w * 1024), voffH); \
-            if (q == 2 && halo_loads_in_step(TAP) > 1)                                                 \
-                lds_dma16(rH1_, ldsBase + (unsigned)((((PAR) + 1) & 1) * G::HALO_BUF + (2 * (TAP) + 1) * HALO_ROW_BYTES + w * 1024), voffH); \
-            if (q % 2 == 0 && q >= 4 && q < 12)                                                        \
-                lds_dma16(rB_, ldsBase + (unsigned)(G::B_BASE + (K_ % NSTG) * G::B_STAGE + (((q - 4) / 2) * NW + w) * 1024), voffB[((q - 4) / 2) & 3]); \
+            if (q == 0) {                                                                              \
+                /* the scalar work of the step's loads, behind its first MFMA */                       \
+                soffB_ = filt_soff(((TAP) + NSTG) % 9, s + (PAR) + ((TAP) + NSTG) / 9);                \
+                deadB_ = filt_dead(s + (PAR) + ((TAP) + NSTG) / 9);                                    \
+                if (halo_loads_in_step(TAP) > 0) { soffH0_ = halo_soff(2 * (TAP), s + (PAR) + 1); deadH0_ = halo_dead(2 * (TAP), s + (PAR) + 1); } \
+                if (halo_loads_in_step(TAP) > 1) { soffH1_ = halo_soff(2 * (TAP) + 1, s + (PAR) + 1); deadH1_ = halo_dead(2 * (TAP) + 1, s + (PAR) + 1); } \
+            }                                                                                          \
+            if (q == 2 && halo_loads_in_step(TAP) > 0)                                                 \
+                lds_dma16_at(rH, ldsBase + (unsigned)((((PAR) + 1) & 1) * G::HALO_BUF + 2 * (TAP) * HALO_ROW_BYTES + w * 1024), voffH | deadH0_, soffH0_); \
+            if (q == 4 && halo_loads_in_step(TAP) > 1)                                                 \
+                lds_dma16_at(rH, ldsBase + (unsigned)((((PAR) + 1) & 1) * G::HALO_BUF + (2 * (TAP) + 1) * HALO_ROW_BYTES + w * 1024), voffH | deadH1_, soffH1_); \
+            if (q % 2 == 0 && q >= 6 && q < 14)                                                        \
+                lds_dma16_at(rB, ldsBase + (unsigned)(G::B_BASE + (K_ % NSTG) * G::B_STAGE + (((q - 6) / 2) * NW + w) * 1024), voffB[((q - 6) / 2) & 3] | deadB_, soffB_); \
             if ((q & 1) && q < 2 * NREAD)                                                              \
                 GE_HALO_READ(q >> 1, ((TAP) + 1) % 9, (TAP) == 8 ? (((PAR) + 1) & 1) : (PAR), (K_ + 1) % NSTG, NX); \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(loads_in_last_four_steps(TAP)) : "memory"); \
+        wait_loads_and_lds<loads_in_last_four_steps(TAP)>();                                           \
+        asm volatile("s_barrier" ::: "memory");                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                             \
     }
 
     {
-        // the halo of slab 0, the filter stages of steps 0..5
-#pragma unroll
-        for (int j = 0; j < HALO_ROWS; ++j) lds_dma16(halo_rsrc(j, 0), ldsBase + (unsigned)(j * HALO_ROW_BYTES + w * 1024), voffH);
-#pragma unroll
-        for (int t = 0; t < NSTG; ++t) {
-            const rsrc_words_t rB = filt_rsrc(t, 0);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) lds_dma16(rB, ldsBase + (unsigned)(G::B_BASE + t * G::B_STAGE + (d * NW + w) * 1024), voffB[d]);
-        }
         // halo and step 0 landed -> its fragments; step 1 landed -> the loop
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(4 * (NSTG - 1)) : "memory");
 #pragma unroll
         for (int r = 0; r < NREAD; ++r) GE_HALO_READ(r, 0, 0, 0, 0);
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(4 * (NSTG - 2)) : "memory");
+        wait_loads_and_lds<4 * (NSTG - 2)>();
+        asm volatile("s_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         // one back edge, no exit from the middle (with more the register allocator spills the accumulators)
         for (int s = 0; s < nSlabs; s += 2) {

@@ -34,6 +34,19 @@
 
 namespace ge {
 
+// s_waitcnt vmcnt(N) lgkmcnt(0) as an instruction the compiler sees.  As inline assembly the wait is opaque
+// to the compiler's bookkeeping of LDS reads: it goes on believing that the fragment reads of the step
+// before are still on their way and guards the first MFMAs of every step with waits of its own ("at most
+// 3, 2, 1 LDS operations outstanding"), which by then count the reads just issued for the next step -- each
+// such wait stalls the one wave of the SIMD for a round trip to LDS, seven or eight times per step.
+template <int N>
+__device__ __forceinline__ void w4_wait_loads_and_lds()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    // vmcnt[3:0] | expcnt[6:4] = 7 (none) | lgkmcnt[11:8] = 0 | vmcnt[5:4] at [15:14]
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));
+}
+
 struct W4Tile {
     static constexpr int BM = 256, BN = 256, BK = 32, NW = 4, WTM = 128, WTN = 128, TM = 8, TN = 8;
     static constexpr int STAGE_BYTES = 256 * BK * 2;        // one operand, 32 k: 16 KB
@@ -240,7 +253,8 @@ gemm_bf16_w4_kernel(const GemmParams p)
             if ((q & 1) && q < 32) GE_W4_READ(q >> 1, ((S) + 1) & 3, NX);                              \
             __builtin_amdgcn_sched_barrier(0);                                                         \
         }                                                                                              \
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(((S) & 1) ? PAIR_LOADS + 2 * RING_LOADS : 2 * RING_LOADS) : "memory"); \
+        w4_wait_loads_and_lds<((S) & 1) ? PAIR_LOADS + 2 * RING_LOADS : 2 * RING_LOADS>();             \
+        asm volatile("s_barrier" ::: "memory");                                                        \
         __builtin_amdgcn_sched_barrier(0);                                                             \
     }
 
@@ -266,7 +280,8 @@ gemm_bf16_w4_kernel(const GemmParams p)
         asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(RING_LOADS > 0 ? 3 * RING_LOADS : PAIR_LOADS) : "memory");
 #pragma unroll
         for (int r = 0; r < 16; ++r) GE_W4_READ(r, 0, 0);
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(RING_LOADS > 0 ? 2 * RING_LOADS : PAIR_LOADS) : "memory");
+        w4_wait_loads_and_lds<(RING_LOADS > 0 ? 2 * RING_LOADS : PAIR_LOADS)>();
+        asm volatile("s_barrier" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
         // one back edge, no exit from the middle: with more the register allocator spills the accumulators
         for (int kt = 0; kt < nk; kt += 4) {

@@ -8,9 +8,8 @@
 #include <cstring>
 
 #include "../../include/gemm_epilogue.h"
-#include "gemm_bf16_fast.h"
-#include "gemm_bf16_w4.h"
 #include "gemm_fused.h"
+#include "gemm_fused_launch.h"
 #include "ge_host.h"
 
 namespace {
@@ -73,7 +72,6 @@ bool fast_ok(const ge_fused_args_t &a)
     return true;
 }
 
-// MODE: 0 = fp32 partial tiles (split-K), 1 = fused epilogue with fp32 output, 2 = with bf16 output
 // 64 k per load phase (see the kernel) where both operands' rows run along k: measured at 8192^3
 // with bf16 output, 0.85 -> 0.81 ms for that layout and 0.75 -> 0.81 ms for each of the other three,
 // whose k-strided operands are fetched in whole lines anyway and only lose the deeper ring.
@@ -84,69 +82,18 @@ bool stage_k64(bool transA, bool transB)
     return !transA && transB;
 }
 
-template <int BM, int BN, int WM, int WN, bool EDGE, int MODE, bool K64>
-void launch_layout(const GemmParams &p, dim3 grid, hipStream_t st)
-{
-    constexpr int threads = WM * WN * 64;
-    constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
-    if constexpr (K64) {        // only the layout stage_k64 names
-        GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H, false, true>), grid, dim3(threads), 0, st, p);
-    } else if (p.transA) {
-        if (p.transB) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(threads), 0, st, p);
-        else          GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, true, false, F, H>), grid, dim3(threads), 0, st, p);
-    } else {
-        if (p.transB) GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(threads), 0, st, p);
-        else          GE_LAUNCH((ge::gemm_bf16_kernel<BM, BN, WM, WN, EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(threads), 0, st, p);
-    }
-}
-
-template <int BM, int BN, int WM, int WN, bool K64>
-void launch_tile_k(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
-{
-    const int mode = raw ? 0 : p.cType == ge::DT_BF16 ? 2 : 1;
-    if (edge) {
-        if (mode == 0)      launch_layout<BM, BN, WM, WN, true, 0, K64>(p, grid, st);
-        else if (mode == 1) launch_layout<BM, BN, WM, WN, true, 1, K64>(p, grid, st);
-        else                launch_layout<BM, BN, WM, WN, true, 2, K64>(p, grid, st);
-    } else {
-        if (mode == 0)      launch_layout<BM, BN, WM, WN, false, 0, K64>(p, grid, st);
-        else if (mode == 1) launch_layout<BM, BN, WM, WN, false, 1, K64>(p, grid, st);
-        else                launch_layout<BM, BN, WM, WN, false, 2, K64>(p, grid, st);
-    }
-}
-
 // A 64-k stage needs the K range of every block to be a multiple of 64, or the edge variant.
-template <int BM, int BN, int WM, int WN>
+template <int BM>
 bool launch_tile(const GemmParams &p, bool edge, bool raw, dim3 grid, hipStream_t st)
 {
     // 128 x 128 blocks: only where more than one block shares a CU (measured with both operands along
     // k, bf16 out: 4096x2048x2048, 512 blocks, 33 us with 64 k per load phase against 44 us with 32;
     // 2048^3, 256 blocks, 27 against 22 us; 2048x2048x8192 81 against 66 us)
     const bool k64 = stage_k64(p.transA != 0, p.transB != 0) && (BM == 256 || grid.x > (unsigned)kNumCU);
-    if (k64) launch_tile_k<BM, BN, WM, WN, true>(p, edge || (p.K % 64) || (p.kPerSlice % 64), raw, grid, st);
-    else     launch_tile_k<BM, BN, WM, WN, false>(p, edge, raw, grid, st);
+    if (k64) edge = edge || (p.K % 64) || (p.kPerSlice % 64);
+    if (BM == 256) { if (edge) fused_tile_256_edge(p, k64, raw, grid, st); else fused_tile_256_full(p, k64, raw, grid, st); }
+    else           { if (edge) fused_tile_128_edge(p, k64, raw, grid, st); else fused_tile_128_full(p, k64, raw, grid, st); }
     return k64;
-}
-
-// the four-wave kernel, by edge handling, output mode and operand storage
-template <int EDGE, int MODE>
-void launch_four_wave_layout(const GemmParams &p, dim3 grid, hipStream_t st)
-{
-    constexpr bool R = MODE == 0, F = MODE != 0, H = MODE == 2;
-    if (p.transA) {         // with B along k; the caller keeps the other storage of B on the eight-wave kernel
-        GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, true, true, F, H>), grid, dim3(256), 0, st, p);
-    } else {
-        if (p.transB) GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, true, F, H>), grid, dim3(256), 0, st, p);
-        else          GE_LAUNCH((ge::gemm_bf16_w4_kernel<EDGE, R, ge::ACT_NONE, false, false, F, H>), grid, dim3(256), 0, st, p);
-    }
-}
-
-template <int EDGE>
-void launch_four_wave(const GemmParams &p, bool raw, dim3 grid, hipStream_t st)
-{
-    if (raw) launch_four_wave_layout<EDGE, 0>(p, grid, st);
-    else if (p.cType == ge::DT_BF16) launch_four_wave_layout<EDGE, 2>(p, grid, st);
-    else launch_four_wave_layout<EDGE, 1>(p, grid, st);
 }
 
 }  // namespace
@@ -244,15 +191,15 @@ extern "C" ge_status_t gemm_epilogue_bf16_fused(const ge_fused_args_t *args, voi
         // kernel has nothing to gain (measured at 8192^3: 0.812 against 0.806 ms)
         if (four_wave_ok(pl, a.K) && !(a.transA && !a.transB)) {
             const int mode = four_wave_edge(pl, a.K);
-            if (mode == 2) launch_four_wave<2>(pg, raw, grid, hs);
-            else if (mode == 1) launch_four_wave<1>(pg, raw, grid, hs);
-            else launch_four_wave<0>(pg, raw, grid, hs);
+            if (mode == 2) fused_four_wave_e2(pg, raw, grid, hs);
+            else if (mode == 1) fused_four_wave_e1(pg, raw, grid, hs);
+            else fused_four_wave_e0(pg, raw, grid, hs);
             set_config("256x256x64_w4", a.transA, a.transB, raw);
-        } else if (launch_tile<256, 256, 2, 4>(pg, pl.edge, raw, grid, hs)) set_config("256x256x64_w8", a.transA, a.transB, raw);
+        } else if (launch_tile<256>(pg, pl.edge, raw, grid, hs)) set_config("256x256x64_w8", a.transA, a.transB, raw);
         else set_config("256x256x32_w8", a.transA, a.transB, raw);
         break;
     case TILE_128:
-        if (launch_tile<128, 128, 2, 2>(pg, pl.edge, raw, grid, hs)) set_config("128x128x64_w4", a.transA, a.transB, raw);
+        if (launch_tile<128>(pg, pl.edge, raw, grid, hs)) set_config("128x128x64_w4", a.transA, a.transB, raw);
         else set_config("128x128x32_w4", a.transA, a.transB, raw);
         break;
     default:
