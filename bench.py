@@ -70,19 +70,19 @@ _F32 = ("bf16_layout.h", "ge_device.h", "gemm_f32_fast.h")
 # TRAFFIC-BEGIN (rows written from the counter runs; see profiles/)
 TRAFFIC = {
     "c1_f32_256": ("f32_small_32x32_k4", 1234, 256, ('ge_device.h', 'gemm_f32_small.h'), "dd9f995f0f263ca2"),
-    "c2_bf16_4096": ("bf16_256x256x64_w4", 98449, 65536, _MAIN_W4, "a1c9de43249d36a2"),
-    "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 805474, 262264, _MAIN_W4, "a1c9de43249d36a2"),
-    "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16475, 262166, _MAIN_W8, "11559b595be739d6"),
-    "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", 131341, 65536, _MAIN_W4, "a1c9de43249d36a2"),
-    "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", 796059, 131170, _MAIN_W4, "a1c9de43249d36a2"),
-    "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 852631, 131072, _MAIN_W8, "11559b595be739d6"),
+    "c2_bf16_4096": ("bf16_256x256x64_w4", 98449, 65536, _MAIN_W4, "77d32919b66e1af9"),
+    "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 794440, 262266, _MAIN_W4, "77d32919b66e1af9"),
+    "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16474, 262170, _MAIN_W8, "11559b595be739d6"),
+    "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", 131331, 65536, _MAIN_W4, "77d32919b66e1af9"),
+    "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", 798487, 131296, _MAIN_W4, "77d32919b66e1af9"),
+    "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 852630, 131072, _MAIN_W8, "11559b595be739d6"),
     "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", 16543, 131072, _MAIN_W8, "11559b595be739d6"),
-    "c9_diag_bf16_8192": ("diag_rows_vec4", 65968, 262602, ('gemm_diag.hip',), "95489dc912964713"),
-    "c10_conv3x3_256_bf16out": ("conv_bf16_halo_3x3_w4_14_11", 60909, 50176, ('bf16_layout.h', 'conv_halo.h', 'conv_halo_launch.h', 'conv_halo_layout.h', 'ge_device.h', 'gemm_bf16_fast.h'), "2c897a6ab3fc04ab"),
-    "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 662342, 262144, _MAIN_W4, "a1c9de43249d36a2"),
-    "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133354, 4390, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
-    "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 783991, 262144, _F32, "5d6b4cbd7727a6ca"),
-    "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16594, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "1974a3533a0d699a"),
+    "c9_diag_bf16_8192": ("diag_rows_vec4", 65965, 262563, ('gemm_diag.hip',), "95489dc912964713"),
+    "c10_conv3x3_256_bf16out": ("conv_bf16_halo_3x3_w4_14_11", 60908, 50176, ('bf16_layout.h', 'conv_halo.h', 'conv_halo_launch.h', 'conv_halo_layout.h', 'ge_device.h', 'gemm_bf16_fast.h'), "f5bd91f43a5342f2"),
+    "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 655867, 262144, _MAIN_W4, "77d32919b66e1af9"),
+    "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133354, 4367, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
+    "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 783993, 262144, _F32, "5d6b4cbd7727a6ca"),
+    "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16593, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "1974a3533a0d699a"),
     "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146151, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "fe59d5571589f9aa"),
 }
 # TRAFFIC-END

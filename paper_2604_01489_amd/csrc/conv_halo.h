@@ -12,10 +12,9 @@
 // Four waves, one per SIMD, each owning all rows of the tile and 64 of its 256 output channels
 // (accumulators in the accumulation registers, fragments of step t + 1 read during the MFMAs of step t,
 // loads and fragment reads issued between the MFMAs, one wait and one barrier per step: the schedule of
-// gemm_bf16_w4.h).  The filters go through a ring of six stages of 16 KB, fetched six steps ahead (with three
-// stages and two steps of slack a step took 0.8-0.9 us whatever its MFMA count: the latency of the filter
-// loads, not the matrix pipes, set the pace), the halo through two buffers: the seven rows of slab s + 1 are
-// fetched during steps 0..3 of slab s and have landed by the end of step 7.  152 KB of LDS in all.
+// gemm_bf16_w4.h).  The filters go through a ring of six stages of 16 KB, fetched six steps ahead (a ring of
+// three measured the same: the loads are not late), the halo through two buffers: the seven rows of slab
+// s + 1 are fetched during steps 0..3 of slab s and have landed by the end of step 7.  152 KB of LDS in all.
 //
 // Tiles of two heights share a launch (conv_halo_layout.h: the plan): TMB1 and TMB2 are the row blocks
 // of 16 positions that the MFMA loop of either kind covers; positions beyond R * OW are multiplied
@@ -52,9 +51,9 @@ static_assert(ge_halo::HALO_ROWS == 7, "the halo loads of steps 0..3 cover seven
 
 // s_waitcnt vmcnt(N) lgkmcnt(0) as an instruction the compiler sees.  Written as inline assembly, the wait
 // is opaque to the compiler's own bookkeeping of LDS reads: it goes on believing that the fragment reads of
-// the step before are still on their way and guards the first MFMAs of a step with waits of its own --
-// "at most 3, 2, 1 LDS operations outstanding" -- which by then count the reads just issued for the next
-// step, so each such wait stalls the wave for a round trip to LDS (four per step: 0.18 us of a 0.63 us step).
+// the step before are still on their way and guards the first MFMAs of a step with waits of its own ("at
+// most 3, 2, 1 LDS operations outstanding").  Those waits are satisfied when they are reached (the counter is
+// already below their bound), so this buys instructions, not time: 88 -> 17 waits per 18 steps.
 template <int N>
 __device__ __forceinline__ void wait_loads_and_lds()
 {
