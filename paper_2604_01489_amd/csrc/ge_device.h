@@ -137,13 +137,39 @@ __device__ inline TileCoord map_block(const GemmParams &p)
 // gelu_tanh(v) = 0.5 v (1 + tanh u) with u = sqrt(2/pi) (v + 0.044715 v^3).
 // Since 0.5 (1 + tanh u) = 1 / (1 + exp(-2u)) this is v / (1 + exp(-2u)): one
 // exponential and one division, finite for every finite v (exp overflow gives
-// v / inf = -0 for very negative v).
+// v / inf = -0 for very negative v).  Written on the hardware's base-2 exponential with the
+// constants folded, -2u log2(e) = v (K0 + K1 v^2): seven vector instructions a value (the
+// epilogue of a tile is a single wave per SIMD issuing them one after the other).
 __device__ inline float gelu_tanh_f32(float v)
 {
-    const float c2 = 2.0f * 0.7978845608028654f;
-    float u2 = c2 * (v + 0.044715f * v * v * v);
-    // hardware reciprocal (1 ulp) instead of an IEEE division: 1 + exp(-2u) >= 1, or +inf -> 0
-    return v * __builtin_amdgcn_rcpf(1.0f + __expf(-u2));
+    constexpr float K0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f, K1 = K0 * 0.044715f;
+    const float p = __builtin_fmaf(v * v, K1, K0);
+    // hardware reciprocal (1 ulp) instead of an IEEE division: 1 + 2^x >= 1, or +inf -> 0
+    return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * p));
+}
+
+// The same for N values, stage by stage: the hardware wants a wait state between a transcendental
+// instruction and the use of its result, and one wave per SIMD has nobody else to fill it; with the N
+// chains advancing together each stage's instructions follow one another and no wait state is left.
+template <int N>
+__device__ __forceinline__ void gelu_tanh_f32_n(float (&v)[N])
+{
+    constexpr float K0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f, K1 = K0 * 0.044715f;
+    float x[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = v[i] * v[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = __builtin_fmaf(x[i], K1, K0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = v[i] * x[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = __builtin_amdgcn_exp2f(x[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = 1.0f + x[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) x[i] = __builtin_amdgcn_rcpf(x[i]);
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = v[i] * x[i];
 }
 
 // scale -> bias -> activation, fp32, in registers.
@@ -154,6 +180,20 @@ __device__ inline float epilogue_value(float acc, float alpha, float bias)
     if (ACT == ACT_RELU) return v > 0.0f ? v : 0.0f;
     if (ACT == ACT_GELU_TANH) return gelu_tanh_f32(v);
     return v;
+}
+
+// scale -> bias -> activation for the N values of one row piece (acc in, result out)
+template <int ACT, int N>
+__device__ __forceinline__ void epilogue_values(float (&v)[N], float alpha, const float (&bias)[N])
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = alpha * v[i] + bias[i];
+    if (ACT == ACT_RELU) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = v[i] > 0.0f ? v[i] : 0.0f;
+    } else if (ACT == ACT_GELU_TANH) {
+        gelu_tanh_f32_n<N>(v);
+    }
 }
 
 __device__ inline float epilogue_value_rt(float acc, float alpha, float bias, int act)
@@ -246,10 +286,16 @@ __device__ __forceinline__ void act_clamp_row_block(const GemmParams &p, f32x4_t
     if constexpr (MODE == CHAIN_LINEAR) {
         return;
     } else if constexpr (MODE == CHAIN_GELU) {
+        float t[TN * 4];
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = gelu_tanh_f32(v[j][r]);
+            for (int r = 0; r < 4; ++r) t[j * 4 + r] = v[j][r];
+        gelu_tanh_f32_n<TN * 4>(t);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = t[j * 4 + r];
         return;
     } else if constexpr (MODE == CHAIN_RELU) {
         float lo = p.clampLo, hi = p.clampHi;

@@ -341,12 +341,14 @@ gemm_bf16_w4_kernel(const GemmParams p)
                 for (int r = 0; r < 4; ++r) {
                     const int m = rowLane + i * 16 + r;
                     float *rowPtr = cBase + (long long)m * ldc + colLane;
+                    // the row's values first, stage by stage over the column blocks, then its stores
+                    float v[TN];
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        float v = acc[i][j][r];
-                        if (!RAW) v = epilogue_value<ACT>(v, p.alpha, bv[j]);
-                        if (!MASK || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v;
-                    }
+                    for (int j = 0; j < TN; ++j) v[j] = acc[i][j][r];
+                    if (!RAW) epilogue_values<ACT, TN>(v, p.alpha, bv);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        if (!MASK || (m < p.M && colLane + j * 16 < p.N)) rowPtr[j * 16] = v[j];
                 }
         };
         if (!EDGE || (m0 + BM <= p.M && n0 + BN <= p.N)) store_tile(std::false_type{});
