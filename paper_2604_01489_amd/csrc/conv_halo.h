@@ -269,8 +269,10 @@ __device__ __forceinline__ void conv_halo_tile(const GemmParams &p, GE_LDS char 
     GemmParams q = p;
     q.M = m0 + rowsValid;
     if constexpr (OUTBF16) {
+        // a bf16 residual goes into the LDS image of the tile first (gemm_bf16_fast.h: stage_residual_bf16)
+        const bool resInLds = stage_residual_bf16<TMB * 16, 256, NW>(p, 0, smem, m0, n0, m0 + rowsValid, waveE, laneE);
         fused_epilogue_bf16_through_lds<TMB * 16, 256, NW, LDS_BYTES, TMB, TN, true>(
-            q, 0, acc, smem, m0, n0, laneE & 15, waveE * 64 + 4 * (laneE >> 4), waveE, laneE);
+            q, 0, acc, smem, m0, n0, laneE & 15, waveE * 64 + 4 * (laneE >> 4), waveE, laneE, resInLds);
     } else {
         const int rowLane = m0 + 4 * (laneE >> 4), colLane = n0 + waveE * 64 + (laneE & 15);
         if (rowsValid == TMB * 16) fused_epilogue_f32_direct<TMB, TN, false>(q, 0, acc, rowLane, colLane);

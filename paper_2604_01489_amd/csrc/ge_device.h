@@ -243,7 +243,8 @@ __device__ inline unsigned pack_bf16_pair(float lo, float hi)
 // i + 1 (row scale, residual) can be issued ahead of the arithmetic of row block i: with a fetch
 // right before each use, a tile pays one round trip to L2 or HBM per row block, which a short-K
 // (store-bound) shape notices and a residual doubles.
-enum { RES_NONE = 0, RES_BF16 = 1, RES_F32 = 2, RES_BF16_SCALAR = 3, RES_F32_SCALAR = 4 };
+enum { RES_NONE = 0, RES_BF16 = 1, RES_F32 = 2, RES_BF16_SCALAR = 3, RES_F32_SCALAR = 4,
+       RES_BF16_LDS = 5 };   // the caller has staged the tile's bf16 residual in the LDS image, where the results are parked
 
 __device__ inline float bf16_bits_as_f32(unsigned bits16) { return __uint_as_float(bits16 << 16); }
 
@@ -441,17 +442,29 @@ __device__ __forceinline__ void chain_and_park_t(const GemmParams &p, int b, f32
     // bf16 pieces are two registers per column block: all of them are fetched up front where that takes at
     // most 128 registers (the fragments' registers are free by now), so that a tile pays one round trip.
     constexpr int PF = RES == RES_BF16 ? (TM * TN * 2 <= 128 ? TM + 1 : 4) : 2;
+    // RES_BF16_LDS: the residual's pieces are read from the image (each by the lane that parks its result
+    // there); memory is asked for the row scale only
+    constexpr int RESF = RES == RES_BF16_LDS ? RES_NONE : RES, RESA = RES == RES_BF16_LDS ? RES_BF16 : RES;
     float rs[PF];
     unsigned raw[PF][TN][4];
 #pragma unroll
     for (int d = 0; d < PF - 1; ++d)
-        if (d < TM) fetch_row_block_t<RES, TN, EDGE>(p, b, m0 + tileRow + d * 16, colLane, rs[d], raw[d]);
+        if (d < TM) fetch_row_block_t<RESF, TN, EDGE>(p, b, m0 + tileRow + d * 16, colLane, rs[d], raw[d]);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row = tileRow + i * 16;
         if (i + PF - 1 < TM)
-            fetch_row_block_t<RES, TN, EDGE>(p, b, m0 + row + (PF - 1) * 16, colLane, rs[(i + PF - 1) % PF], raw[(i + PF - 1) % PF]);
-        apply_row_block_t<RES, TN, EDGE, MODE>(p, b, acc[i], bv, rs[i % PF], raw[i % PF], m0 + row, colLane);
+            fetch_row_block_t<RESF, TN, EDGE>(p, b, m0 + row + (PF - 1) * 16, colLane, rs[(i + PF - 1) % PF], raw[(i + PF - 1) % PF]);
+        if constexpr (RES == RES_BF16_LDS) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int cb = (tileCol + j * 16) * 2;
+                const u32x2_t t = *(const GE_LDS u32x2_t *)(lds + row * PITCH + (((cb >> 4) ^ (row & (CHUNKS - 1))) << 4) + (cb & 15));
+                raw[i % PF][j][0] = t[0];
+                raw[i % PF][j][1] = t[1];
+            }
+        }
+        apply_row_block_t<RESA, TN, EDGE, MODE>(p, b, acc[i], bv, rs[i % PF], raw[i % PF], m0 + row, colLane);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int cb = (tileCol + j * 16) * 2;
@@ -473,6 +486,8 @@ __device__ __forceinline__ void chain_and_park_t(const GemmParams &p, int b, f32
 // whole rows to C with 16 bytes per lane.  Each row block runs the whole chain and is parked
 // before the next one starts.  C must be able to take 16-byte row pieces (the host checks).
 // `lds` must hold BM*BN*2 bytes nobody reads any more; all NW waves of the block call this.
+// resInLds: the caller has copied the tile's bf16 residual into the image (same rows, same chunk swizzle) and
+// waited for its own copies; the barrier below makes them visible, and each lane reads the pieces it replaces.
 // (tileRow, tileCol): row of this lane and first of its 4 columns in block (0, 0) of the wave
 // tile, relative to the block tile.
 // NT: the row pieces leave with the non-temporal hint (C is not read back).  Measured at 8192^3 on the
@@ -480,7 +495,8 @@ __device__ __forceinline__ void chain_and_park_t(const GemmParams &p, int b, f32
 // with A stored K x M) or a loss (3 x 3 convolution, 0.132 -> 0.135 ms), so only the former asks for it.
 template <int BM, int BN, int NW, int LDS_BYTES, int TM, int TN, bool EDGE, bool NT = false>
 __device__ __forceinline__ void fused_epilogue_bf16_through_lds(const GemmParams &p, int b, f32x4_t (&acc)[TM][TN], GE_LDS char *lds,
-                                                       int m0, int n0, int tileRow, int tileCol, int w, int lane)
+                                                       int m0, int n0, int tileRow, int tileCol, int w, int lane,
+                                                       bool resInLds = false)
 {
     constexpr int PITCH = BN * 2, CHUNKS = PITCH / 16, ROWS_PER_INSTR = 1024 / PITCH;
     static_assert(BM * PITCH <= LDS_BYTES, "bf16 image of the tile fits the stages");
@@ -499,6 +515,7 @@ __device__ __forceinline__ void fused_epilogue_bf16_through_lds(const GemmParams
     } while (0)
     const int mode = chain_mode(p);
     if (p.R == nullptr) GE_PARK_BY_MODE(RES_NONE);
+    else if (resInLds) GE_PARK_BY_MODE(RES_BF16_LDS);
     else if (p.rVec && p.rType == DT_BF16) GE_PARK_BY_MODE(RES_BF16);
     else if (p.rVec) GE_PARK_BY_MODE(RES_F32);
     else if (p.rType == DT_BF16) GE_PARK(RES_BF16_SCALAR, CHAIN_ANY);

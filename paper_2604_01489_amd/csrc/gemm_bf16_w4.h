@@ -310,9 +310,10 @@ gemm_bf16_w4_kernel(const GemmParams p)
     const int colLane = n0 + (waveE % 2) * T::WTN + (laneE & 15);
     if constexpr (FUSED) {
         if constexpr (OUTBF16) {
+            const bool resInLds = stage_residual_bf16<BM, BN, NW>(p, tc.b, (GE_LDS char *)smem, m0, n0, p.M, waveE, laneE);
             fused_epilogue_bf16_through_lds<BM, BN, NW, T::LDS_BYTES, TM, TN, EDGE, true>(
                 p, tc.b, acc, (GE_LDS char *)smem, m0, n0, (waveE / 2) * T::WTM + (laneE & 15),
-                (waveE % 2) * T::WTN + 4 * (laneE >> 4), waveE, laneE);
+                (waveE % 2) * T::WTN + 4 * (laneE >> 4), waveE, laneE, resInLds);
         } else {
             // only the tiles that hang over M or N pay for masked stores (a uniform branch; masked, the
             // stores of an 8192^3-sized launch cost 10 % of its run)
