@@ -71,19 +71,19 @@ _F32 = ("bf16_layout.h", "ge_device.h", "gemm_f32_fast.h")
 TRAFFIC = {
     "c1_f32_256": ("f32_small_32x32_k4", 1234, 256, ('ge_device.h', 'gemm_f32_small.h'), "1637c34d4b8c3bd3"),
     "c2_bf16_4096": ("bf16_256x256x64_w4", 98449, 65536, _MAIN_W4, "f4cba42cb2332e07"),
-    "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 799789, 262148, _MAIN_W4, "f4cba42cb2332e07"),
-    "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16480, 262166, _MAIN_W8, "82ded2225dc3e4ae"),
-    "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", 131389, 65536, _MAIN_W4, "f4cba42cb2332e07"),
-    "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", 796805, 131201, _MAIN_W4, "f4cba42cb2332e07"),
-    "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 855662, 131072, _MAIN_W8, "82ded2225dc3e4ae"),
-    "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", 16542, 131072, _MAIN_W8, "82ded2225dc3e4ae"),
-    "c9_diag_bf16_8192": ("diag_rows_vec4", 65971, 262621, ('gemm_diag.hip',), "95489dc912964713"),
-    "c10_conv3x3_256_bf16out": ("conv_bf16_halo_3x3_w4_14_11", 60944, 50176, ('bf16_layout.h', 'conv_halo.h', 'conv_halo_launch.h', 'conv_halo_layout.h', 'ge_device.h', 'gemm_bf16_fast.h'), "f685fd9175249a3d"),
-    "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 660893, 262144, _MAIN_W4, "f4cba42cb2332e07"),
+    "c3_bf16_8192_bias_gelu": ("bf16_256x256x64_w4", 799742, 262147, _MAIN_W4, "f4cba42cb2332e07"),
+    "c4_bf16_batched_512x512x64": ("bf16_256x256x32_w8", 16479, 262157, _MAIN_W8, "eee542088afa5b72"),
+    "c5_bf16_splitk_1024x1024x65536": ("bf16_256x256x64_w4_splitk", 131500, 65536, _MAIN_W4, "f4cba42cb2332e07"),
+    "c6_fused_nt_8192_bias_gelu_bf16out": ("bf16_fused_256x256x64_w4_nt", 792367, 131149, _MAIN_W4, "f4cba42cb2332e07"),
+    "c7_fused_tn_8192_chain": ("bf16_fused_256x256x32_w8_tn", 860439, 131072, _MAIN_W8, "eee542088afa5b72"),
+    "c8_fused_batched_512x512x64_bf16out": ("bf16_fused_256x256x32_w8_nn", 16542, 131072, _MAIN_W8, "eee542088afa5b72"),
+    "c9_diag_bf16_8192": ("diag_rows_vec4", 65970, 262594, ('gemm_diag.hip',), "95489dc912964713"),
+    "c10_conv3x3_256_bf16out": ("conv_bf16_halo_3x3_w4_14_11", 60945, 50176, ('bf16_layout.h', 'conv_halo.h', 'conv_halo_launch.h', 'conv_halo_layout.h', 'ge_device.h', 'gemm_bf16_fast.h'), "8ba5a9b1fd08f19c"),
+    "c11_fused_lower_8192_bias_relu": ("bf16_fused_256x256x64_w4_nn", 670998, 262144, _MAIN_W4, "f4cba42cb2332e07"),
     "c12_rowsum_linear_8192": ("rowsum_rows_wide", 133354, 4374, ('gemm_rowsum.hip',), "ccd59ba6279a089a"),
     "c13_f32_8192x8192x2048": ("f32_128x128x16_w4", 783979, 262144, _F32, "994f5e7506b6a876"),
     "c15_conv7x7_first_layer_bf16out": ("conv_bf16_rows_k32", 16594, 50176, ('conv_rows.h', 'conv_rows_layout.h', 'ge_device.h'), "92d0096482844c2c"),
-    "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146153, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "a15e2616694f0443"),
+    "c14_symm_lower_16384_n16": ("bf16_symm_lower_768x768_n16", 146167, 23552, ('ge_device.h', 'gemm_fused.h', 'gemm_symm.h', 'symm_layout.h'), "a15e2616694f0443"),
 }
 # TRAFFIC-END
 

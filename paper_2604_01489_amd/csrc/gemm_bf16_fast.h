@@ -94,7 +94,9 @@ __device__ __forceinline__ bool stage_residual_bf16(const GemmParams &p, int b, 
 {
     constexpr int PITCH = BN * 2, CHUNKS = PITCH / 16, ROWS_PER_INSTR = 1024 / PITCH;
     static_assert((BM / ROWS_PER_INSTR) % NW == 0, "the image's kilobytes divide over the waves");
-    const bool take = p.R != nullptr && p.rVec && p.rType == DT_BF16 && (long long)BM * p.ldr * 2 < (1ll << 31);
+    // (rVec: R is 16-byte aligned and its rows are multiples of 16 bytes; a batch's first row must be as well)
+    const bool take = p.R != nullptr && p.rVec && p.rType == DT_BF16 && (long long)BM * p.ldr * 2 < (1ll << 31) &&
+                      (((long long)b * p.strideR) & 7) == 0;
     if (!take) return false;
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");      // every wave is done with the stages
     const rsrc_words_t rR = make_rsrc((const char *)p.R + ((long long)b * p.strideR + (long long)m0 * p.ldr + n0) * 2, RSRC_RECORDS);
